@@ -1,0 +1,176 @@
+/*
+ * spindle.h - C ABI of the MI355X (gfx950) prefill-time KV-cache reduction pass
+ * of SpindleKV (arXiv 2507.06517).
+ *
+ * Two operations, each working on `batch * n_kv_heads` independent problems
+ * ("units") per call; fold layers into `batch` to process a stack in one call:
+ *
+ *   spindle_compress_deep     attention-weight token eviction
+ *                             (Sec. "Attention Weight Based Token Eviction", Eq. 1-3, 7)
+ *   spindle_compress_shallow  similarity codebook replacement
+ *                             (Sec. "Similarity Based Token Replacement", Eq. 8-13, Alg. 1)
+ *   spindle_reconstruct       codebook look-up and rescale (Eq. 14)
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, contiguous in
+ *     the stated shape, 16-byte aligned.  The library allocates no device memory
+ *     and keeps no state between calls; scratch space is the caller's `workspace`
+ *     (size from the *_workspace_bytes query, 256-byte aligned).
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue
+ *     work on it and return without synchronising; all data-dependent counts stay
+ *     on the device.
+ *   - K, V, Qw and the vector outputs share `dtype`.  head_dim must be 128.
+ *   - Inputs are assumed finite; NaN/Inf give undefined selections.
+ *   - Return value: SPINDLE_OK or an error code; spindle_last_error() gives a
+ *     thread-local message for the last failing call.  Nothing is enqueued when a
+ *     call fails validation.
+ *   - Two calls that share a workspace must be ordered on one stream.
+ */
+#ifndef SPINDLE_H
+#define SPINDLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPINDLE_OK = 0,
+  SPINDLE_ERR_INVALID_ARG = 1,  /* null pointer, bad shape, bad parameter            */
+  SPINDLE_ERR_UNSUPPORTED = 2,  /* valid but outside what the kernels handle         */
+  SPINDLE_ERR_WORKSPACE = 3,    /* workspace missing, misaligned or too small        */
+  SPINDLE_ERR_HIP = 4           /* a HIP runtime call failed (message has the cause) */
+} spindle_status;
+
+typedef enum { SPINDLE_F32 = 0, SPINDLE_F16 = 1, SPINDLE_BF16 = 2 } spindle_dtype;
+
+/* Divisor of the accumulated attention score, Eq. 2. */
+typedef enum {
+  SPINDLE_NORM_PAPER = 0, /* divide the window sum of key a by (l - a), as printed */
+  SPINDLE_NORM_NONE = 1   /* plain window sum                                      */
+} spindle_norm;
+
+/* Shape of the KV cache of one call: K, V are [batch, n_kv_heads, seq_len, head_dim]. */
+typedef struct {
+  int32_t batch;      /* B   >= 1                                                  */
+  int32_t n_kv_heads; /* h_g >= 1                                                  */
+  int32_t group_size; /* h_n = query heads per KV head (used by the deep path)     */
+  int32_t seq_len;    /* l   >= 1                                                  */
+  int32_t head_dim;   /* d_h, must be 128                                          */
+  int32_t dtype;      /* spindle_dtype                                             */
+} spindle_kv_desc;
+
+/* ------------------------------------------------------------------------- */
+/* Deep layers: attention-weight eviction                                     */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Bytes of workspace spindle_compress_deep needs for this shape and window.
+ */
+spindle_status spindle_deep_workspace_bytes(const spindle_kv_desc *desc, int32_t window,
+                                            size_t *bytes);
+
+/*
+ * For every unit (b, i):
+ *   1. logits of the `window` last queries of the h_n query heads of KV head i
+ *      against all keys, causal mask, softmax over the visible keys (Eq. 1);
+ *   2. per context key a < l_c = seq_len - window: sum over the window queries,
+ *      divided by (l - a) under SPINDLE_NORM_PAPER (Eq. 2), mean over the h_n
+ *      heads of the group (Eq. 3);
+ *   3. 1-D max pooling over context positions, odd kernel `pool_kernel`, stride 1,
+ *      same length, neighbours outside the context ignored (1 = no pooling);
+ *   4. the k = budget - window largest pooled scores, equal scores lowest position
+ *      first (Eq. 7); kept positions in ascending order followed by the whole
+ *      window l_c .. l-1 (the observation window is always kept);
+ *   5. K_out = K[kept], V_out = V[kept].
+ *
+ *   Qw          [B, h_g*h_n, window, d]; query head h serves KV head h / h_n, row w is
+ *               the query at position l - window + w.  window*h_n <= 256.
+ *   scale       logit scale, normally 1/sqrt(d).
+ *   budget      total kept tokens per unit, window included; window <= budget.
+ *               budget >= seq_len keeps everything.
+ *   budgets     optional device int32 [B*h_g] per-unit budgets overriding `budget`
+ *               (each window <= budgets[u]); NULL = uniform.
+ *   out_stride  row pitch of the outputs in tokens, >= the largest budget in use
+ *               (clamped to seq_len).
+ *   kept_idx    [B, h_g, out_stride] int32; entries past a unit's budget are -1.
+ *   K_out,V_out [B, h_g, out_stride, d]; rows past a unit's budget are zero.
+ *               V and V_out may both be NULL (keys only).
+ *   scores_out  optional [B, h_g, l_c] float32 pooled scores (step 3), else NULL.
+ */
+spindle_status spindle_compress_deep(const spindle_kv_desc *desc, const void *K, const void *V,
+                                     const void *Qw, int32_t window, int32_t pool_kernel,
+                                     float scale, int32_t norm, int32_t budget,
+                                     const int32_t *budgets, int32_t out_stride,
+                                     int32_t *kept_idx, void *K_out, void *V_out,
+                                     float *scores_out, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Shallow layers: similarity codebook                                        */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Bytes of workspace spindle_compress_shallow needs when `n_tensors` (1 or 2) of
+ * K, V are processed in one call.  Dominated by the bit-packed adjacency matrix:
+ * seq_len^2 / 8 bytes per unit and tensor.
+ */
+spindle_status spindle_shallow_workspace_bytes(const spindle_kv_desc *desc, int32_t n_tensors,
+                                               size_t *bytes);
+
+/*
+ * Alg. 1 for every unit, independently for K (threshold theta_k) and V (theta_v):
+ *   m_a = |x_a| (Eq. 8); S_ab = x_a.x_b / (m_a m_b) (Eq. 4; 0 if either norm is 0);
+ *   G_ab = [S_ab > theta], G_aa = 1 (Eq. 9); then repeatedly pick the token of highest
+ *   degree among the remaining ones (lowest index on ties), append its unit vector to
+ *   the codebook, point every remaining neighbour (itself included) to that entry and
+ *   remove them (Eq. 10-13), until no token remains.
+ * The adjacency decision S_ab > theta is taken exactly as a double-precision
+ * evaluation (dimension-order summation) would take it.
+ * Codebook cap: only the first `max_codes` entries in pick order are stored; a token
+ * whose entry was cut is pointed to the stored entry of highest cosine similarity
+ * (lowest entry index on ties).  max_codes >= seq_len never cuts.
+ *
+ *   K, V        either may be NULL (with all of its outputs) to process one tensor.
+ *   Ck, Cv      [B, h_g, max_codes, d] unit vectors in `dtype`; rows >= n_codes are zero.
+ *   n_codes_*   [B, h_g] int32 stored entries = min(found, max_codes).
+ *   n_found_*   optional [B, h_g] int32 entries found before the cap, else NULL.
+ *   ref_*       [B, h_g, l] int32 code index of each token, in [0, n_codes).
+ *   mag_*       [B, h_g, l] float32 magnitudes m_a.
+ *   adj_*       optional [B, h_g, l, ceil(l/32)] uint32 adjacency bits (bit b of row a at
+ *               word b/32, position b%32), else NULL.
+ *   deg_*       optional [B, h_g, l] int32 degrees (row sums of G), else NULL.
+ * seq_len <= 65535.
+ */
+spindle_status spindle_compress_shallow(const spindle_kv_desc *desc, const void *K, const void *V,
+                                        float theta_k, float theta_v, int32_t max_codes,
+                                        void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v,
+                                        int32_t *n_found_k, int32_t *n_found_v,
+                                        int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v,
+                                        uint32_t *adj_k, uint32_t *adj_v,
+                                        int32_t *deg_k, int32_t *deg_v,
+                                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Eq. 14: out[u, a, :] = C[u, ref[u, a], :] * mag[u, a] for all units u and tokens a.
+ *   C [units, max_codes, d] and out [units, l, d] in `dtype`; ref [units, l] int32;
+ *   mag [units, l] float32.  No workspace.
+ */
+spindle_status spindle_reconstruct(int32_t units, int32_t seq_len, int32_t head_dim, int32_t dtype,
+                                   int32_t max_codes, const void *C, const int32_t *ref,
+                                   const float *mag, void *out, void *stream);
+
+/* ------------------------------------------------------------------------- */
+
+/* Thread-local message of the last failing call on this thread ("" if none). */
+const char *spindle_last_error(void);
+
+/* Library version, major << 16 | minor. */
+uint32_t spindle_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPINDLE_H */

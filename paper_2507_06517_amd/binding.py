@@ -1,0 +1,247 @@
+"""Thin ctypes binding of the C ABI in ``include/spindle.h``.
+
+Argument marshalling only: every step of both paths runs in the HIP kernels of
+``libspindle.so``.  PyTorch supplies device memory and the current HIP stream.
+The raw entry points keep their C names (``spindle_compress_deep`` ...); the
+``compress_deep`` / ``compress_shallow`` / ``reconstruct`` helpers allocate the
+outputs and the workspace and call them.  There is no fallback: a missing
+library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libspindle.so")
+
+F32, F16, BF16 = 0, 1, 2
+NORM_PAPER, NORM_NONE = 0, 1
+_DT = {"f32": F32, "f16": F16, "bf16": BF16}
+
+EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
+           "spindle_compress_shallow", "spindle_reconstruct", "spindle_last_error", "spindle_version"]
+
+
+class KvDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_kv_heads", C.c_int32), ("group_size", C.c_int32),
+                ("seq_len", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+
+
+class SpindleError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"spindle status {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libspindle.so (built by paper_2507_06517_amd.build); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2507_06517_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
+        L.spindle_deep_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
+        L.spindle_compress_deep.argtypes = [C.POINTER(KvDesc), vp, vp, vp, i32, i32, f32, i32, i32, vp, i32,
+                                            vp, vp, vp, vp, vp, sz, vp]
+        L.spindle_shallow_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
+        L.spindle_compress_shallow.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 14 + [vp, sz, vp]
+        L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        for name in EXPORTS[:5]:
+            getattr(L, name).restype = C.c_int
+        L.spindle_last_error.restype = C.c_char_p
+        L.spindle_version.restype = C.c_uint32
+        _lib = L
+    return _lib
+
+
+def _check(code):
+    if code != 0:
+        raise SpindleError(code, lib().spindle_last_error().decode())
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def torch_dtype(dtype: str):
+    import torch
+    return {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
+
+
+def to_device(bits: np.ndarray, dtype: str, device="cuda"):
+    """numpy device representation (see workloads) -> torch tensor on the GPU."""
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(bits).to(device)
+
+
+def to_host_bits(t, dtype: str) -> np.ndarray:
+    import torch
+    if dtype == "bf16":
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def desc_of(K, group_size: int, dtype: str) -> KvDesc:
+    B, H, l, d = K.shape
+    return KvDesc(B, H, group_size, l, d, _DT[dtype])
+
+
+# ------------------------------------------------------------------ raw calls (same names as the C ABI)
+
+def spindle_deep_workspace_bytes(desc: KvDesc, window: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().spindle_deep_workspace_bytes(C.byref(desc), window, C.byref(out)))
+    return out.value
+
+
+def spindle_shallow_workspace_bytes(desc: KvDesc, n_tensors: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().spindle_shallow_workspace_bytes(C.byref(desc), n_tensors, C.byref(out)))
+    return out.value
+
+
+def spindle_compress_deep(desc, K, V, Qw, window, pool_kernel, scale, norm, budget, budgets, out_stride,
+                          kept_idx, K_out, V_out, scores_out, workspace, workspace_bytes, stream=None):
+    _check(lib().spindle_compress_deep(C.byref(desc), _ptr(K), _ptr(V), _ptr(Qw), window, pool_kernel,
+                                       float(scale), norm, budget, _ptr(budgets), out_stride, _ptr(kept_idx),
+                                       _ptr(K_out), _ptr(V_out), _ptr(scores_out), _ptr(workspace),
+                                       workspace_bytes, stream if stream is not None else _stream()))
+
+
+def spindle_compress_shallow(desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_codes_k, n_codes_v,
+                             n_found_k, n_found_v, ref_k, ref_v, mag_k, mag_v, adj_k, adj_v, deg_k, deg_v,
+                             workspace, workspace_bytes, stream=None):
+    _check(lib().spindle_compress_shallow(C.byref(desc), _ptr(K), _ptr(V), float(theta_k), float(theta_v),
+                                          max_codes, _ptr(Ck), _ptr(Cv), _ptr(n_codes_k), _ptr(n_codes_v),
+                                          _ptr(n_found_k), _ptr(n_found_v), _ptr(ref_k), _ptr(ref_v),
+                                          _ptr(mag_k), _ptr(mag_v), _ptr(adj_k), _ptr(adj_v), _ptr(deg_k),
+                                          _ptr(deg_v), _ptr(workspace), workspace_bytes,
+                                          stream if stream is not None else _stream()))
+
+
+def spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, Cb, ref, mag, out, stream=None):
+    _check(lib().spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, _ptr(Cb), _ptr(ref),
+                                     _ptr(mag), _ptr(out), stream if stream is not None else _stream()))
+
+
+# ------------------------------------------------------------------ allocating helpers
+
+@dataclass
+class DeepPlan:
+    """Pre-allocated outputs and workspace of one deep call shape."""
+    desc: KvDesc
+    window: int
+    pool: int
+    scale: float
+    norm: int
+    budget: int
+    out_stride: int
+    kept: object
+    K_out: object
+    V_out: object
+    scores: object
+    ws: object
+    ws_bytes: int
+    budgets: object = None
+
+    def run(self, K, V, Qw):
+        spindle_compress_deep(self.desc, K, V, Qw, self.window, self.pool, self.scale, self.norm, self.budget,
+                              self.budgets, self.out_stride, self.kept, self.K_out, self.V_out, self.scores,
+                              self.ws, self.ws_bytes)
+        return self.kept, self.K_out, self.V_out, self.scores
+
+
+def plan_deep(K, group_size, dtype, window, pool, budget, scale=None, norm=NORM_PAPER, want_scores=True,
+              budgets=None, out_stride=None, with_v=True) -> DeepPlan:
+    import torch
+    B, H, l, d = K.shape
+    desc = desc_of(K, group_size, dtype)
+    if scale is None:
+        scale = float(np.float32(1.0 / np.sqrt(d)))
+    if out_stride is None:
+        out_stride = min(budget, l)
+    nbytes = spindle_deep_workspace_bytes(desc, window)
+    dev = K.device
+    return DeepPlan(desc, window, pool, scale, norm, budget, out_stride,
+                    torch.empty((B, H, out_stride), dtype=torch.int32, device=dev),
+                    torch.empty((B, H, out_stride, d), dtype=K.dtype, device=dev),
+                    torch.empty((B, H, out_stride, d), dtype=K.dtype, device=dev) if with_v else None,
+                    torch.empty((B, H, max(l - window, 1)), dtype=torch.float32, device=dev) if want_scores else None,
+                    torch.empty(nbytes, dtype=torch.uint8, device=dev), nbytes, budgets)
+
+
+def compress_deep(K, V, Qw, group_size, dtype, window, pool, budget, **kw):
+    plan = plan_deep(K, group_size, dtype, window, pool, budget, with_v=V is not None, **kw)
+    return plan.run(K, V, Qw)
+
+
+@dataclass
+class ShallowPlan:
+    desc: KvDesc
+    theta_k: float
+    theta_v: float
+    max_codes: int
+    out: dict
+    ws: object
+    ws_bytes: int
+
+    def run(self, K, V):
+        o = self.out
+        g = lambda k: o.get(k)
+        spindle_compress_shallow(self.desc, K, V, self.theta_k, self.theta_v, self.max_codes,
+                                 g("C_k"), g("C_v"), g("n_codes_k"), g("n_codes_v"), g("n_found_k"), g("n_found_v"),
+                                 g("ref_k"), g("ref_v"), g("mag_k"), g("mag_v"), g("adj_k"), g("adj_v"),
+                                 g("deg_k"), g("deg_v"), self.ws, self.ws_bytes)
+        return o
+
+
+def plan_shallow(K, dtype, theta_k, theta_v, max_codes, tensors=("k", "v"), debug=False) -> ShallowPlan:
+    import torch
+    B, H, l, d = K.shape
+    desc = desc_of(K, 1, dtype)
+    nbytes = spindle_shallow_workspace_bytes(desc, len(tensors))
+    dev = K.device
+    out = {}
+    for t in tensors:
+        out[f"C_{t}"] = torch.empty((B, H, max_codes, d), dtype=K.dtype, device=dev)
+        out[f"n_codes_{t}"] = torch.empty((B, H), dtype=torch.int32, device=dev)
+        out[f"n_found_{t}"] = torch.empty((B, H), dtype=torch.int32, device=dev)
+        out[f"ref_{t}"] = torch.empty((B, H, l), dtype=torch.int32, device=dev)
+        out[f"mag_{t}"] = torch.empty((B, H, l), dtype=torch.float32, device=dev)
+        if debug:
+            out[f"adj_{t}"] = torch.empty((B, H, l, (l + 31) // 32), dtype=torch.int32, device=dev)
+            out[f"deg_{t}"] = torch.empty((B, H, l), dtype=torch.int32, device=dev)
+    return ShallowPlan(desc, theta_k, theta_v, max_codes, out,
+                       torch.empty(nbytes, dtype=torch.uint8, device=dev), nbytes)
+
+
+def compress_shallow(K, V, dtype, theta_k, theta_v, max_codes, debug=False):
+    ref = K if K is not None else V
+    tensors = tuple(t for t, x in (("k", K), ("v", V)) if x is not None)
+    plan = plan_shallow(ref, dtype, theta_k, theta_v, max_codes, tensors, debug)
+    return plan.run(K, V)
+
+
+def reconstruct(Cb, ref, mag, dtype):
+    import torch
+    B, H, cap, d = Cb.shape
+    l = ref.shape[-1]
+    out = torch.empty((B, H, l, d), dtype=Cb.dtype, device=Cb.device)
+    spindle_reconstruct(B * H, l, d, _DT[dtype], cap, Cb, ref, mag, out)
+    return out

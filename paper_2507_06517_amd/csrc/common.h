@@ -1,0 +1,90 @@
+// Shared host/device helpers of the HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "spindle.h"
+
+namespace spindle {
+
+constexpr int kHeadDim = 128;
+constexpr int kWave = 64;
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------- error reporting
+void set_error(const char *fmt, ...);
+spindle_status check_desc(const spindle_kv_desc *d);
+
+#define SPINDLE_FAIL(code, ...)        \
+  do {                                 \
+    ::spindle::set_error(__VA_ARGS__); \
+    return (code);                     \
+  } while (0)
+
+#define SPINDLE_HIP(call)                                                            \
+  do {                                                                               \
+    hipError_t e_ = (call);                                                          \
+    if (e_ != hipSuccess) SPINDLE_FAIL(SPINDLE_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline int dtype_bytes(int dt) { return dt == SPINDLE_F32 ? 4 : 2; }
+
+// Bump allocator over the caller's workspace.
+struct Carver {
+  char *base;
+  size_t off = 0;
+  explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+  template <typename T>
+  T *take(size_t count) {
+    off = align_up(off, 256);
+    T *r = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return r;
+  }
+  size_t total() const { return align_up(off, 256); }
+};
+
+// ---------------------------------------------------------------- element access
+template <int DT>
+struct Elem;
+template <>
+struct Elem<SPINDLE_F32> {
+  typedef float type;
+  static __device__ __forceinline__ float to_float(float v) { return v; }
+  static __device__ __forceinline__ float from_float(float v) { return v; }
+};
+template <>
+struct Elem<SPINDLE_F16> {
+  typedef _Float16 type;
+  static __device__ __forceinline__ float to_float(_Float16 v) { return (float)v; }
+  static __device__ __forceinline__ _Float16 from_float(float v) { return (_Float16)v; }
+};
+template <>
+struct Elem<SPINDLE_BF16> {
+  typedef uint16_t type;
+  static __device__ __forceinline__ float to_float(uint16_t v) {
+    return __uint_as_float(((uint32_t)v) << 16);
+  }
+  static __device__ __forceinline__ uint16_t from_float(float v) {  // round to nearest even
+    uint32_t u = __float_as_uint(v);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  }
+};
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Spread the four nibbles of a 16-bit value to bits [8k, 8k+4) of a 32-bit word.
+__device__ __forceinline__ uint32_t spread_nibbles(uint32_t p) {
+  return (p & 0xFu) | ((p & 0xF0u) << 4) | ((p & 0xF00u) << 8) | ((p & 0xF000u) << 12);
+}
+
+}  // namespace spindle

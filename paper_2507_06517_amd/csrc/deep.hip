@@ -1,0 +1,555 @@
+// Attention-weight token eviction (Sec. "Attention Weight Based Token Eviction").
+//
+// Kernels, all enqueued on the caller's stream:
+//   deep_pass<.., false>  window logits by MFMA, per-row softmax statistics (Eq. 1)
+//   deep_combine          merges the per-chunk statistics into (max, 1/sum) per query row
+//   deep_pass<.., true>   recomputes the logits, forms softmax weights, sums them over
+//                         the window queries and the GQA group (Eq. 2, 3)
+//   deep_select           max-pool, radix select of the k largest, ordered compaction (Eq. 7)
+//   deep_gather           K_out = K[kept], V_out = V[kept]
+#include <math.h>
+
+#include "common.h"
+#include "mma.h"
+
+namespace spindle {
+namespace {
+
+constexpr int kStageKeys = 128;      // keys per LDS stage
+constexpr int kStagesPerBlock = 4;   // keys per block = 512
+constexpr int kKeysPerBlock = kStageKeys * kStagesPerBlock;
+constexpr int kDeepThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct DeepParams {
+  const char *K;       // [U][l][128] elements
+  const char *Q;       // [U][R][128] elements (R = hn*lw rows, head-major)
+  float2 *partial;     // [U][nchunks][Rpad] (max, sum) per chunk of keys
+  float2 *stats;       // [U][Rpad] (max, 1/sum)
+  float *scores;       // [U][lc] group-averaged accumulated attention
+  int l, lc, lw, hn, R, Rpad, nchunks;
+  float sc2;           // scale * log2(e): logits are kept in base-2 units
+  float inv_hn;
+  int norm;
+};
+
+// ---------------------------------------------------------------- stage loading
+template <int DT>
+struct Stage {
+  typedef Mma<DT> M;
+  static constexpr int kThreadsPerRow = M::kRowBytes / 16;
+  static constexpr int kRowsPerPass = kDeepThreads / kThreadsPerRow;
+  static constexpr int kPasses = kStageKeys / kRowsPerPass;
+  static constexpr int kBytes = kStageKeys * M::kLdsRow;
+
+  // global -> registers; keys at or beyond `l` read as zero
+  static __device__ __forceinline__ void fetch(u4 (&r)[kPasses], const char *Kunit, int k0, int l) {
+    const int tr = threadIdx.x / kThreadsPerRow, tc = threadIdx.x % kThreadsPerRow;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int key = k0 + p * kRowsPerPass + tr;
+      u4 v = {0, 0, 0, 0};
+      if (key < l) v = *reinterpret_cast<const u4 *>(Kunit + (size_t)key * M::kRowBytes + tc * 16);
+      r[p] = v;
+    }
+  }
+  static __device__ __forceinline__ void store(const u4 (&r)[kPasses], char *lds) {
+    const int tr = threadIdx.x / kThreadsPerRow, tc = threadIdx.x % kThreadsPerRow;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p)
+      *reinterpret_cast<u4 *>(lds + (p * kRowsPerPass + tr) * M::kLdsRow + tc * 16) = r[p];
+  }
+};
+
+// One pass over a block's keys.  ACCUM = false: softmax statistics; true: weights.
+// WR waves split the (padded) query rows in groups of 64, the other 4/WR split the
+// four 32-key tiles of a stage.
+template <int DT, int WR, bool ACCUM>
+__global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
+  typedef Mma<DT> M;
+  typedef Stage<DT> S;
+  constexpr int WK = 4 / WR;
+  constexpr int kTilesPerWave = 4 / WK;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  // ACCUM: column partial sums [2][2*WR][kStageKeys] placed after the stage buffers
+  float *colpart = reinterpret_cast<float *>(smem + 2 * S::kBytes);
+
+  const int u = blockIdx.y;
+  const int chunk = blockIdx.x;
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int g = lane >> 5, c = lane & 31;
+  const int wr = wave % WR, wk = wave / WR;
+  const int key_begin = chunk * kKeysPerBlock;
+  const int key_limit = ACCUM ? p.lc : p.l;   // keys at or beyond this index are not needed
+  const char *Kunit = p.K + (size_t)u * p.l * M::kRowBytes;
+  const char *Qunit = p.Q + (size_t)u * p.R * M::kRowBytes;
+
+  // query fragments stay in registers for the whole block
+  typename M::frag qf[2][M::kSteps];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = 64 * wr + 32 * rb + c;
+#pragma unroll
+    for (int ks = 0; ks < M::kSteps; ++ks)
+      qf[rb][ks] = row < p.R ? M::load(Qunit + (size_t)row * M::kRowBytes, ks, g) : M::zero();
+  }
+
+  // per-row state of this lane: stats pass (reference, sum); accumulate pass (max, weight)
+  float s0[2][16], s1[2][16];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (ACCUM) {
+        const int row = 64 * wr + 32 * rb + mma_row(v, g);
+        const float2 st = p.stats[(size_t)u * p.Rpad + row];
+        s0[rb][v] = st.x;
+        s1[rb][v] = st.y;
+      } else {
+        s0[rb][v] = -INFINITY;
+        s1[rb][v] = 0.f;
+      }
+    }
+
+  u4 regs[S::kPasses];
+  S::fetch(regs, Kunit, key_begin, key_limit);
+  S::store(regs, smem);
+  __syncthreads();
+
+  for (int s = 0; s < kStagesPerBlock; ++s) {
+    const int k0 = key_begin + s * kStageKeys;
+    if (k0 >= key_limit) break;                       // uniform over the block
+    const bool more = (s + 1 < kStagesPerBlock) && (k0 + kStageKeys < key_limit);
+    if (more) S::fetch(regs, Kunit, k0 + kStageKeys, key_limit);
+
+    if (ACCUM && s > 0 && threadIdx.x < kStageKeys) {
+      // finish the previous stage: fixed-order sum of the partial column sums
+      const float *cp = colpart + ((s - 1) & 1) * (2 * WR * kStageKeys);
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 2 * WR; ++j) sum += cp[j * kStageKeys + threadIdx.x];
+      const int a = k0 - kStageKeys + threadIdx.x;
+      if (a < p.lc) {
+        float v = sum * p.inv_hn;
+        if (p.norm == SPINDLE_NORM_PAPER) v = v / (float)(p.l - a);
+        p.scores[(size_t)u * p.lc + a] = v;
+      }
+    }
+
+    const char *lds = smem + (s & 1) * S::kBytes;
+    const bool tail = !ACCUM && (k0 + kStageKeys > p.lc);   // causal mask / end of sequence
+#pragma unroll
+    for (int t = 0; t < kTilesPerWave; ++t) {
+      const int ct = wk + t * WK;
+      f16v acc[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
+      const char *krow = lds + (ct * 32 + c) * M::kLdsRow;
+#pragma unroll
+      for (int ks = 0; ks < M::kSteps; ++ks) {
+        const typename M::frag kf = M::load(krow, ks, g);
+        acc[0] = M::mma(qf[0][ks], kf, acc[0]);
+        acc[1] = M::mma(qf[1][ks], kf, acc[1]);
+      }
+      if (ACCUM) {
+        float cs0 = 0.f, cs1 = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          cs0 = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[0][v], p.sc2, -s0[0][v])), s1[0][v], cs0);
+          cs1 = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[1][v], p.sc2, -s0[1][v])), s1[1][v], cs1);
+        }
+        colpart[(s & 1) * (2 * WR * kStageKeys) + (2 * wr + g) * kStageKeys + ct * 32 + c] = cs0 + cs1;
+      } else if (!tail) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          float d[16], t_[16];
+          float dmax = -INFINITY;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            t_[v] = acc[rb][v] * p.sc2;
+            d[v] = t_[v] - s0[rb][v];
+            dmax = fmaxf(dmax, d[v]);
+          }
+          if (__any(dmax > 40.f)) {      // move the reference up (always on the first tile)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              if (d[v] > 0.f) {
+                s1[rb][v] *= __builtin_amdgcn_exp2f(s0[rb][v] - t_[v]);
+                s0[rb][v] = t_[v];
+                d[v] = 0.f;
+              }
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v) s1[rb][v] += __builtin_amdgcn_exp2f(d[v]);
+        }
+      } else {
+        const int key = k0 + ct * 32 + c;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = 64 * wr + 32 * rb + mma_row(v, g);
+            const bool valid = row < p.R && key < p.l && key <= p.lc + (row % p.lw);
+            if (valid) {
+              const float t = acc[rb][v] * p.sc2;
+              if (t > s0[rb][v]) {
+                s1[rb][v] = s1[rb][v] * __builtin_amdgcn_exp2f(s0[rb][v] - t) + 1.f;
+                s0[rb][v] = t;
+              } else {
+                s1[rb][v] += __builtin_amdgcn_exp2f(t - s0[rb][v]);
+              }
+            }
+          }
+      }
+    }
+    if (more) S::store(regs, smem + ((s + 1) & 1) * S::kBytes);
+    __syncthreads();
+    if (ACCUM && !more && threadIdx.x < kStageKeys) {
+      const float *cp = colpart + (s & 1) * (2 * WR * kStageKeys);
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 2 * WR; ++j) sum += cp[j * kStageKeys + threadIdx.x];
+      const int a = k0 + threadIdx.x;
+      if (a < p.lc) {
+        float v = sum * p.inv_hn;
+        if (p.norm == SPINDLE_NORM_PAPER) v = v / (float)(p.l - a);
+        p.scores[(size_t)u * p.lc + a] = v;
+      }
+    }
+  }
+
+  if (!ACCUM) {
+    // lane partials -> LDS (swizzled slot so that the row-wise readers spread over banks)
+    constexpr int kSlots = WK * 32;
+    __syncthreads();
+    float2 *red = reinterpret_cast<float2 *>(smem);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = 64 * wr + 32 * rb + mma_row(v, g);
+        const int slot = (wk * 32 + c + row) % kSlots;
+        red[row * kSlots + slot] = make_float2(s0[rb][v], s1[rb][v]);
+      }
+    __syncthreads();
+    const int row = threadIdx.x;
+    if (row < 64 * WR) {
+      float m = -INFINITY;
+      for (int j = 0; j < kSlots; ++j) m = fmaxf(m, red[row * kSlots + (j + row) % kSlots].x);
+      float z = 0.f;
+      if (m > -INFINITY)
+        for (int j = 0; j < kSlots; ++j) {
+          const float2 e = red[row * kSlots + (j + row) % kSlots];
+          if (e.y > 0.f) z += e.y * __builtin_amdgcn_exp2f(e.x - m);
+        }
+      p.partial[((size_t)u * p.nchunks + chunk) * p.Rpad + row] = make_float2(m, z);
+    }
+  }
+}
+
+__global__ void deep_combine(DeepParams p, int U) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= U * p.Rpad) return;
+  const int u = i / p.Rpad, row = i % p.Rpad;
+  float m = -INFINITY;
+  for (int ch = 0; ch < p.nchunks; ++ch)
+    m = fmaxf(m, p.partial[((size_t)u * p.nchunks + ch) * p.Rpad + row].x);
+  float z = 0.f;
+  if (m > -INFINITY)
+    for (int ch = 0; ch < p.nchunks; ++ch) {
+      const float2 e = p.partial[((size_t)u * p.nchunks + ch) * p.Rpad + row];
+      if (e.y > 0.f) z += e.y * __builtin_amdgcn_exp2f(e.x - m);
+    }
+  const bool ok = row < p.R && z > 0.f;
+  p.stats[i] = make_float2(ok ? m : 0.f, ok ? 1.f / z : 0.f);
+}
+
+// ---------------------------------------------------------------- pool + top-k
+struct SelectParams {
+  const float *scores;   // [U][lc]
+  float *pooled;         // [U][lc]
+  float *scores_out;     // optional [U][lc]
+  const int32_t *budgets;
+  int32_t *kept;         // [U][out_stride]
+  int l, lc, lw, pool, budget, out_stride;
+};
+
+constexpr int kSelThreads = 1024;
+
+__device__ __forceinline__ uint32_t orderable(float f) {
+  const uint32_t b = __float_as_uint(f);
+  return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+// exclusive scan of (a, b) over the block; returns this thread's offsets and the totals
+__device__ __forceinline__ void block_scan2(int a, int b, int &oa, int &ob, int &ta, int &tb,
+                                            int (*wsum)[2]) {
+  const int lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int ia = a, ib = b;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int xa = __shfl_up(ia, o), xb = __shfl_up(ib, o);
+    if (lane >= o) { ia += xa; ib += xb; }
+  }
+  if (lane == 63) { wsum[wave][0] = ia; wsum[wave][1] = ib; }
+  __syncthreads();
+  int pa = 0, pb = 0;
+  ta = 0; tb = 0;
+  for (int w = 0; w < nw; ++w) {
+    if (w < wave) { pa += wsum[w][0]; pb += wsum[w][1]; }
+    ta += wsum[w][0]; tb += wsum[w][1];
+  }
+  oa = pa + ia - a;
+  ob = pb + ib - b;
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p) {
+  __shared__ int hist[256];
+  __shared__ int wsum[kSelThreads / 64][2];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_krem;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int lc = p.lc;
+  const float *raw = p.scores + (size_t)u * lc;
+  float *pooled = p.pooled + (size_t)u * lc;
+  int32_t *kept = p.kept + (size_t)u * p.out_stride;
+  int budget = p.budgets ? p.budgets[u] : p.budget;
+  if (budget < p.lw) budget = p.lw;
+  int k = budget - p.lw;
+  if (k > lc) k = lc;
+  if (k > p.out_stride - p.lw) k = p.out_stride - p.lw;   // never write past the row pitch
+
+  // 1-D max pooling, window clipped to the context
+  const int r = (p.pool - 1) / 2;
+  for (int a = tid; a < lc; a += kSelThreads) {
+    float m = raw[a];
+    const int lo = a - r < 0 ? 0 : a - r, hi = a + r >= lc ? lc - 1 : a + r;
+    for (int j = lo; j <= hi; ++j) m = fmaxf(m, raw[j]);
+    pooled[a] = m;
+    if (p.scores_out) p.scores_out[(size_t)u * lc + a] = m;
+  }
+  __syncthreads();
+
+  // value of the k-th largest pooled score by most-significant-digit radix select
+  uint32_t prefix = 0;
+  int krem = k;   // how many still to take among the elements matching `prefix`
+  if (k > 0 && k < lc) {
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int a = tid; a < lc; a += kSelThreads) {
+        const uint32_t x = orderable(pooled[a]);
+        if (shift == 24 || (x >> (shift + 8)) == (prefix >> (shift + 8)))
+          atomicAdd(&hist[(x >> shift) & 255u], 1);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int rem = krem, d = 255;
+        for (; d > 0; --d) {
+          const int cnt = hist[d];
+          if (cnt >= rem) break;
+          rem -= cnt;
+        }
+        sh_prefix = prefix | ((uint32_t)d << shift);
+        sh_krem = rem;
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      krem = sh_krem;
+      __syncthreads();
+    }
+  }
+  // ordered compaction: everything above the threshold, then the first `krem` equal to it
+  const int per = (lc + kSelThreads - 1) / kSelThreads;
+  const int a0 = tid * per, a1 = (a0 + per < lc) ? a0 + per : lc;
+  int ngt = 0, neq = 0;
+  if (k >= lc) {
+    ngt = a1 > a0 ? a1 - a0 : 0;
+  } else if (k > 0) {
+    for (int a = a0; a < a1; ++a) {
+      const uint32_t x = orderable(pooled[a]);
+      ngt += x > prefix;
+      neq += x == prefix;
+    }
+  }
+  int ogt, oeq, tgt, teq;
+  block_scan2(ngt, neq, ogt, oeq, tgt, teq, wsum);
+  if (k >= lc) {
+    for (int a = a0; a < a1; ++a) kept[a] = a;
+  } else if (k > 0) {
+    int eq_seen = oeq, gt_seen = ogt;
+    for (int a = a0; a < a1; ++a) {
+      const uint32_t x = orderable(pooled[a]);
+      if (x > prefix) {
+        kept[gt_seen + (eq_seen < krem ? eq_seen : krem)] = a;
+        ++gt_seen;
+      } else if (x == prefix) {
+        if (eq_seen < krem) kept[gt_seen + eq_seen] = a;
+        ++eq_seen;
+      }
+    }
+  }
+  for (int b = tid; b < p.lw; b += kSelThreads) kept[k + b] = lc + b;
+  for (int j = k + p.lw + tid; j < p.out_stride; j += kSelThreads) kept[j] = -1;
+}
+
+// ---------------------------------------------------------------- gather
+struct GatherParams {
+  const char *K, *V;
+  char *Ko, *Vo;
+  const int32_t *kept;
+  int l, out_stride, row_bytes;
+};
+
+__global__ __launch_bounds__(256) void deep_gather(GatherParams p) {
+  const int tpr = p.row_bytes / 16;
+  const int rows_per_block = 256 / tpr;
+  const int u = blockIdx.y;
+  const int j = blockIdx.x * rows_per_block + threadIdx.x / tpr;
+  const int t = threadIdx.x % tpr;
+  if (j >= p.out_stride) return;
+  const int idx = p.kept[(size_t)u * p.out_stride + j];
+  const size_t dst = ((size_t)u * p.out_stride + j) * p.row_bytes + t * 16;
+  const size_t src = ((size_t)u * p.l + (idx < 0 ? 0 : idx)) * p.row_bytes + t * 16;
+  u4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+  if (idx >= 0) {
+    kv = *reinterpret_cast<const u4 *>(p.K + src);
+    if (p.V) vv = *reinterpret_cast<const u4 *>(p.V + src);
+  }
+  *reinterpret_cast<u4 *>(p.Ko + dst) = kv;
+  if (p.Vo) *reinterpret_cast<u4 *>(p.Vo + dst) = vv;
+}
+
+// ---------------------------------------------------------------- host side
+struct DeepLayout {
+  float2 *partial, *stats;
+  float *scores, *pooled;
+  size_t bytes;
+};
+
+DeepLayout deep_layout(void *ws, int U, int l, int lw, int Rpad) {
+  Carver cv(ws);
+  DeepLayout L;
+  const int nchunks = (l + kKeysPerBlock - 1) / kKeysPerBlock;
+  const int lc = l - lw;
+  L.partial = cv.take<float2>((size_t)U * nchunks * Rpad);
+  L.stats = cv.take<float2>((size_t)U * Rpad);
+  L.scores = cv.take<float>((size_t)U * (lc > 0 ? lc : 1));
+  L.pooled = cv.take<float>((size_t)U * (lc > 0 ? lc : 1));
+  L.bytes = cv.total();
+  return L;
+}
+
+int padded_rows(int R) { return R <= 64 ? 64 : (R <= 128 ? 128 : 256); }
+
+template <int DT, int WR>
+spindle_status launch_passes(const DeepParams &p, int U, hipStream_t st) {
+  typedef Stage<DT> S;
+  const size_t smem_stats = 2 * (size_t)S::kBytes > 65536 ? 2 * (size_t)S::kBytes : 65536;
+  const size_t smem_acc = 2 * (size_t)S::kBytes + 2 * 2 * WR * kStageKeys * sizeof(float);
+  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&deep_pass<DT, WR, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_stats));
+  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&deep_pass<DT, WR, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_acc));
+  hipLaunchKernelGGL((deep_pass<DT, WR, false>), dim3(p.nchunks, U), dim3(kDeepThreads), smem_stats, st, p);
+  const int total = U * p.Rpad;
+  hipLaunchKernelGGL(deep_combine, dim3((total + 255) / 256), dim3(256), 0, st, p, U);
+  if (p.lc > 0) {
+    const int nacc = (p.lc + kKeysPerBlock - 1) / kKeysPerBlock;
+    hipLaunchKernelGGL((deep_pass<DT, WR, true>), dim3(nacc, U), dim3(kDeepThreads), smem_acc, st, p);
+  }
+  SPINDLE_HIP(hipGetLastError());
+  return SPINDLE_OK;
+}
+
+template <int DT>
+spindle_status launch_dtype(const DeepParams &p, int U, hipStream_t st) {
+  if (p.Rpad == 64) return launch_passes<DT, 1>(p, U, st);
+  if (p.Rpad == 128) return launch_passes<DT, 2>(p, U, st);
+  return launch_passes<DT, 4>(p, U, st);
+}
+
+}  // namespace
+}  // namespace spindle
+
+using namespace spindle;
+
+extern "C" spindle_status spindle_deep_workspace_bytes(const spindle_kv_desc *desc, int32_t window,
+                                                       size_t *bytes) {
+  spindle_status s = check_desc(desc);
+  if (s != SPINDLE_OK) return s;
+  if (!bytes) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "bytes is NULL");
+  if (window < 1 || window > desc->seq_len) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "window must be in [1, seq_len]");
+  if (desc->group_size < 1 || (int64_t)window * desc->group_size > 256)
+    SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "window * group_size must be in [1, 256]");
+  const int U = desc->batch * desc->n_kv_heads;
+  *bytes = deep_layout(nullptr, U, desc->seq_len, window, padded_rows(window * desc->group_size)).bytes;
+  return SPINDLE_OK;
+}
+
+extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, const void *K, const void *V,
+                                                const void *Qw, int32_t window, int32_t pool_kernel,
+                                                float scale, int32_t norm, int32_t budget,
+                                                const int32_t *budgets, int32_t out_stride,
+                                                int32_t *kept_idx, void *K_out, void *V_out,
+                                                float *scores_out, void *workspace,
+                                                size_t workspace_bytes, void *stream) {
+  size_t need = 0;
+  spindle_status s = spindle_deep_workspace_bytes(desc, window, &need);
+  if (s != SPINDLE_OK) return s;
+  if (!K || !Qw || !kept_idx || !K_out) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "K, Qw, kept_idx and K_out are required");
+  if ((V == nullptr) != (V_out == nullptr)) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "V and V_out must both be given or both NULL");
+  if (pool_kernel < 1 || (pool_kernel & 1) == 0) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "pool_kernel must be odd and >= 1");
+  if (norm != SPINDLE_NORM_PAPER && norm != SPINDLE_NORM_NONE) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "unknown norm mode %d", norm);
+  if (!(scale == scale) || fabsf(scale) > 3.0e38f) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "scale must be finite");
+  const int l = desc->seq_len, lw = window, lc = l - lw;
+  if (!budgets && budget < lw) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "budget (%d) must be >= window (%d)", budget, lw);
+  if (out_stride < lw || (!budgets && out_stride < (budget < l ? budget : l)))
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "out_stride (%d) is smaller than the kept-token count", out_stride);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+  const uintptr_t al = reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V) |
+                       reinterpret_cast<uintptr_t>(Qw) | reinterpret_cast<uintptr_t>(K_out) |
+                       reinterpret_cast<uintptr_t>(V_out);
+  if (al & 15) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int U = desc->batch * desc->n_kv_heads;
+  const int R = lw * desc->group_size, Rpad = padded_rows(R);
+  DeepLayout L = deep_layout(workspace, U, l, lw, Rpad);
+
+  DeepParams p;
+  p.K = static_cast<const char *>(K);
+  p.Q = static_cast<const char *>(Qw);
+  p.partial = L.partial;
+  p.stats = L.stats;
+  p.scores = L.scores;
+  p.l = l; p.lc = lc; p.lw = lw; p.hn = desc->group_size; p.R = R; p.Rpad = Rpad;
+  p.nchunks = (l + kKeysPerBlock - 1) / kKeysPerBlock;
+  p.sc2 = scale * kLog2e;
+  p.inv_hn = 1.0f / (float)desc->group_size;
+  p.norm = norm;
+  if (desc->dtype == SPINDLE_F16) s = launch_dtype<SPINDLE_F16>(p, U, st);
+  else if (desc->dtype == SPINDLE_BF16) s = launch_dtype<SPINDLE_BF16>(p, U, st);
+  else s = launch_dtype<SPINDLE_F32>(p, U, st);
+  if (s != SPINDLE_OK) return s;
+
+  SelectParams sp;
+  sp.scores = L.scores; sp.pooled = L.pooled; sp.scores_out = scores_out;
+  sp.budgets = budgets; sp.kept = kept_idx;
+  sp.l = l; sp.lc = lc; sp.lw = lw; sp.pool = pool_kernel; sp.budget = budget; sp.out_stride = out_stride;
+  hipLaunchKernelGGL(deep_select, dim3(U), dim3(kSelThreads), 0, st, sp);
+
+  GatherParams gp;
+  gp.K = static_cast<const char *>(K); gp.V = static_cast<const char *>(V);
+  gp.Ko = static_cast<char *>(K_out); gp.Vo = static_cast<char *>(V_out);
+  gp.kept = kept_idx; gp.l = l; gp.out_stride = out_stride;
+  gp.row_bytes = kHeadDim * dtype_bytes(desc->dtype);
+  const int rows_per_block = 256 / (gp.row_bytes / 16);
+  hipLaunchKernelGGL(deep_gather, dim3((out_stride + rows_per_block - 1) / rows_per_block, U), dim3(256), 0, st, gp);
+  SPINDLE_HIP(hipGetLastError());
+  return SPINDLE_OK;
+}

@@ -1,0 +1,729 @@
+// Similarity codebook replacement (Sec. "Similarity Based Token Replacement", Alg. 1).
+//
+// Kernels, all enqueued on the caller's stream; ut = tensor * units + unit indexes one
+// independent (batch, kv-head, K|V) problem of n tokens:
+//   shallow_prep    magnitudes (Eq. 8) in double precision, unit vectors rounded to fp16
+//   shallow_gram    cosine similarity tiles by fp16 MFMA, thresholded and bit-packed
+//                   into the adjacency matrix G (Eq. 4, 9); pairs whose fp16 similarity
+//                   lies within kGuard of theta are deferred to shallow_fixup
+//   shallow_fixup   exact double-precision decision for the deferred pairs
+//   shallow_merge   persistent kernel: degrees (Eq. 10) and the greedy highest-degree
+//                   codebook construction (Eq. 11-13), all rounds on the device
+//   shallow_overflow  re-points tokens whose entry fell beyond the codebook cap
+#include <math.h>
+#include <string.h>
+
+#include "common.h"
+#include "mma.h"
+
+namespace spindle {
+namespace {
+
+// |fp16 MFMA cosine - exact cosine| stays below this bound: both unit vectors carry a
+// relative rounding error of 2^-11 per component (sum <= 2^-10 by Cauchy-Schwarz), plus
+// flushed fp16 subnormal components (< 7e-4) and fp32 accumulation (< 1e-5).
+constexpr float kGuard = 2.0e-3f;
+
+constexpr int kPanelRows = 256;   // rows of G's column range held in registers per block
+constexpr int kChunkCols = 1024;  // tokens streamed through LDS per block
+constexpr int kStageCols = 64;
+constexpr int kGramThreads = 256;
+constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad
+constexpr int kStageBytes = kStageCols * kLdsRow;
+
+constexpr int kMergeThreads = 256;
+constexpr int kCounters = 16;     // ints per ut
+enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4 };
+
+struct ShallowParams {
+  const char *X[2];        // input tensors [U][n][128] in `dtype` (index = tensor slot)
+  float theta[2];
+  int dtype, U, UT, n, Wp;  // Wp = words per adjacency row (multiple of 8)
+  int cap;
+  // workspace
+  _Float16 *Xh;            // [UT][n][128] unit vectors
+  double *m64;             // [UT][n]
+  uint32_t *G;             // [UT][n][Wp]
+  int *deg, *status, *slot, *cand, *dying, *pick_vert, *rank, *rank_vert;   // [UT][n]
+  uint32_t *key, *m1, *pick_key;                                             // [UT][n]
+  int *counters;           // [UT][kCounters]
+  unsigned *bar;           // [groups]
+  int *err;                // [1] set if a bounded wait expired
+  unsigned long long *fix; // deferred pairs
+  unsigned *fix_count;
+  unsigned fix_cap;
+  uint32_t *ovf;           // [UT*n] tokens to re-point, packed ut << 16 | token
+  unsigned *ovf_count;
+  // outputs (index = tensor slot)
+  char *C[2];
+  int32_t *n_codes[2], *n_found[2], *ref[2];
+  float *mag[2];
+  int32_t *deg_out[2];     // optional initial degrees
+  // merge launch shape
+  int blocks_per_group, n_groups;
+  unsigned spin_limit;
+};
+
+__device__ __forceinline__ const char *x_row(const ShallowParams &p, int ut, int a) {
+  const int t = ut / p.U, u = ut % p.U;
+  return p.X[t] + ((size_t)u * p.n + a) * (size_t)(kHeadDim * (p.dtype == SPINDLE_F32 ? 4 : 2));
+}
+
+// x_a . x_b in double precision, summed in dimension order (products are exact).
+template <int DT>
+__device__ double dot64(const char *ra, const char *rb) {
+  typedef typename Elem<DT>::type T;
+  constexpr int per = 16 / sizeof(T);
+  double acc = 0.0;
+  for (int ch = 0; ch < kHeadDim / per; ++ch) {
+    const u4 va = reinterpret_cast<const u4 *>(ra)[ch];
+    const u4 vb = reinterpret_cast<const u4 *>(rb)[ch];
+    const T *ea = reinterpret_cast<const T *>(&va);
+    const T *eb = reinterpret_cast<const T *>(&vb);
+#pragma unroll
+    for (int i = 0; i < per; ++i)
+      acc += (double)Elem<DT>::to_float(ea[i]) * (double)Elem<DT>::to_float(eb[i]);
+  }
+  return acc;
+}
+
+__device__ double dot64_any(int dtype, const char *ra, const char *rb) {
+  if (dtype == SPINDLE_F16) return dot64<SPINDLE_F16>(ra, rb);
+  if (dtype == SPINDLE_BF16) return dot64<SPINDLE_BF16>(ra, rb);
+  return dot64<SPINDLE_F32>(ra, rb);
+}
+
+// Eq. 4 evaluated the way the adjacency decision is defined: double precision,
+// dimension-order dot product, 0 when either vector is zero.
+__device__ double cos64(const ShallowParams &p, int ut, int a, int b) {
+  const double den = p.m64[(size_t)ut * p.n + a] * p.m64[(size_t)ut * p.n + b];
+  if (!(den > 0.0)) return 0.0;
+  return dot64_any(p.dtype, x_row(p, ut, a), x_row(p, ut, b)) / den;
+}
+
+// ---------------------------------------------------------------- prep
+template <int DT>
+__global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
+  typedef typename Elem<DT>::type T;
+  constexpr int kRows = 64;
+  constexpr int row_bytes = kHeadDim * sizeof(T);
+  constexpr int lds_row = row_bytes + 16;
+  constexpr int tpr = row_bytes / 16;
+  __shared__ __attribute__((aligned(16))) char tile_in[kRows * lds_row];
+  __shared__ __attribute__((aligned(16))) char tile_out[kRows * kLdsRow];
+  const int ut = blockIdx.y, t = ut / p.U;
+  const int row0 = blockIdx.x * kRows;
+  for (int i = threadIdx.x; i < kRows * tpr; i += 256) {
+    const int r = i / tpr, ch = i % tpr;
+    u4 v = {0, 0, 0, 0};
+    if (row0 + r < p.n) v = *reinterpret_cast<const u4 *>(x_row(p, ut, row0 + r) + ch * 16);
+    *reinterpret_cast<u4 *>(tile_in + r * lds_row + ch * 16) = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < kRows && row0 + threadIdx.x < p.n) {
+    const int r = threadIdx.x;
+    constexpr int per = 16 / sizeof(T);
+    double ss = 0.0;
+    for (int ch = 0; ch < tpr; ++ch) {
+      const u4 v = *reinterpret_cast<const u4 *>(tile_in + r * lds_row + ch * 16);
+      const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+      for (int i = 0; i < per; ++i) {
+        const double x = (double)Elem<DT>::to_float(e[i]);
+        ss += x * x;
+      }
+    }
+    const double m = sqrt(ss);
+    const size_t idx = (size_t)ut * p.n + row0 + r;
+    p.m64[idx] = m;
+    p.mag[t][(size_t)(ut % p.U) * p.n + row0 + r] = (float)m;
+    const float inv = m > 0.0 ? (float)(1.0 / m) : 0.f;
+    for (int ch = 0; ch < tpr; ++ch) {
+      const u4 v = *reinterpret_cast<const u4 *>(tile_in + r * lds_row + ch * 16);
+      const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+      for (int i = 0; i < per; ++i)
+        reinterpret_cast<_Float16 *>(tile_out + r * kLdsRow)[ch * per + i] =
+            (_Float16)(Elem<DT>::to_float(e[i]) * inv);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kRows * 16; i += 256) {
+    const int r = i / 16, ch = i % 16;
+    if (row0 + r < p.n)
+      *reinterpret_cast<u4 *>(reinterpret_cast<char *>(p.Xh) + ((size_t)ut * p.n + row0 + r) * 256 + ch * 16) =
+          *reinterpret_cast<const u4 *>(tile_out + r * kLdsRow + ch * 16);
+  }
+}
+
+// ---------------------------------------------------------------- gram
+// Block = 4 waves; wave w keeps the unit vectors of tokens a in [I*256 + 64w, +64) as
+// MFMA A-fragments and streams tokens b of the column chunk through LDS.  Lane (g, c)
+// of a 32-column tile holds, for token b = col + c, the similarities with 16 of the 32
+// tokens a of each row block; their signs relative to theta are packed by alignbit
+// into the bits of word (a / 32) of row b of G.
+__global__ __launch_bounds__(kGramThreads) void shallow_gram(ShallowParams p) {
+  typedef Mma<SPINDLE_F16> M;
+  __shared__ __attribute__((aligned(16))) char stage[2 * kStageBytes];
+  const int n = p.n;
+  const int nI = (n + kPanelRows - 1) / kPanelRows;
+  const int nJ = (n + kChunkCols - 1) / kChunkCols;
+  // blocks are dealt round-robin to the 8 XCDs: give each XCD one (ut, chunk) at a time
+  // and let it sweep the row panels, so the chunk is re-read from that XCD's L2
+  const int xcd = blockIdx.x & 7, s_ = blockIdx.x >> 3;
+  const int I = s_ % nI;
+  const int pj = (s_ / nI) * 8 + xcd;
+  if (pj >= p.UT * nJ) return;
+  const int ut = pj / nJ, J = pj % nJ;
+  const float theta = p.theta[ut / p.U];
+  const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
+  const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
+  const int arow0 = I * kPanelRows + 64 * wave;   // first token a of this wave
+
+  M::frag af[2][M::kSteps];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int a = arow0 + 32 * rb + c;
+#pragma unroll
+    for (int ks = 0; ks < M::kSteps; ++ks)
+      af[rb][ks] = a < n ? M::load(Xh + (size_t)a * 256, ks, g) : M::zero();
+  }
+
+  const int col_begin = J * kChunkCols;
+  const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
+  const int nstages = (col_end - col_begin + kStageCols - 1) / kStageCols;
+  const int tr = threadIdx.x >> 4, tc = threadIdx.x & 15;   // 16 rows x 16 chunks per pass
+  u4 regs[4];
+  auto fetch = [&](int b0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int b = b0 + q * 16 + tr;
+      u4 v = {0, 0, 0, 0};
+      if (b < n) v = *reinterpret_cast<const u4 *>(Xh + (size_t)b * 256 + tc * 16);
+      regs[q] = v;
+    }
+  };
+  auto stash = [&](char *dst) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *reinterpret_cast<u4 *>(dst + (q * 16 + tr) * kLdsRow + tc * 16) = regs[q];
+  };
+  fetch(col_begin);
+  stash(stage);
+  __syncthreads();
+
+  uint32_t *Gut = p.G + (size_t)ut * n * p.Wp;
+  for (int s = 0; s < nstages; ++s) {
+    const int b0 = col_begin + s * kStageCols;
+    const bool more = s + 1 < nstages;
+    if (more) fetch(b0 + kStageCols);
+    const char *lds = stage + (s & 1) * kStageBytes;
+#pragma unroll 1
+    for (int ct = 0; ct < kStageCols / 32; ++ct) {
+      const int bcol0 = b0 + ct * 32;
+      if (bcol0 >= n) break;
+      f16v acc[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rb][v] = -theta;
+      const char *brow = lds + (ct * 32 + c) * kLdsRow;
+#pragma unroll
+      for (int ks = 0; ks < M::kSteps; ++ks) {
+        const M::frag bf = M::load(brow, ks, g);
+        acc[0] = M::mma(af[0][ks], bf, acc[0]);
+        acc[1] = M::mma(af[1][ks], bf, acc[1]);
+      }
+      // sign bits -> bit v of q[rb]; adjacency = cosine - theta > 0
+      uint32_t sg0 = 0, sg1 = 0;
+      float mn = INFINITY;
+#pragma unroll
+      for (int v = 15; v >= 0; --v) {
+        sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(acc[0][v]), 31);
+        sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(acc[1][v]), 31);
+        mn = fminf(mn, fminf(fabsf(acc[0][v]), fabsf(acc[1][v])));
+      }
+      uint32_t q[2] = {~sg0 & 0xFFFFu, ~sg1 & 0xFFFFu};
+      const int b = bcol0 + c;
+      if (__any(mn < kGuard)) {
+        // some pair is too close to theta for fp16: decide it exactly later (or here
+        // when the list is full)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (fabsf(acc[rb][v]) < kGuard) {
+              const int a = arow0 + 32 * rb + mma_row(v, g);
+              q[rb] &= ~(1u << v);
+              if (a < n && b < n && a != b) {
+                const unsigned at = atomicAdd(p.fix_count, 1u);
+                if (at < p.fix_cap) {
+                  p.fix[at] = ((unsigned long long)ut << 48) | ((unsigned long long)b << 24) | (unsigned long long)a;
+                } else if (cos64(p, ut, a, b) > (double)theta) {
+                  q[rb] |= 1u << v;
+                }
+              }
+            }
+      }
+      if (bcol0 < arow0 + 64 && bcol0 + 32 > arow0) {   // tile touches the diagonal: G_aa = 1
+        const int i = b - arow0;
+        if (i >= 0 && i < 64 && ((i & 7) >> 2) == g) q[i >> 5] |= 1u << (4 * ((i & 31) >> 3) + (i & 3));
+      }
+      if (arow0 + 64 > n) {                             // tokens a beyond the sequence
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (arow0 + 32 * rb + mma_row(v, g) >= n) q[rb] &= ~(1u << v);
+      }
+      const uint32_t own = q[0] | (q[1] << 16);
+      const uint32_t other = __shfl_xor(own, 32);
+      const uint32_t mine = (own >> (16 * g)) & 0xFFFFu, theirs = (other >> (16 * g)) & 0xFFFFu;
+      const uint32_t word = (spread_nibbles(mine) << (4 * g)) | (spread_nibbles(theirs) << (4 * (1 - g)));
+      if (b < n) Gut[(size_t)b * p.Wp + (arow0 >> 5) + g] = word;
+    }
+    if (more) stash(stage + ((s + 1) & 1) * kStageBytes);
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------- exact fix-up
+__global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
+  unsigned count = *p.fix_count;
+  if (count > p.fix_cap) count = p.fix_cap;
+  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) {
+    const unsigned long long e = p.fix[i];
+    const int ut = (int)(e >> 48), b = (int)((e >> 24) & 0xFFFFFFu), a = (int)(e & 0xFFFFFFu);
+    if (cos64(p, ut, a, b) > (double)p.theta[ut / p.U])
+      atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+  }
+}
+
+// ---------------------------------------------------------------- greedy merge
+// Exact parallel form of the loop of Alg. 1.  With key(v) = (degree among remaining
+// tokens, lower index first), the sequential loop always takes the remaining token of
+// largest key.  A token whose key is the largest within two hops cannot lose a
+// neighbour before it is taken itself (whoever removed one would be within two hops and
+// would have needed a larger key), and tokens taken meanwhile are three or more hops away,
+// so they do not touch its neighbourhood.  Each round therefore takes every two-hop
+// maximum at once; sorting all picks by their key at pick time (which strictly decreases
+// along the sequential loop) restores the codebook order.
+
+__device__ __forceinline__ bool group_barrier(const ShallowParams &p, int group, unsigned &target) {
+  __shared__ int ok_s;
+  __threadfence();
+  __syncthreads();
+  if (p.blocks_per_group == 1) return true;
+  target += (unsigned)p.blocks_per_group;
+  if (threadIdx.x == 0) {
+    unsigned *bar = p.bar + group;
+    __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0;
+    int ok = 1;
+    while (__hip_atomic_load(bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      __builtin_amdgcn_s_sleep(4);
+      if (++spins > p.spin_limit) { ok = 0; break; }
+    }
+    if (!ok) atomicExch(p.err, 1);
+    ok_s = ok;
+  }
+  __syncthreads();
+  __threadfence();
+  return ok_s != 0;
+}
+
+template <typename F>
+__device__ __forceinline__ void for_each_neighbour(const uint32_t *row, int Wp, F f) {
+  for (int w4 = lane_id(); w4 < Wp / 4; w4 += kWave) {
+    const u4 q = reinterpret_cast<const u4 *>(row)[w4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t bits = q[j];
+      while (bits) {
+        const int t = __builtin_ctz(bits);
+        bits &= bits - 1;
+        f((w4 * 4 + j) * 32 + t);
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t x = __shfl_xor(v, o);
+    v = x > v ? x : v;
+  }
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+template <int DT>
+__device__ __forceinline__ void emit_code(const ShallowParams &p, int ut, int vert, int r) {
+  typedef typename Elem<DT>::type T;
+  const int t = ut / p.U, u = ut % p.U;
+  const T *src = reinterpret_cast<const T *>(x_row(p, ut, vert));
+  T *dst = reinterpret_cast<T *>(p.C[t]) + ((size_t)u * p.cap + r) * kHeadDim;
+  const double m = p.m64[(size_t)ut * p.n + vert];
+  for (int d = lane_id(); d < kHeadDim; d += kWave) {
+    const double x = (double)Elem<DT>::to_float(src[d]);
+    dst[d] = Elem<DT>::from_float(m > 0.0 ? (float)(x / m) : 0.f);
+  }
+}
+
+__global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) {
+  __shared__ int sh_cnt;
+  __shared__ uint32_t sh_keys[1024];
+  const int group = blockIdx.x / p.blocks_per_group, brank = blockIdx.x % p.blocks_per_group;
+  const int lane = lane_id();
+  const int gw = brank * (kMergeThreads / 64) + (threadIdx.x >> 6);
+  const int GW = p.blocks_per_group * (kMergeThreads / 64);
+  const int gt = brank * kMergeThreads + threadIdx.x, GT = p.blocks_per_group * kMergeThreads;
+  const int n = p.n, Wp = p.Wp;
+  unsigned target = 0;
+
+  for (int ut = group; ut < p.UT; ut += p.n_groups) {
+    const uint32_t *G = p.G + (size_t)ut * n * Wp;
+    int *deg = p.deg + (size_t)ut * n, *status = p.status + (size_t)ut * n, *slot = p.slot + (size_t)ut * n;
+    int *cand = p.cand + (size_t)ut * n, *dying = p.dying + (size_t)ut * n;
+    int *pick_vert = p.pick_vert + (size_t)ut * n, *rank = p.rank + (size_t)ut * n;
+    int *rank_vert = p.rank_vert + (size_t)ut * n;
+    uint32_t *key = p.key + (size_t)ut * n, *m1 = p.m1 + (size_t)ut * n, *pick_key = p.pick_key + (size_t)ut * n;
+    int *cnt = p.counters + (size_t)ut * kCounters;
+
+    // degrees, Eq. 10
+    for (int v = gw; v < n; v += GW) {
+      int c = 0;
+      for (int w4 = lane; w4 < Wp / 4; w4 += kWave) {
+        const u4 q = reinterpret_cast<const u4 *>(G + (size_t)v * Wp)[w4];
+        c += __popc(q[0]) + __popc(q[1]) + __popc(q[2]) + __popc(q[3]);
+      }
+      c = wave_sum(c);
+      if (lane == 0) {
+        deg[v] = c; status[v] = 0; slot[v] = -1;
+        if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = c;
+      }
+    }
+    if (!group_barrier(p, group, target)) return;
+
+    for (int round = 0;; ++round) {
+      // keys of the remaining tokens; count them
+      int alive = 0;
+      for (int v = gt; v < n; v += GT) {
+        uint32_t k = 0;
+        if (status[v] == 0) { k = ((uint32_t)deg[v] << 16) | (uint32_t)(0xFFFF - v); ++alive; }
+        key[v] = k;
+      }
+      if (threadIdx.x == 0) sh_cnt = 0;
+      __syncthreads();
+      alive = wave_sum(alive);
+      if (lane == 0 && alive) atomicAdd(&sh_cnt, alive);
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        if (sh_cnt) atomicAdd(&cnt[round & 1], sh_cnt);
+        if (brank == 0) { cnt[(round & 1) ^ 1] = 0; cnt[C_CAND] = 0; cnt[C_DYING] = 0; }
+      }
+      if (!group_barrier(p, group, target)) return;
+      if (__hip_atomic_load(&cnt[round & 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) break;
+
+      // one-hop maxima
+      for (int v = gw; v < n; v += GW) {
+        if (status[v] != 0) continue;
+        uint32_t m = 0;
+        for_each_neighbour(G + (size_t)v * Wp, Wp, [&](int b) { const uint32_t k = key[b]; m = k > m ? k : m; });
+        m = wave_max(m);
+        if (lane == 0) {
+          m1[v] = m;
+          if (m == key[v]) cand[atomicAdd(&cnt[C_CAND], 1)] = v;
+        }
+      }
+      if (!group_barrier(p, group, target)) return;
+
+      // two-hop maxima are picked; their remaining neighbours get the pick's slot
+      const int ncand = __hip_atomic_load(&cnt[C_CAND], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int i = gw; i < ncand; i += GW) {
+        const int uvert = cand[i];
+        const uint32_t ku = key[uvert];
+        const uint32_t *row = G + (size_t)uvert * Wp;
+        uint32_t m = 0;
+        for_each_neighbour(row, Wp, [&](int b) {
+          if (key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; }
+        });
+        m = wave_max(m);
+        if (m != ku) continue;
+        int s = 0;
+        if (lane == 0) {
+          s = atomicAdd(&cnt[C_PICKS], 1);
+          pick_key[s] = ku;
+          pick_vert[s] = uvert;
+        }
+        s = __shfl(s, 0);
+        for_each_neighbour(row, Wp, [&](int b) {
+          if (key[b] != 0) {
+            slot[b] = s;
+            status[b] = 1;
+            dying[atomicAdd(&cnt[C_DYING], 1)] = b;
+          }
+        });
+      }
+      if (!group_barrier(p, group, target)) return;
+
+      // removed tokens no longer count towards their neighbours' degrees (Eq. 13)
+      const int ndying = __hip_atomic_load(&cnt[C_DYING], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int i = gw; i < ndying; i += GW) {
+        const int v = dying[i];
+        for_each_neighbour(G + (size_t)v * Wp, Wp, [&](int w) {
+          if (status[w] == 0) atomicSub(&deg[w], 1);
+        });
+      }
+      if (!group_barrier(p, group, target)) return;
+    }
+
+    // codebook order: rank of each pick among all picks by decreasing key
+    const int P = __hip_atomic_load(&cnt[C_PICKS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int s0 = 0; s0 < P; s0 += GT) {
+      const int s = s0 + gt;
+      const uint32_t ks = s < P ? pick_key[s] : 0xFFFFFFFFu;
+      int r = 0;
+      for (int base = 0; base < P; base += 1024) {
+        __syncthreads();
+        for (int j = threadIdx.x; j < 1024; j += kMergeThreads) sh_keys[j] = base + j < P ? pick_key[base + j] : 0u;
+        __syncthreads();
+        const int lim = P - base < 1024 ? P - base : 1024;
+        for (int j = 0; j < lim; ++j) r += sh_keys[j] > ks;
+      }
+      if (s < P) { rank[s] = r; rank_vert[r] = pick_vert[s]; }
+    }
+    if (!group_barrier(p, group, target)) return;
+
+    const int t = ut / p.U, u = ut % p.U;
+    const int stored = P < p.cap ? P : p.cap;
+    if (gt == 0) {
+      p.n_codes[t][u] = stored;
+      if (p.n_found[t]) p.n_found[t][u] = P;
+    }
+    for (int v = gt; v < n; v += GT) {
+      const int r = rank[slot[v]];
+      p.ref[t][(size_t)u * n + v] = r;
+      if (r >= p.cap) p.ovf[atomicAdd(p.ovf_count, 1u)] = ((uint32_t)ut << 16) | (uint32_t)v;
+    }
+    for (int r = gw; r < stored; r += GW) {
+      const int vert = rank_vert[r];
+      if (p.dtype == SPINDLE_F16) emit_code<SPINDLE_F16>(p, ut, vert, r);
+      else if (p.dtype == SPINDLE_BF16) emit_code<SPINDLE_BF16>(p, ut, vert, r);
+      else emit_code<SPINDLE_F32>(p, ut, vert, r);
+    }
+    if (!group_barrier(p, group, target)) return;
+  }
+}
+
+// ---------------------------------------------------------------- codebook cap
+// One block per token whose entry was cut: highest cosine (Eq. 4, double precision)
+// among the stored entries, lowest entry index on ties.
+__global__ __launch_bounds__(256) void shallow_overflow(ShallowParams p) {
+  __shared__ double sh_v[256];
+  __shared__ int sh_j[256];
+  const unsigned count = *p.ovf_count;
+  for (unsigned i = blockIdx.x; i < count; i += gridDim.x) {
+    const uint32_t e = p.ovf[i];
+    const int ut = (int)(e >> 16), a = (int)(e & 0xFFFFu);
+    const int *rank_vert = p.rank_vert + (size_t)ut * p.n;
+    double bv = -INFINITY;
+    int bj = 0x7FFFFFFF;
+    for (int j = threadIdx.x; j < p.cap; j += 256) {
+      const double cv = cos64(p, ut, a, rank_vert[j]);
+      if (cv > bv) { bv = cv; bj = j; }
+    }
+    sh_v[threadIdx.x] = bv;
+    sh_j[threadIdx.x] = bj;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+      if (threadIdx.x < o) {
+        const double ov = sh_v[threadIdx.x + o];
+        const int oj = sh_j[threadIdx.x + o];
+        if (ov > sh_v[threadIdx.x] || (ov == sh_v[threadIdx.x] && oj < sh_j[threadIdx.x])) {
+          sh_v[threadIdx.x] = ov;
+          sh_j[threadIdx.x] = oj;
+        }
+      }
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) p.ref[ut / p.U][(size_t)(ut % p.U) * p.n + a] = sh_j[0];
+    __syncthreads();
+  }
+}
+
+__global__ void fill_u32(uint32_t *dst, size_t count, uint32_t v) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = v;
+}
+
+// Copies the rows of G without their padding words.
+__global__ void export_adj(const uint32_t *G, uint32_t *out, size_t rows, int Wp, int W) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < rows * W; i += (size_t)gridDim.x * blockDim.x)
+    out[i] = G[(i / W) * Wp + (i % W)];
+}
+
+// ---------------------------------------------------------------- host side
+struct ShallowLayout {
+  size_t bytes;
+};
+
+size_t carve(ShallowParams &p, void *ws, int UT, int n) {
+  Carver cv(ws);
+  const size_t N = (size_t)UT * n;
+  p.Wp = ((n + 255) / 256) * 8;
+  p.Xh = cv.take<_Float16>(N * kHeadDim);
+  p.m64 = cv.take<double>(N);
+  p.G = cv.take<uint32_t>(N * p.Wp);
+  p.deg = cv.take<int>(N);
+  p.status = cv.take<int>(N);
+  p.slot = cv.take<int>(N);
+  p.cand = cv.take<int>(N);
+  p.dying = cv.take<int>(N);
+  p.pick_vert = cv.take<int>(N);
+  p.rank = cv.take<int>(N);
+  p.rank_vert = cv.take<int>(N);
+  p.key = cv.take<uint32_t>(N);
+  p.m1 = cv.take<uint32_t>(N);
+  p.pick_key = cv.take<uint32_t>(N);
+  p.ovf = cv.take<uint32_t>(N);
+  p.fix_cap = (unsigned)(N * 8 > (1u << 20) ? (N * 8 < (1u << 26) ? N * 8 : (1u << 26)) : (1u << 20));
+  p.fix = cv.take<unsigned long long>(p.fix_cap);
+  // everything that must start at zero sits together at the end
+  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + UT);
+  p.fix_count = reinterpret_cast<unsigned *>(p.counters ? p.counters + (size_t)UT * kCounters : nullptr);
+  p.ovf_count = p.fix_count ? p.fix_count + 1 : nullptr;
+  p.err = p.counters ? p.counters + (size_t)UT * kCounters + 2 : nullptr;
+  p.bar = reinterpret_cast<unsigned *>(p.counters ? p.counters + (size_t)UT * kCounters + 4 : nullptr);
+  return cv.total();
+}
+
+struct DeviceShape {
+  int cus = 0, merge_blocks_per_cu = 0;
+};
+
+spindle_status device_shape(DeviceShape &out) {
+  static DeviceShape cache[64];
+  int dev = 0;
+  SPINDLE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "device index %d out of range", dev);
+  if (cache[dev].cus == 0) {
+    int cus = 0, occ = 0;
+    SPINDLE_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    SPINDLE_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, shallow_merge, kMergeThreads, 0));
+    if (cus < 1 || occ < 1) SPINDLE_FAIL(SPINDLE_ERR_HIP, "occupancy query returned %d CUs, %d blocks/CU", cus, occ);
+    cache[dev].merge_blocks_per_cu = occ > 4 ? 4 : occ;
+    cache[dev].cus = cus;
+  }
+  out = cache[dev];
+  return SPINDLE_OK;
+}
+
+}  // namespace
+}  // namespace spindle
+
+using namespace spindle;
+
+extern "C" spindle_status spindle_shallow_workspace_bytes(const spindle_kv_desc *desc, int32_t n_tensors,
+                                                          size_t *bytes) {
+  spindle_status s = check_desc(desc);
+  if (s != SPINDLE_OK) return s;
+  if (!bytes) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "bytes is NULL");
+  if (n_tensors < 1 || n_tensors > 2) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "n_tensors must be 1 or 2");
+  if (desc->seq_len > 65535) SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "seq_len must be <= 65535 for the codebook path");
+  ShallowParams p;
+  *bytes = carve(p, nullptr, desc->batch * desc->n_kv_heads * n_tensors, desc->seq_len);
+  return SPINDLE_OK;
+}
+
+extern "C" spindle_status spindle_compress_shallow(
+    const spindle_kv_desc *desc, const void *K, const void *V, float theta_k, float theta_v,
+    int32_t max_codes, void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v, int32_t *n_found_k,
+    int32_t *n_found_v, int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v, uint32_t *adj_k,
+    uint32_t *adj_v, int32_t *deg_k, int32_t *deg_v, void *workspace, size_t workspace_bytes,
+    void *stream) {
+  const int T = (K ? 1 : 0) + (V ? 1 : 0);
+  if (T == 0) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "at least one of K, V is required");
+  size_t need = 0;
+  spindle_status s = spindle_shallow_workspace_bytes(desc, T, &need);
+  if (s != SPINDLE_OK) return s;
+  if (max_codes < 1) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "max_codes must be >= 1");
+  if (K && (!Ck || !n_codes_k || !ref_k || !mag_k)) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "K given but one of Ck, n_codes_k, ref_k, mag_k is NULL");
+  if (V && (!Cv || !n_codes_v || !ref_v || !mag_v)) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "V given but one of Cv, n_codes_v, ref_v, mag_v is NULL");
+  if (!(theta_k == theta_k) || !(theta_v == theta_v)) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "thresholds must not be NaN");
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+  const uintptr_t al = reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V) |
+                       reinterpret_cast<uintptr_t>(Ck) | reinterpret_cast<uintptr_t>(Cv);
+  if (al & 15) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int U = desc->batch * desc->n_kv_heads, n = desc->seq_len;
+  ShallowParams p;
+  memset(&p, 0, sizeof(p));
+  p.dtype = desc->dtype; p.U = U; p.UT = U * T; p.n = n;
+  p.cap = max_codes;
+  carve(p, workspace, p.UT, n);
+  int t = 0;
+  uint32_t *adj[2] = {nullptr, nullptr};
+  if (K) {
+    p.X[t] = static_cast<const char *>(K); p.theta[t] = theta_k; p.C[t] = static_cast<char *>(Ck);
+    p.n_codes[t] = n_codes_k; p.n_found[t] = n_found_k; p.ref[t] = ref_k; p.mag[t] = mag_k;
+    adj[t] = adj_k; p.deg_out[t] = deg_k; ++t;
+  }
+  if (V) {
+    p.X[t] = static_cast<const char *>(V); p.theta[t] = theta_v; p.C[t] = static_cast<char *>(Cv);
+    p.n_codes[t] = n_codes_v; p.n_found[t] = n_found_v; p.ref[t] = ref_v; p.mag[t] = mag_v;
+    adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
+  }
+  DeviceShape ds;
+  s = device_shape(ds);
+  if (s != SPINDLE_OK) return s;
+  const int resident = ds.cus * ds.merge_blocks_per_cu;
+  int bpg = resident / p.UT;
+  if (bpg < 1) bpg = 1;
+  const int useful = (n + 15) / 16;          // no more than one wave per 4 rows
+  if (bpg > useful) bpg = useful > 0 ? useful : 1;
+  if (bpg > 64) bpg = 64;
+  p.blocks_per_group = bpg;
+  p.n_groups = resident / bpg < p.UT ? resident / bpg : p.UT;
+  p.spin_limit = 50u * 1000u * 1000u;
+
+  // zero: counters, list counts, error flag, barriers; codebooks
+  const size_t nzero = (size_t)p.UT * kCounters + 4 + p.UT;
+  hipLaunchKernelGGL(fill_u32, dim3(64), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.counters), nzero, 0u);
+  for (int i = 0; i < T; ++i)   // -1 marks "not finished": stays if a bounded wait expires
+    hipLaunchKernelGGL(fill_u32, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.n_codes[i]), (size_t)U, 0xFFFFFFFFu);
+  const size_t cwords = (size_t)U * max_codes * kHeadDim * dtype_bytes(p.dtype) / 4;
+  for (int i = 0; i < T; ++i)
+    hipLaunchKernelGGL(fill_u32, dim3(1024), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.C[i]), cwords, 0u);
+
+  const dim3 pgrid((n + 63) / 64, p.UT);
+  if (p.dtype == SPINDLE_F16) hipLaunchKernelGGL(shallow_prep<SPINDLE_F16>, pgrid, dim3(256), 0, st, p);
+  else if (p.dtype == SPINDLE_BF16) hipLaunchKernelGGL(shallow_prep<SPINDLE_BF16>, pgrid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(shallow_prep<SPINDLE_F32>, pgrid, dim3(256), 0, st, p);
+
+  const int nI = (n + kPanelRows - 1) / kPanelRows, nJ = (n + kChunkCols - 1) / kChunkCols;
+  const int pairs8 = (p.UT * nJ + 7) / 8;
+  hipLaunchKernelGGL(shallow_gram, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p);
+  hipLaunchKernelGGL(shallow_fixup, dim3(1024), dim3(256), 0, st, p);
+  SPINDLE_HIP(hipGetLastError());
+
+  void *args[] = {&p};
+  SPINDLE_HIP(hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&shallow_merge),
+                                         dim3(p.n_groups * p.blocks_per_group), dim3(kMergeThreads), args, 0, st));
+  hipLaunchKernelGGL(shallow_overflow, dim3(2048), dim3(256), 0, st, p);
+
+  const int W = (n + 31) / 32;
+  for (int i = 0; i < T; ++i) {
+    if (adj[i])
+      hipLaunchKernelGGL(export_adj, dim3(1024), dim3(256), 0, st, p.G + (size_t)i * U * n * p.Wp, adj[i],
+                         (size_t)U * n, p.Wp, W);
+  }
+  SPINDLE_HIP(hipGetLastError());
+  return SPINDLE_OK;
+}

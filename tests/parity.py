@@ -1,0 +1,156 @@
+"""Helpers shared by the GPU parity tests: run one layer through the HIP library and
+through the CPU oracle and compare.  The oracle never sees a value produced by the
+HIP path; expected values come from the oracle alone."""
+from __future__ import annotations
+
+import numpy as np
+
+from paper_2507_06517_amd import workloads as wl
+
+# Relative tolerance on floating-point outputs (fp16/bf16/fp32 inputs, fp32 accumulation).
+RTOL = 1e-3
+# Relative half-width of the band around the k-th largest pooled score inside which the
+# fp32 GPU scores and the fp64 oracle scores may order two tokens differently.
+SELECT_BAND = 2e-5
+
+ULP = {"f32": 2.0 ** -23, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}
+
+
+def scale_of(d):
+    return float(np.float32(1.0 / np.sqrt(d)))
+
+
+# ------------------------------------------------------------------ eviction path
+
+def oracle_deep(orc, L: wl.Layer, budget=None, norm=0, threads=16):
+    K = wl.to_f64(L.K, L.dtype)
+    Q = wl.to_f64(L.Qw, L.dtype)
+    return orc.deep_layer(Q, K, L.group_size, scale_of(L.head_dim), L.pool, budget or L.budget, norm, threads)
+
+
+def gpu_deep(L: wl.Layer, budget=None, norm=0, budgets=None, out_stride=None):
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    K, V, Q = (sb.to_device(x, L.dtype) for x in (L.K, L.V, L.Qw))
+    bt = torch.tensor(budgets, dtype=torch.int32, device="cuda") if budgets is not None else None
+    kept, Ko, Vo, sc = sb.compress_deep(K, V, Q, L.group_size, L.dtype, L.window, L.pool, budget or L.budget,
+                                        scale=scale_of(L.head_dim), norm=norm, budgets=bt, out_stride=out_stride)
+    torch.cuda.synchronize()
+    return (kept.cpu().numpy(), sb.to_host_bits(Ko, L.dtype), sb.to_host_bits(Vo, L.dtype),
+            sc.cpu().numpy().astype(np.float64))
+
+
+def lowest_index_topk(p, k):
+    """Indices of the k largest entries of p, ties to the lowest index, ascending."""
+    return np.sort(np.lexsort((np.arange(len(p)), -p))[:k])
+
+
+def check_deep_unit(p64, kept64, p_gpu, kept_gpu, lw, l, report):
+    """One unit.  Floats within RTOL; kept indices identical to the oracle's unless some
+    token's oracle score lies within SELECT_BAND of the selection threshold (then the
+    GPU choice must still be a valid top-k up to that band, and is counted in report)."""
+    lc = l - lw
+    n_keep = len(kept64)
+    k = n_keep - lw
+    np.testing.assert_allclose(p_gpu[:lc], p64, rtol=RTOL, atol=1e-30)
+    g = kept_gpu[:n_keep]
+    assert np.all(kept_gpu[n_keep:] == -1)
+    assert g[k:].tolist() == list(range(lc, l)), "window tokens must all be kept"
+    assert np.all(np.diff(g) > 0), "kept positions ascending and unique"
+    # the selection is exactly the lowest-index top-k of the library's own scores
+    assert np.array_equal(g[:k], lowest_index_topk(p_gpu[:lc].astype(np.float32), k))
+    if k == 0 or k >= lc:
+        assert np.array_equal(g, kept64)
+        return
+    T = np.sort(p64)[lc - k]
+    band = (np.abs(p64 - T) <= SELECT_BAND * T) & (p64 != T)
+    if not band.any():
+        assert np.array_equal(g, kept64), "kept indices differ from the oracle outside any ambiguity band"
+        return
+    report["ambiguous_units"] = report.get("ambiguous_units", 0) + 1
+    sel = np.zeros(lc, bool)
+    sel[g[:k]] = True
+    assert sel[p64 > T * (1 + SELECT_BAND)].all()
+    assert not sel[p64 < T * (1 - SELECT_BAND)].any()
+    diff = np.setxor1d(g, kept64)
+    report["swapped_tokens"] = report.get("swapped_tokens", 0) + len(diff)
+    assert band[diff[diff < lc]].all() if len(diff) else True
+
+
+def check_deep_layer(orc, L: wl.Layer, budget=None, norm=0):
+    budget = budget or L.budget
+    p64, kept64 = oracle_deep(orc, L, budget, norm)
+    kept, Ko, Vo, sc = gpu_deep(L, budget, norm)
+    report = {}
+    B, H, l, d = L.K.shape
+    for b in range(B):
+        for h in range(H):
+            check_deep_unit(p64[b, h], kept64[b, h], sc[b, h], kept[b, h], L.window, l, report)
+            g = kept[b, h]
+            g = g[g >= 0]
+            assert np.array_equal(Ko[b, h, :len(g)], L.K[b, h][g]), "gathered keys must be bit copies"
+            assert np.array_equal(Vo[b, h, :len(g)], L.V[b, h][g]), "gathered values must be bit copies"
+            assert not Ko[b, h, len(g):].any()
+    return report
+
+
+# ------------------------------------------------------------------ codebook path
+
+def gpu_shallow(L: wl.Layer, cap=None, debug=True, tensors=("k", "v")):
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    K = sb.to_device(L.K, L.dtype) if "k" in tensors else None
+    V = sb.to_device(L.V, L.dtype) if "v" in tensors else None
+    out = sb.compress_shallow(K, V, L.dtype, L.theta_k, L.theta_v, cap or L.max_codes, debug=debug)
+    torch.cuda.synchronize()
+    res = {}
+    for k, v in out.items():
+        if k.startswith("C_"):
+            res[k] = sb.to_host_bits(v, L.dtype)
+        elif k.startswith("adj_"):
+            res[k] = v.cpu().numpy().view(np.uint32)
+        else:
+            res[k] = v.cpu().numpy()
+    return res
+
+
+def check_codebook_vectors(C_gpu_bits, C64, dtype):
+    got = wl.to_f64(C_gpu_bits, dtype)
+    err = np.abs(got - C64)
+    tol = np.maximum(np.abs(C64) * max(RTOL, ULP[dtype]), 1e-7 if dtype == "f32" else 2.0 ** -24)
+    assert np.all(err <= tol), f"codebook entry off by {err.max()}"
+
+
+def check_shallow_unit(orc, X64, theta, cap, dtype, g, t, b, h, full_adj=True):
+    """Compare unit (b, h) of tensor t ('k'|'v') of the GPU result g with the oracle."""
+    o = orc.shallow_unit(X64, float(np.float32(theta)), cap)
+    n = X64.shape[0]
+    if full_adj and f"adj_{t}" in g:
+        assert np.array_equal(g[f"adj_{t}"][b, h], o["G"]), "adjacency bits differ"
+        assert np.array_equal(g[f"deg_{t}"][b, h], o["deg"]), "degrees differ"
+    assert g[f"n_found_{t}"][b, h] == o["n_codes_uncapped"]
+    assert g[f"n_codes_{t}"][b, h] == o["n_codes"]
+    assert np.array_equal(g[f"ref_{t}"][b, h], o["ref"]), "code assignment differs"
+    assert np.array_equal(g[f"mag_{t}"][b, h], o["mag"].astype(np.float32)), "magnitudes differ"
+    nc = o["n_codes"]
+    check_codebook_vectors(g[f"C_{t}"][b, h, :nc], o["C"], dtype)
+    assert not g[f"C_{t}"][b, h, nc:].any(), "rows past n_codes must be zero"
+    return o
+
+
+def check_shallow_layer(orc, L: wl.Layer, cap=None, units=None, tensors=("k", "v"), g=None):
+    cap = cap or L.max_codes
+    if g is None:
+        g = gpu_shallow(L, cap, tensors=tensors)
+    B, H, l, d = L.K.shape
+    todo = units if units is not None else [(b, h) for b in range(B) for h in range(H)]
+    from concurrent.futures import ThreadPoolExecutor
+    jobs = [(t, b, h) for t in tensors for (b, h) in todo]
+
+    def run(job):
+        t, b, h = job
+        X = wl.to_f64((L.K if t == "k" else L.V)[b, h], L.dtype)
+        return check_shallow_unit(orc, X, L.theta_k if t == "k" else L.theta_v, cap, L.dtype, g, t, b, h)
+
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        return list(ex.map(run, jobs)), g

@@ -1,0 +1,86 @@
+"""GPU parity of the codebook path against the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+
+from paper_2507_06517_amd import workloads as wl
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_fp32_with_cap(oracle):
+    L = wl.config1(0)
+    res, g = parity.check_shallow_layer(oracle, L)
+    assert any(o["n_codes_uncapped"] > L.max_codes for o in res)      # the cap path is exercised
+    parity.check_shallow_layer(oracle, L, cap=512)                      # and the uncapped one
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("l", [1, 31, 33, 257, 300, 1100])
+def test_small_ragged(oracle, dtype, l):
+    L = wl.small_random(7, dtype, B=1, H=2, l=l, lw=1, cap=max(1, l // 5), n_centroids=6, noise_frac=0.3)
+    parity.check_shallow_layer(oracle, L)
+    parity.check_shallow_layer(oracle, L, cap=l)
+
+
+def test_threshold_extremes_and_single_tensor(oracle):
+    L = wl.small_random(8, "f16", B=1, H=1, l=200, lw=1, cap=200)
+    L.theta_k, L.theta_v = 1.0, -1.5
+    res, g = parity.check_shallow_layer(oracle, L)
+    assert g["n_codes_k"][0, 0] == 200 and g["n_codes_v"][0, 0] == 1
+    L.theta_k = 0.98
+    parity.check_shallow_layer(oracle, L, tensors=("k",))
+    parity.check_shallow_layer(oracle, L, tensors=("v",))
+
+
+def test_knife_edge_pairs_are_decided_exactly(oracle):
+    # a random-walk drift gives a continuum of similarities around theta: many pairs fall
+    # inside the fp16 guard band and must still match the double-precision decision
+    L = wl.small_random(9, "f16", B=1, H=2, l=1500, lw=1, cap=1500, n_centroids=3, noise_frac=0.0,
+                        drift_sigma=0.004)
+    res, g = parity.check_shallow_layer(oracle, L)
+    X = wl.to_f64(L.K[0, 0], "f16")
+    Xn = X / np.linalg.norm(X, axis=1, keepdims=True)
+    S = Xn @ Xn.T
+    assert (np.abs(S - L.theta_k) < 1e-3).sum() > 1000                # the band is well populated
+
+
+def test_duplicates_and_zero_vectors(oracle):
+    L = wl.small_random(10, "f16", B=1, H=1, l=400, lw=1, cap=400)
+    L.K[0, 0, 100:150] = L.K[0, 0, 7]            # exact duplicates
+    L.K[0, 0, 200:203] = 0                        # zero vectors
+    L.V[0, 0, 5] = 0
+    res, g = parity.check_shallow_layer(oracle, L)
+    assert len(set(g["ref_k"][0, 0, 100:150].tolist() + [g["ref_k"][0, 0, 7]])) == 1
+
+
+def test_config2(oracle):
+    res, g = parity.check_shallow_layer(oracle, wl.config2(0))
+    print("config2 codes", [o["n_codes_uncapped"] for o in res])
+
+
+def test_reconstruct(oracle):
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    L = wl.small_random(11, "f16", B=1, H=2, l=500, lw=1, cap=500)
+    K = sb.to_device(L.K, "f16")
+    out = sb.compress_shallow(K, None, "f16", L.theta_k, L.theta_v, 500)
+    R = sb.reconstruct(out["C_k"], out["ref_k"], out["mag_k"], "f16")
+    torch.cuda.synchronize()
+    R = R.cpu().numpy().astype(np.float64)
+    for h in range(2):
+        X = wl.to_f64(L.K[0, h], "f16")
+        o = oracle.shallow_unit(X, float(np.float32(L.theta_k)), 500)
+        want = oracle.reconstruct(o["C"], o["ref"], o["mag"])
+        np.testing.assert_allclose(R[0, h], want, rtol=2e-3, atol=1e-3)
+        c = np.einsum("ad,ad->a", R[0, h], X) / (np.linalg.norm(R[0, h], axis=1) * np.linalg.norm(X, axis=1))
+        assert np.all(c > L.theta_k - 1e-3)
+
+
+def test_deterministic_across_runs():
+    L = wl.config2(2)
+    a = parity.gpu_shallow(L)
+    b = parity.gpu_shallow(L)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
