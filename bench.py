@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Throughput of the prefill-time KV reduction pass on one MI355X.
+
+One step = one pass of the whole hot path over one layer of the 32k-context
+workload (benchmark configs[3]: Mistral-7B-shaped, 8 KV heads x 4 query heads,
+head_dim 128, seq_len 32768, fp16, clustered keys/values with drift):
+  spindle_compress_deep    (window 64, pool 7, budget 2048)  and
+  spindle_compress_shallow (K and V, theta 0.98 / 0.95, codebook cap 2048).
+Inputs are resident in HBM before the timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2500.0      # MI355X dense fp16 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(L, wl, sample_n=12288):
+    """The oracle as it stands, timed on this host: the eviction path on one full unit and
+    the codebook path on the first `sample_n` tokens of one K unit; scaled to a whole layer
+    (eviction linear in units, codebook quadratic in tokens and linear in units)."""
+    import oracle
+    oracle.lib()
+    d = L.head_dim
+    scale = float(np.float32(1.0 / np.sqrt(d)))
+    K0 = wl.to_f64(L.K[0, 0], L.dtype)
+    Q0 = wl.to_f64(L.Qw[0, :L.group_size], L.dtype)
+    t0 = time.perf_counter()
+    oracle.deep_unit(Q0, K0, scale, L.pool, L.budget)
+    t_deep_unit = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.shallow_unit(K0[:sample_n], float(np.float32(L.theta_k)), min(L.max_codes, sample_n))
+    t_sh_sample = time.perf_counter() - t0
+    units = L.batch * L.n_kv_heads
+    t_layer = units * t_deep_unit + 2 * units * t_sh_sample * (L.seq_len / sample_n) ** 2
+    return {"value": L.batch * L.seq_len / t_layer, "unit": "tokens/s/layer", "cores": 1, "kind": "oracle",
+            "sample": f"deep: 1 of {units} units in full ({t_deep_unit:.2f} s); shallow: first {sample_n} tokens of "
+                      f"1 of {2 * units} K/V units ({t_sh_sample:.2f} s), scaled by units and by (l/{sample_n})^2"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--seq-len", type=int, default=32768)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "shallow_gram_config4_traffic.json"))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2507_06517_amd import binding as sb, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sb.lib()
+    torch.cuda.set_device(0)
+
+    L = wl.config4(0, seq_len=args.seq_len)
+    K, V, Q = (sb.to_device(x, L.dtype) for x in (L.K, L.V, L.Qw))
+    deep = sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, want_scores=False)
+    shallow = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        deep.run(K, V, Q)
+        shallow.run(K, V)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: whole-step wall time, and per-kernel HIP events on the launch stream
+    sb.spindle_profile(True)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[3 * i].record(stream)
+        deep.run(K, V, Q)
+        ev[3 * i + 1].record(stream)
+        shallow.run(K, V)
+        ev[3 * i + 2].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    recs = sb.spindle_profile_read()
+    sb.spindle_profile(False)
+
+    ms_step = wall * 1e3 / args.steps
+    ms_deep = float(np.mean([ev[3 * i].elapsed_time(ev[3 * i + 1]) for i in range(args.steps)]))
+    ms_shallow = float(np.mean([ev[3 * i + 1].elapsed_time(ev[3 * i + 2]) for i in range(args.steps)]))
+    per_kernel = {}
+    for name, ms in recs:
+        per_kernel.setdefault(name, []).append(ms)
+    kernel_ms = {k: float(np.mean(v)) for k, v in per_kernel.items()}
+
+    n_codes = {t: shallow.out[f"n_found_{t}"].cpu().numpy().ravel().tolist() for t in ("k", "v")}
+    assert min(shallow.out["n_codes_k"].min().item(), shallow.out["n_codes_v"].min().item()) >= 1, \
+        "codebook construction did not finish"
+
+    tokens = L.batch * L.seq_len
+    units = L.batch * L.n_kv_heads
+    # dominant kernel: the similarity tiles.  Algorithmic work = each unordered token pair
+    # once: n^2/2 pairs x 128 multiply-adds x 2 flop, per (unit, K|V).
+    gram_flop = 2 * units * (L.seq_len ** 2 / 2) * L.head_dim * 2
+    gram_ms = kernel_ms.get("shallow_gram", float("nan"))
+    achieved = gram_flop / (gram_ms * 1e-3) / 1e12
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            traffic = json.load(open(args.traffic_json)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    out = {
+        "metric": "KV tokens compressed/sec per layer (deep & shallow) at 32k ctx",
+        "value": tokens / (ms_step * 1e-3),
+        "unit": "tokens/s/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"configs[3]: Mistral-7B-shaped layer, 8 KV heads x 4 Q heads, head_dim 128, "
+                               f"seq_len {L.seq_len}, fp16, 256 drifting clusters; deep: window 64, pool 7, "
+                               f"budget 2048; shallow: K and V, theta 0.98/0.95, cap 2048; batch 1"},
+        "deep_ms": ms_deep, "shallow_ms": ms_shallow,
+        "deep_tokens_per_s": tokens / (ms_deep * 1e-3), "shallow_tokens_per_s": tokens / (ms_shallow * 1e-3),
+        "kernel_ms": kernel_ms,
+        "codebook_entries_found": n_codes,
+        "roofline": {"kernel": "shallow_gram", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F16_TFLOPS,
+                     "traffic": traffic},
+    }
+    # secondary: the eviction path against the HBM roofline (K read once + gathered rows r/w + scores)
+    deep_bytes = units * (L.seq_len * L.head_dim * 2 + 2 * 2 * L.budget * L.head_dim * 2 + 3 * 4 * L.seq_len)
+    out["deep_roofline"] = {"bound": "hbm", "achieved": deep_bytes / (ms_deep * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                            "unit": "GB/s", "frac": deep_bytes / (ms_deep * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(L, wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,6 +163,26 @@ spindle_status spindle_reconstruct(int32_t units, int32_t seq_len, int32_t head_
                                    const float *mag, void *out, void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Per-kernel timing (measurement aid for the roofline figures)                */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * enable != 0: every kernel the library launches from now on is bracketed by a pair of
+ * HIP events recorded on the stream it is launched on; enable == 0 stops recording.
+ * Either call discards the records collected so far.  Process-wide; not meant to be
+ * switched while another thread is inside a compress call.
+ */
+spindle_status spindle_profile(int32_t enable);
+
+/*
+ * Waits for the recorded events, writes up to `max` records in launch order
+ * (names[i*32 .. i*32+31] = NUL-terminated kernel name, ms[i] = elapsed milliseconds),
+ * clears the records and returns how many were written (negative on a HIP error).
+ * `names` and `ms` are HOST buffers.
+ */
+int32_t spindle_profile_read(char *names, float *ms, int32_t max);
+
+/* ------------------------------------------------------------------------- */
 
 /* Thread-local message of the last failing call on this thread ("" if none). */
 const char *spindle_last_error(void);

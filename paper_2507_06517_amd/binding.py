@@ -24,7 +24,8 @@ NORM_PAPER, NORM_NONE = 0, 1
 _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
-           "spindle_compress_shallow", "spindle_reconstruct", "spindle_last_error", "spindle_version"]
+           "spindle_compress_shallow", "spindle_reconstruct", "spindle_profile", "spindle_profile_read",
+           "spindle_last_error", "spindle_version"]
 
 
 class KvDesc(C.Structure):
@@ -55,7 +56,10 @@ def lib():
         L.spindle_shallow_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_compress_shallow.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 14 + [vp, sz, vp]
         L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
-        for name in EXPORTS[:5]:
+        L.spindle_profile.argtypes = [i32]
+        L.spindle_profile_read.argtypes = [C.c_char_p, C.POINTER(C.c_float), i32]
+        L.spindle_profile_read.restype = C.c_int32
+        for name in EXPORTS[:6]:
             getattr(L, name).restype = C.c_int
         L.spindle_last_error.restype = C.c_char_p
         L.spindle_version.restype = C.c_uint32
@@ -138,6 +142,20 @@ def spindle_compress_shallow(desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_
 def spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, Cb, ref, mag, out, stream=None):
     _check(lib().spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, _ptr(Cb), _ptr(ref),
                                      _ptr(mag), _ptr(out), stream if stream is not None else _stream()))
+
+
+def spindle_profile(enable: bool) -> None:
+    _check(lib().spindle_profile(1 if enable else 0))
+
+
+def spindle_profile_read(max_records: int = 4096):
+    """-> list of (kernel name, milliseconds) in launch order; clears the records."""
+    names = C.create_string_buffer(32 * max_records)
+    ms = (C.c_float * max_records)()
+    n = lib().spindle_profile_read(names, ms, max_records)
+    if n < 0:
+        raise SpindleError(4, "spindle_profile_read failed")
+    return [(names.raw[i * 32:(i + 1) * 32].split(b"\0", 1)[0].decode(), float(ms[i])) for i in range(n)]
 
 
 # ------------------------------------------------------------------ allocating helpers

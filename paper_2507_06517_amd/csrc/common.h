@@ -33,6 +33,14 @@ spindle_status check_desc(const spindle_kv_desc *d);
     if (e_ != hipSuccess) SPINDLE_FAIL(SPINDLE_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
 
+// Brackets one kernel launch with HIP events on its stream while profiling is enabled.
+struct ProfScope {
+  int idx;
+  hipStream_t st;
+  ProfScope(const char *name, hipStream_t s);
+  ~ProfScope();
+};
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 inline int dtype_bytes(int dt) { return dt == SPINDLE_F32 ? 4 : 2; }

@@ -454,11 +454,14 @@ spindle_status launch_passes(const DeepParams &p, int U, hipStream_t st) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_stats));
   SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&deep_pass<DT, WR, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_acc));
-  hipLaunchKernelGGL((deep_pass<DT, WR, false>), dim3(p.nchunks, U), dim3(kDeepThreads), smem_stats, st, p);
+  { ProfScope ps("deep_stats", st);
+  hipLaunchKernelGGL((deep_pass<DT, WR, false>), dim3(p.nchunks, U), dim3(kDeepThreads), smem_stats, st, p); }
   const int total = U * p.Rpad;
-  hipLaunchKernelGGL(deep_combine, dim3((total + 255) / 256), dim3(256), 0, st, p, U);
+  { ProfScope ps("deep_combine", st);
+  hipLaunchKernelGGL(deep_combine, dim3((total + 255) / 256), dim3(256), 0, st, p, U); }
   if (p.lc > 0) {
     const int nacc = (p.lc + kKeysPerBlock - 1) / kKeysPerBlock;
+    ProfScope ps("deep_accumulate", st);
     hipLaunchKernelGGL((deep_pass<DT, WR, true>), dim3(nacc, U), dim3(kDeepThreads), smem_acc, st, p);
   }
   SPINDLE_HIP(hipGetLastError());
@@ -541,7 +544,8 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   sp.scores = L.scores; sp.pooled = L.pooled; sp.scores_out = scores_out;
   sp.budgets = budgets; sp.kept = kept_idx;
   sp.l = l; sp.lc = lc; sp.lw = lw; sp.pool = pool_kernel; sp.budget = budget; sp.out_stride = out_stride;
-  hipLaunchKernelGGL(deep_select, dim3(U), dim3(kSelThreads), 0, st, sp);
+  { ProfScope ps("deep_select", st);
+  hipLaunchKernelGGL(deep_select, dim3(U), dim3(kSelThreads), 0, st, sp); }
 
   GatherParams gp;
   gp.K = static_cast<const char *>(K); gp.V = static_cast<const char *>(V);
@@ -549,7 +553,8 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   gp.kept = kept_idx; gp.l = l; gp.out_stride = out_stride;
   gp.row_bytes = kHeadDim * dtype_bytes(desc->dtype);
   const int rows_per_block = 256 / (gp.row_bytes / 16);
-  hipLaunchKernelGGL(deep_gather, dim3((out_stride + rows_per_block - 1) / rows_per_block, U), dim3(256), 0, st, gp);
+  { ProfScope ps("deep_gather", st);
+  hipLaunchKernelGGL(deep_gather, dim3((out_stride + rows_per_block - 1) / rows_per_block, U), dim3(256), 0, st, gp); }
   SPINDLE_HIP(hipGetLastError());
   return SPINDLE_OK;
 }

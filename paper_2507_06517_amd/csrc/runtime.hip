@@ -2,6 +2,9 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "common.h"
 
 namespace spindle {
@@ -28,7 +31,65 @@ spindle_status check_desc(const spindle_kv_desc *d) {
   return SPINDLE_OK;
 }
 
+struct ProfRec {
+  char name[32];
+  hipEvent_t a, b;
+};
+static std::mutex g_prof_mu;
+static std::vector<ProfRec> g_prof;
+static bool g_prof_on = false;
+
+static void prof_clear() {
+  for (ProfRec &r : g_prof) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  g_prof.clear();
+}
+
+ProfScope::ProfScope(const char *name, hipStream_t s) : idx(-1), st(s) {
+  if (!g_prof_on) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  ProfRec r;
+  strncpy(r.name, name, sizeof(r.name) - 1);
+  r.name[sizeof(r.name) - 1] = 0;
+  if (hipEventCreate(&r.a) != hipSuccess) return;
+  if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+  (void)hipEventRecord(r.a, st);
+  idx = (int)g_prof.size();
+  g_prof.push_back(r);
+}
+
+ProfScope::~ProfScope() {
+  if (idx < 0) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (idx < (int)g_prof.size()) (void)hipEventRecord(g_prof[idx].b, st);
+}
+
 }  // namespace spindle
+
+extern "C" spindle_status spindle_profile(int32_t enable) {
+  std::lock_guard<std::mutex> lk(spindle::g_prof_mu);
+  spindle::prof_clear();
+  spindle::g_prof_on = enable != 0;
+  return SPINDLE_OK;
+}
+
+extern "C" int32_t spindle_profile_read(char *names, float *ms, int32_t max) {
+  std::lock_guard<std::mutex> lk(spindle::g_prof_mu);
+  int32_t n = 0;
+  for (spindle::ProfRec &r : spindle::g_prof) {
+    if (n >= max || !names || !ms) break;
+    if (hipEventSynchronize(r.b) != hipSuccess) return -1;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) return -1;
+    memcpy(names + (size_t)n * 32, r.name, 32);
+    ms[n] = t;
+    ++n;
+  }
+  spindle::prof_clear();
+  return n;
+}
 
 extern "C" const char *spindle_last_error(void) { return spindle::g_error; }
 

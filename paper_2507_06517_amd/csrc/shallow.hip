@@ -703,20 +703,25 @@ extern "C" spindle_status spindle_compress_shallow(
     hipLaunchKernelGGL(fill_u32, dim3(1024), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.C[i]), cwords, 0u);
 
   const dim3 pgrid((n + 63) / 64, p.UT);
+  { ProfScope ps("shallow_prep", st);
   if (p.dtype == SPINDLE_F16) hipLaunchKernelGGL(shallow_prep<SPINDLE_F16>, pgrid, dim3(256), 0, st, p);
   else if (p.dtype == SPINDLE_BF16) hipLaunchKernelGGL(shallow_prep<SPINDLE_BF16>, pgrid, dim3(256), 0, st, p);
-  else hipLaunchKernelGGL(shallow_prep<SPINDLE_F32>, pgrid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(shallow_prep<SPINDLE_F32>, pgrid, dim3(256), 0, st, p); }
 
   const int nI = (n + kPanelRows - 1) / kPanelRows, nJ = (n + kChunkCols - 1) / kChunkCols;
   const int pairs8 = (p.UT * nJ + 7) / 8;
-  hipLaunchKernelGGL(shallow_gram, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p);
-  hipLaunchKernelGGL(shallow_fixup, dim3(1024), dim3(256), 0, st, p);
+  { ProfScope ps("shallow_gram", st);
+  hipLaunchKernelGGL(shallow_gram, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p); }
+  { ProfScope ps("shallow_fixup", st);
+  hipLaunchKernelGGL(shallow_fixup, dim3(1024), dim3(256), 0, st, p); }
   SPINDLE_HIP(hipGetLastError());
 
   void *args[] = {&p};
+  { ProfScope ps("shallow_merge", st);
   SPINDLE_HIP(hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&shallow_merge),
-                                         dim3(p.n_groups * p.blocks_per_group), dim3(kMergeThreads), args, 0, st));
-  hipLaunchKernelGGL(shallow_overflow, dim3(2048), dim3(256), 0, st, p);
+                                         dim3(p.n_groups * p.blocks_per_group), dim3(kMergeThreads), args, 0, st)); }
+  { ProfScope ps("shallow_overflow", st);
+  hipLaunchKernelGGL(shallow_overflow, dim3(2048), dim3(256), 0, st, p); }
 
   const int W = (n + 31) / 32;
   for (int i = 0; i < T; ++i) {
