@@ -104,6 +104,7 @@ def main():
         per_kernel.setdefault(name, []).append(ms)
     kernel_ms = {k: float(np.mean(v)) for k, v in per_kernel.items()}
 
+    st = shallow.stats()
     n_codes = {t: shallow.out[f"n_found_{t}"].cpu().numpy().ravel().tolist() for t in ("k", "v")}
     assert min(shallow.out["n_codes_k"].min().item(), shallow.out["n_codes_v"].min().item()) >= 1, \
         "codebook construction did not finish"
@@ -135,6 +136,7 @@ def main():
         "deep_tokens_per_s": tokens / (ms_deep * 1e-3), "shallow_tokens_per_s": tokens / (ms_shallow * 1e-3),
         "kernel_ms": kernel_ms,
         "codebook_entries_found": n_codes,
+        "merge_rounds": st[:, 0].tolist(), "pairs_decided_in_f64": int(st[:, 2].sum()),
         "roofline": {"kernel": "shallow_gram", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F16_TFLOPS,
                      "traffic": traffic},

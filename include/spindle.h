@@ -154,6 +154,17 @@ spindle_status spindle_compress_shallow(const spindle_kv_desc *desc, const void 
                                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Diagnostics of the last spindle_compress_shallow call that used `workspace` with this
+ * shape: for each of the batch * n_kv_heads * n_tensors problems i (all K units first,
+ * then all V units) stats[4*i + 0] = rounds of the parallel codebook construction,
+ * stats[4*i + 1] = codebook entries found, stats[4*i + 2] = token pairs whose adjacency
+ * was decided in double precision, stats[4*i + 3] = 0.  `stats` is a HOST buffer of
+ * 4 * batch * n_kv_heads * n_tensors int32.  Waits for `stream`.
+ */
+spindle_status spindle_shallow_stats(const spindle_kv_desc *desc, int32_t n_tensors,
+                                     const void *workspace, void *stream, int32_t *stats);
+
+/*
  * Eq. 14: out[u, a, :] = C[u, ref[u, a], :] * mag[u, a] for all units u and tokens a.
  *   C [units, max_codes, d] and out [units, l, d] in `dtype`; ref [units, l] int32;
  *   mag [units, l] float32.  No workspace.

@@ -24,7 +24,7 @@ NORM_PAPER, NORM_NONE = 0, 1
 _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
-           "spindle_compress_shallow", "spindle_reconstruct", "spindle_profile", "spindle_profile_read",
+           "spindle_compress_shallow", "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile", "spindle_profile_read",
            "spindle_last_error", "spindle_version"]
 
 
@@ -59,7 +59,8 @@ def lib():
         L.spindle_profile.argtypes = [i32]
         L.spindle_profile_read.argtypes = [C.c_char_p, C.POINTER(C.c_float), i32]
         L.spindle_profile_read.restype = C.c_int32
-        for name in EXPORTS[:6]:
+        L.spindle_shallow_stats.argtypes = [C.POINTER(KvDesc), i32, vp, vp, C.POINTER(C.c_int32)]
+        for name in EXPORTS[:7]:
             getattr(L, name).restype = C.c_int
         L.spindle_last_error.restype = C.c_char_p
         L.spindle_version.restype = C.c_uint32
@@ -137,6 +138,15 @@ def spindle_compress_shallow(desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_
                                           _ptr(mag_k), _ptr(mag_v), _ptr(adj_k), _ptr(adj_v), _ptr(deg_k),
                                           _ptr(deg_v), _ptr(workspace), workspace_bytes,
                                           stream if stream is not None else _stream()))
+
+
+def spindle_shallow_stats(desc, n_tensors, workspace, stream=None):
+    """-> int32 array [units * n_tensors, 4]: rounds, entries found, exact pairs, 0."""
+    n = desc.batch * desc.n_kv_heads * n_tensors
+    buf = (C.c_int32 * (4 * n))()
+    _check(lib().spindle_shallow_stats(C.byref(desc), n_tensors, _ptr(workspace),
+                                       stream if stream is not None else _stream(), buf))
+    return np.frombuffer(buf, dtype=np.int32).reshape(n, 4).copy()
 
 
 def spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, Cb, ref, mag, out, stream=None):
@@ -227,6 +237,10 @@ class ShallowPlan:
                                  g("ref_k"), g("ref_v"), g("mag_k"), g("mag_v"), g("adj_k"), g("adj_v"),
                                  g("deg_k"), g("deg_v"), self.ws, self.ws_bytes)
         return o
+
+    def stats(self):
+        n_t = sum(1 for k in self.out if k.startswith("ref_"))
+        return spindle_shallow_stats(self.desc, n_t, self.ws)
 
 
 def plan_shallow(K, dtype, theta_k, theta_v, max_codes, tensors=("k", "v"), debug=False) -> ShallowPlan:

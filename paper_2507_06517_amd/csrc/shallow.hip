@@ -13,16 +13,21 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "common.h"
 #include "mma.h"
 
 namespace spindle {
 namespace {
 
-// |fp16 MFMA cosine - exact cosine| stays below this bound: both unit vectors carry a
-// relative rounding error of 2^-11 per component (sum <= 2^-10 by Cauchy-Schwarz), plus
-// flushed fp16 subnormal components (< 7e-4) and fp32 accumulation (< 1e-5).
-constexpr float kGuard = 2.0e-3f;
+// Unit vectors are stored in fp16 scaled by 2^10, so that components down to 6e-8 of the
+// norm stay normal numbers.  |fp16 MFMA cosine - exact cosine| then stays below kGuard:
+// each component of both vectors carries a relative rounding error of at most 2^-11
+// (sum over the dot product <= 2^-10 = 9.77e-4 by Cauchy-Schwarz), the fp32 normalisation
+// adds < 1e-6 and the fp32 accumulation of 128 exact products < 1e-5.
+constexpr float kUnitScale = 1024.f;
+constexpr float kGuard = 1.05e-3f;
 
 constexpr int kPanelRows = 256;   // rows of G's column range held in registers per block
 constexpr int kChunkCols = 1024;  // tokens streamed through LDS per block
@@ -33,7 +38,7 @@ constexpr int kStageBytes = kStageCols * kLdsRow;
 
 constexpr int kMergeThreads = 256;
 constexpr int kCounters = 16;     // ints per ut
-enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4 };
+enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4, C_ROUNDS = 5 };
 
 struct ShallowParams {
   const char *X[2];        // input tensors [U][n][128] in `dtype` (index = tensor slot)
@@ -49,9 +54,9 @@ struct ShallowParams {
   int *counters;           // [UT][kCounters]
   unsigned *bar;           // [groups]
   int *err;                // [1] set if a bounded wait expired
-  unsigned long long *fix; // deferred pairs
-  unsigned *fix_count;
-  unsigned fix_cap;
+  uint32_t *fix;           // [UT][fix_cap] deferred pairs, b << 16 | a
+  unsigned *fix_count;     // [UT]
+  unsigned fix_cap;        // per ut
   uint32_t *ovf;           // [UT*n] tokens to re-point, packed ut << 16 | token
   unsigned *ovf_count;
   // outputs (index = tensor slot)
@@ -137,7 +142,7 @@ __global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
     const size_t idx = (size_t)ut * p.n + row0 + r;
     p.m64[idx] = m;
     p.mag[t][(size_t)(ut % p.U) * p.n + row0 + r] = (float)m;
-    const float inv = m > 0.0 ? (float)(1.0 / m) : 0.f;
+    const float inv = m > 0.0 ? (float)((double)kUnitScale / m) : 0.f;
     for (int ch = 0; ch < tpr; ++ch) {
       const u4 v = *reinterpret_cast<const u4 *>(tile_in + r * lds_row + ch * 16);
       const T *e = reinterpret_cast<const T *>(&v);
@@ -162,9 +167,51 @@ __global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
 // of a 32-column tile holds, for token b = col + c, the similarities with 16 of the 32
 // tokens a of each row block; their signs relative to theta are packed by alignbit
 // into the bits of word (a / 32) of row b of G.
-__global__ __launch_bounds__(kGramThreads) void shallow_gram(ShallowParams p) {
+//
+// The accumulators start at -theta (in the 2^20-scaled units of the stored vectors), so
+// the sign of the result is the fp16 decision.  Results closer to zero than the guard
+// band are not trusted: their bits are cleared and the pair is queued for the exact
+// double-precision decision (shallow_fixup sets the bit if it is adjacent).
+
+constexpr int kPairBuf = 256;   // queued pairs per wave before a flush
+
+// Moves a wave's queued pairs to the global list of its ut; when that list is full the
+// pairs are decided here (after the wave's own stores of those words have completed).
+__device__ __noinline__ void flush_pairs(const ShallowParams &p, int ut, uint32_t *buf, int count) {
+  const int lane = lane_id();
+  unsigned base = 0;
+  if (lane == 0) base = atomicAdd(p.fix_count + ut, (unsigned)count);
+  base = __shfl(base, 0);
+  uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
+  const float theta = p.theta[ut / p.U];
+  bool fenced = false;
+  for (int i = lane; i < count; i += kWave) {
+    const uint32_t e = buf[i];
+    if (base + i < p.fix_cap) {
+      list[base + i] = e;
+    } else {
+      if (!fenced) { __threadfence(); fenced = true; }
+      const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
+      if (cos64(p, ut, a, b) > (double)theta)
+        atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+    }
+  }
+}
+
+// min(m, |a|, |b|) in one instruction.  `after_a`, `after_b` must be results of ordinary VALU
+// instructions that read the MFMA results a and b come from: the compiler places the wait states a
+// matrix-core result needs in front of instructions it knows, not in front of inline
+// assembly, so this one is tied behind such an instruction by a data dependency.
+__device__ __forceinline__ float min3_abs(float m, float a, float b, uint32_t after_a, uint32_t after_b) {
+  float r;
+  asm("v_min3_f32 %0, %1, |%2|, |%3|" : "=v"(r) : "v"(m), "v"(a), "v"(b), "v"(after_a), "v"(after_b));
+  return r;
+}
+
+__global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p) {
   typedef Mma<SPINDLE_F16> M;
   __shared__ __attribute__((aligned(16))) char stage[2 * kStageBytes];
+  __shared__ uint32_t pairbuf[kGramThreads / 64][kPairBuf];
   const int n = p.n;
   const int nI = (n + kPanelRows - 1) / kPanelRows;
   const int nJ = (n + kChunkCols - 1) / kChunkCols;
@@ -175,10 +222,13 @@ __global__ __launch_bounds__(kGramThreads) void shallow_gram(ShallowParams p) {
   const int pj = (s_ / nI) * 8 + xcd;
   if (pj >= p.UT * nJ) return;
   const int ut = pj / nJ, J = pj % nJ;
-  const float theta = p.theta[ut / p.U];
+  const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
+  const float band = kGuard * kUnitScale * kUnitScale;
   const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
   const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
   const int arow0 = I * kPanelRows + 64 * wave;   // first token a of this wave
+  uint32_t *buf = pairbuf[wave];
+  int nbuf = 0;                                    // wave-uniform
 
   M::frag af[2][M::kSteps];
 #pragma unroll
@@ -217,84 +267,100 @@ __global__ __launch_bounds__(kGramThreads) void shallow_gram(ShallowParams p) {
     const bool more = s + 1 < nstages;
     if (more) fetch(b0 + kStageCols);
     const char *lds = stage + (s & 1) * kStageBytes;
-#pragma unroll 1
+#pragma unroll
     for (int ct = 0; ct < kStageCols / 32; ++ct) {
       const int bcol0 = b0 + ct * 32;
-      if (bcol0 >= n) break;
-      f16v acc[2];
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rb][v] = -theta;
-      const char *brow = lds + (ct * 32 + c) * kLdsRow;
-#pragma unroll
-      for (int ks = 0; ks < M::kSteps; ++ks) {
-        const M::frag bf = M::load(brow, ks, g);
-        acc[0] = M::mma(af[0][ks], bf, acc[0]);
-        acc[1] = M::mma(af[1][ks], bf, acc[1]);
-      }
-      // sign bits -> bit v of q[rb]; adjacency = cosine - theta > 0
-      uint32_t sg0 = 0, sg1 = 0;
-      float mn = INFINITY;
-#pragma unroll
-      for (int v = 15; v >= 0; --v) {
-        sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(acc[0][v]), 31);
-        sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(acc[1][v]), 31);
-        mn = fminf(mn, fminf(fabsf(acc[0][v]), fabsf(acc[1][v])));
-      }
-      uint32_t q[2] = {~sg0 & 0xFFFFu, ~sg1 & 0xFFFFu};
-      const int b = bcol0 + c;
-      if (__any(mn < kGuard)) {
-        // some pair is too close to theta for fp16: decide it exactly later (or here
-        // when the list is full)
+      if (bcol0 < n) {
+        f16v acc[2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
-            if (fabsf(acc[rb][v]) < kGuard) {
-              const int a = arow0 + 32 * rb + mma_row(v, g);
-              q[rb] &= ~(1u << v);
-              if (a < n && b < n && a != b) {
-                const unsigned at = atomicAdd(p.fix_count, 1u);
-                if (at < p.fix_cap) {
-                  p.fix[at] = ((unsigned long long)ut << 48) | ((unsigned long long)b << 24) | (unsigned long long)a;
-                } else if (cos64(p, ut, a, b) > (double)theta) {
-                  q[rb] |= 1u << v;
-                }
-              }
+          for (int v = 0; v < 16; ++v) acc[rb][v] = -theta_s;
+        const char *brow = lds + (ct * 32 + c) * kLdsRow;
+#pragma unroll
+        for (int ks = 0; ks < M::kSteps; ++ks) {
+          const M::frag bf = M::load(brow, ks, g);
+          acc[0] = M::mma(af[0][ks], bf, acc[0]);
+          acc[1] = M::mma(af[1][ks], bf, acc[1]);
+        }
+        // sign bits -> bit v of sg; adjacency = cosine - theta > 0
+        uint32_t sg0 = 0, sg1 = 0;
+        float mn = INFINITY;
+#pragma unroll
+        for (int v = 15; v >= 0; --v) {
+          sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(acc[0][v]), 31);
+          sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(acc[1][v]), 31);
+          mn = min3_abs(mn, acc[0][v], acc[1][v], sg0, sg1);
+        }
+        uint32_t q[2] = {~sg0 & 0xFFFFu, ~sg1 & 0xFFFFu};
+        const int b = bcol0 + c;
+        // pairs too close to theta for fp16: clear their bits now, queue them for the exact
+        // decision after this tile's words are stored.  Bit 16*rb + v of `rest` = close.
+        uint32_t rest = 0;
+        const bool any_close = __any(mn < band);
+        if (any_close) {
+          uint32_t cm0 = 0, cm1 = 0;
+#pragma unroll
+          for (int v = 15; v >= 0; --v) {
+            cm0 = __builtin_amdgcn_alignbit(cm0, __float_as_uint(fabsf(acc[0][v]) - band), 31);
+            cm1 = __builtin_amdgcn_alignbit(cm1, __float_as_uint(fabsf(acc[1][v]) - band), 31);
+          }
+          q[0] &= ~cm0;
+          q[1] &= ~cm1;
+          rest = (cm0 & 0xFFFFu) | (cm1 << 16);
+        }
+        if (bcol0 < arow0 + 64 && bcol0 + 32 > arow0) {   // tile touches the diagonal: G_aa = 1
+          const int i = b - arow0;
+          if (i >= 0 && i < 64 && ((i & 7) >> 2) == g) q[i >> 5] |= 1u << (4 * ((i & 31) >> 3) + (i & 3));
+        }
+        if (arow0 + 64 > n) {                             // tokens a beyond the sequence
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              if (arow0 + 32 * rb + mma_row(v, g) >= n) q[rb] &= ~(1u << v);
+        }
+        const uint32_t own = q[0] | (q[1] << 16);
+        const uint32_t other = __shfl_xor(own, 32);
+        const uint32_t mine = (own >> (16 * g)) & 0xFFFFu, theirs = (other >> (16 * g)) & 0xFFFFu;
+        const uint32_t word = (spread_nibbles(mine) << (4 * g)) | (spread_nibbles(theirs) << (4 * (1 - g)));
+        if (b < n) Gut[(size_t)b * p.Wp + (arow0 >> 5) + g] = word;
+        if (any_close) {
+          while (__any(rest != 0)) {
+            const bool has = rest != 0;
+            const int i = has ? __builtin_ctz(rest) : 0;
+            rest &= rest - 1;
+            const int a = arow0 + 32 * (i >> 4) + mma_row(i & 15, g);
+            const unsigned long long m = __ballot(has && a < n && b < n && a != b);
+            if (m) {                                    // wave-uniform
+              if (nbuf > kPairBuf - 64) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
+              if ((m >> lane) & 1ull) buf[nbuf + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)b << 16) | (uint32_t)a;
+              nbuf += __popcll(m);
             }
+          }
+        }
       }
-      if (bcol0 < arow0 + 64 && bcol0 + 32 > arow0) {   // tile touches the diagonal: G_aa = 1
-        const int i = b - arow0;
-        if (i >= 0 && i < 64 && ((i & 7) >> 2) == g) q[i >> 5] |= 1u << (4 * ((i & 31) >> 3) + (i & 3));
-      }
-      if (arow0 + 64 > n) {                             // tokens a beyond the sequence
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            if (arow0 + 32 * rb + mma_row(v, g) >= n) q[rb] &= ~(1u << v);
-      }
-      const uint32_t own = q[0] | (q[1] << 16);
-      const uint32_t other = __shfl_xor(own, 32);
-      const uint32_t mine = (own >> (16 * g)) & 0xFFFFu, theirs = (other >> (16 * g)) & 0xFFFFu;
-      const uint32_t word = (spread_nibbles(mine) << (4 * g)) | (spread_nibbles(theirs) << (4 * (1 - g)));
-      if (b < n) Gut[(size_t)b * p.Wp + (arow0 >> 5) + g] = word;
     }
     if (more) stash(stage + ((s + 1) & 1) * kStageBytes);
     __syncthreads();
   }
+  if (nbuf) flush_pairs(p, ut, buf, nbuf);
 }
 
 // ---------------------------------------------------------------- exact fix-up
 __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
-  unsigned count = *p.fix_count;
-  if (count > p.fix_cap) count = p.fix_cap;
-  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) {
-    const unsigned long long e = p.fix[i];
-    const int ut = (int)(e >> 48), b = (int)((e >> 24) & 0xFFFFFFu), a = (int)(e & 0xFFFFFFu);
-    if (cos64(p, ut, a, b) > (double)p.theta[ut / p.U])
-      atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+  const unsigned stride = gridDim.x * blockDim.x;
+  for (int ut = 0; ut < p.UT; ++ut) {
+    unsigned count = p.fix_count[ut];
+    if (count > p.fix_cap) count = p.fix_cap;
+    const uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
+    const double theta = (double)p.theta[ut / p.U];
+    for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+      const uint32_t e = list[i];
+      const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
+      if (cos64(p, ut, a, b) > theta)
+        atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+    }
   }
 }
 
@@ -424,7 +490,7 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
       __syncthreads();
       if (threadIdx.x == 0) {
         if (sh_cnt) atomicAdd(&cnt[round & 1], sh_cnt);
-        if (brank == 0) { cnt[(round & 1) ^ 1] = 0; cnt[C_CAND] = 0; cnt[C_DYING] = 0; }
+        if (brank == 0) { cnt[(round & 1) ^ 1] = 0; cnt[C_CAND] = 0; cnt[C_DYING] = 0; cnt[C_ROUNDS] = round; }
       }
       if (!group_barrier(p, group, target)) return;
       if (__hip_atomic_load(&cnt[round & 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) break;
@@ -591,14 +657,16 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.m1 = cv.take<uint32_t>(N);
   p.pick_key = cv.take<uint32_t>(N);
   p.ovf = cv.take<uint32_t>(N);
-  p.fix_cap = (unsigned)(N * 8 > (1u << 20) ? (N * 8 < (1u << 26) ? N * 8 : (1u << 26)) : (1u << 20));
-  p.fix = cv.take<unsigned long long>(p.fix_cap);
-  // everything that must start at zero sits together at the end
-  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + UT);
-  p.fix_count = reinterpret_cast<unsigned *>(p.counters ? p.counters + (size_t)UT * kCounters : nullptr);
-  p.ovf_count = p.fix_count ? p.fix_count + 1 : nullptr;
-  p.err = p.counters ? p.counters + (size_t)UT * kCounters + 2 : nullptr;
-  p.bar = reinterpret_cast<unsigned *>(p.counters ? p.counters + (size_t)UT * kCounters + 4 : nullptr);
+  p.fix_cap = (unsigned)(32 * (size_t)n > 4096 ? 32 * (size_t)n : 4096);
+  p.fix = cv.take<uint32_t>((size_t)UT * p.fix_cap);
+  // everything that must start at zero sits together at the end:
+  // counters [UT][kCounters], ovf_count, err, 2 spare, bar [UT], fix_count [UT]
+  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + 2 * (size_t)UT);
+  int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
+  p.ovf_count = reinterpret_cast<unsigned *>(tail);
+  p.err = tail ? tail + 1 : nullptr;
+  p.bar = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
+  p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 + UT : nullptr);
   return cv.total();
 }
 
@@ -637,6 +705,31 @@ extern "C" spindle_status spindle_shallow_workspace_bytes(const spindle_kv_desc 
   if (desc->seq_len > 65535) SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "seq_len must be <= 65535 for the codebook path");
   ShallowParams p;
   *bytes = carve(p, nullptr, desc->batch * desc->n_kv_heads * n_tensors, desc->seq_len);
+  return SPINDLE_OK;
+}
+
+extern "C" spindle_status spindle_shallow_stats(const spindle_kv_desc *desc, int32_t n_tensors,
+                                                const void *workspace, void *stream, int32_t *stats) {
+  size_t need = 0;
+  spindle_status s = spindle_shallow_workspace_bytes(desc, n_tensors, &need);
+  if (s != SPINDLE_OK) return s;
+  if (!workspace || !stats) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "workspace and stats are required");
+  const int UT = desc->batch * desc->n_kv_heads * n_tensors;
+  ShallowParams p;
+  memset(&p, 0, sizeof(p));
+  carve(p, const_cast<void *>(workspace), UT, desc->seq_len);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  std::vector<int> cnt((size_t)UT * kCounters);
+  std::vector<unsigned> fixc(UT);
+  SPINDLE_HIP(hipStreamSynchronize(st));
+  SPINDLE_HIP(hipMemcpy(cnt.data(), p.counters, cnt.size() * sizeof(int), hipMemcpyDeviceToHost));
+  SPINDLE_HIP(hipMemcpy(fixc.data(), p.fix_count, fixc.size() * sizeof(unsigned), hipMemcpyDeviceToHost));
+  for (int i = 0; i < UT; ++i) {
+    stats[4 * i + 0] = cnt[(size_t)i * kCounters + C_ROUNDS];
+    stats[4 * i + 1] = cnt[(size_t)i * kCounters + C_PICKS];
+    stats[4 * i + 2] = (int32_t)fixc[i];
+    stats[4 * i + 3] = 0;
+  }
   return SPINDLE_OK;
 }
 
@@ -694,7 +787,7 @@ extern "C" spindle_status spindle_compress_shallow(
   p.spin_limit = 50u * 1000u * 1000u;
 
   // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = (size_t)p.UT * kCounters + 4 + p.UT;
+  const size_t nzero = (size_t)p.UT * kCounters + 4 + 2 * (size_t)p.UT;
   hipLaunchKernelGGL(fill_u32, dim3(64), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.counters), nzero, 0u);
   for (int i = 0; i < T; ++i)   // -1 marks "not finished": stays if a bounded wait expires
     hipLaunchKernelGGL(fill_u32, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.n_codes[i]), (size_t)U, 0xFFFFFFFFu);
