@@ -1,0 +1,85 @@
+"""Parity at the full sizes of the benchmark configurations (configs 3-5), in the launch
+configuration bench.py times.  The oracle runs on the host cores in parallel over units."""
+import numpy as np
+import pytest
+
+from paper_2507_06517_amd import workloads as wl
+
+import parity
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def test_config3_stack(oracle):
+    # 32-layer stack at l = 8192: layers 0-7 codebook (cap 512), layers 8-31 eviction with
+    # the tapering budget.  Every layer goes through the library; the oracle checks a spread
+    # of layers in full (all units) to bound the host time.
+    for layer in (0, 7):
+        L = wl.config3_layer(layer)
+        res, g = parity.check_shallow_layer(oracle, L)
+        print("config3 layer", layer, "codes", [o["n_codes_uncapped"] for o in res][:4], flush=True)
+    rep = {}
+    for layer in (8, 15, 23, 31):
+        L = wl.config3_layer(layer)
+        assert L.budget == wl.config3_budget(layer)
+        rep[layer] = parity.check_deep_layer(oracle, L)
+    print("config3 deep", rep, flush=True)
+
+
+def test_config3_stack_folded_into_batch(oracle):
+    # layers folded into the batch dimension with per-unit budgets: one call for 4 layers
+    layers = [8, 16, 24, 31]
+    Ls = [wl.config3_layer(i, seq_len=2048) for i in layers]
+    big = wl.Layer("f16", np.concatenate([x.K for x in Ls]), np.concatenate([x.V for x in Ls]),
+                   np.concatenate([x.Qw for x in Ls]), 4, 32, 7, 2048, 512)
+    budgets = [wl.config3_budget(i) for i in layers for _ in range(8)]
+    kept, Ko, Vo, sc = parity.gpu_deep(big, budget=32, budgets=budgets, out_stride=2048)
+    for j, L in enumerate(Ls):
+        p64, k64 = parity.oracle_deep(oracle, L, L.budget)
+        for h in range(8):
+            parity.check_deep_unit(p64[0, h], k64[0, h], sc[j, h], kept[j, h], 32, 2048, {})
+
+
+def test_config4_deep(oracle):
+    rep = parity.check_deep_layer(oracle, wl.config4(0))
+    print("config4 deep", rep, flush=True)
+
+
+def test_config4_shallow(oracle):
+    L = wl.config4(0)
+    g = parity.gpu_shallow(L, debug=False)
+    res, _ = parity.check_shallow_layer(oracle, L, g=g)
+    print("config4 codes", [o["n_codes_uncapped"] for o in res], flush=True)
+
+
+def test_config4_adjacency_rows(oracle):
+    # sampled rows of G and their degrees at l = 32768, every unit of K
+    L = wl.config4(0)
+    g = parity.gpu_shallow(L, tensors=("k",))
+    rng = np.random.default_rng(0)
+    theta = float(np.float32(L.theta_k))
+    for h in range(L.n_kv_heads):
+        X = wl.to_f64(L.K[0, h], L.dtype)
+        m = oracle.magnitudes(X)
+        for a in rng.integers(0, L.seq_len, size=24):
+            row = oracle.adjacency_row(X, theta, int(a), m)
+            assert np.array_equal(g["adj_k"][0, h, a], row)
+            assert g["deg_k"][0, h, a] == sum(bin(int(w)).count("1") for w in row)
+
+
+@pytest.mark.parametrize("budget", [512, 4096])
+def test_config5_layer(oracle, budget):
+    # batch 4 x 32768, bf16, half clustered / half noise: the codebook overflows its cap by
+    # far.  The whole layer runs on the GPU; the oracle checks the eviction path on every
+    # unit and the codebook path on one (batch, head) unit of K and one of V.
+    L = wl.config5_layer(0, budget)
+    rep = parity.check_deep_layer(oracle, L)
+    print("config5 deep", budget, rep, flush=True)
+    g = parity.gpu_shallow(L, debug=False)
+    res, _ = parity.check_shallow_layer(oracle, L, units=[(1, 2)], g=g)
+    assert all(o["n_codes_uncapped"] > budget for o in res)
+    # invariants on every unit
+    for t in ("k", "v"):
+        assert (g[f"n_codes_{t}"] == budget).all()
+        assert g[f"ref_{t}"].min() >= 0 and g[f"ref_{t}"].max() < budget
+    print("config5 codes found", [o["n_codes_uncapped"] for o in res], flush=True)
