@@ -137,6 +137,7 @@ def main():
         "kernel_ms": kernel_ms,
         "codebook_entries_found": n_codes,
         "merge_rounds": st[:, 0].tolist(), "pairs_decided_in_f64": int(st[:, 2].sum()),
+        "merge_phase_us_unit0": st[0, 4:14].tolist(),
         "roofline": {"kernel": "shallow_gram", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F16_TFLOPS,
                      "traffic": traffic},

@@ -141,12 +141,12 @@ def spindle_compress_shallow(desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_
 
 
 def spindle_shallow_stats(desc, n_tensors, workspace, stream=None):
-    """-> int32 array [units * n_tensors, 4]: rounds, entries found, exact pairs, 0."""
+    """-> int32 array [units * n_tensors, 16]: rounds, entries found, exact pairs, 0, phase us..."""
     n = desc.batch * desc.n_kv_heads * n_tensors
-    buf = (C.c_int32 * (4 * n))()
+    buf = (C.c_int32 * (16 * n))()
     _check(lib().spindle_shallow_stats(C.byref(desc), n_tensors, _ptr(workspace),
                                        stream if stream is not None else _stream(), buf))
-    return np.frombuffer(buf, dtype=np.int32).reshape(n, 4).copy()
+    return np.frombuffer(buf, dtype=np.int32).reshape(n, 16).copy()
 
 
 def spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, Cb, ref, mag, out, stream=None):

@@ -7,8 +7,9 @@
 //                   into the adjacency matrix G (Eq. 4, 9); pairs whose fp16 similarity
 //                   lies within kGuard of theta are deferred to shallow_fixup
 //   shallow_fixup   exact double-precision decision for the deferred pairs
-//   shallow_merge   persistent kernel: degrees (Eq. 10) and the greedy highest-degree
-//                   codebook construction (Eq. 11-13), all rounds on the device
+//   shallow_lists   degrees (Eq. 10) and compact neighbour lists of the sparse rows of G
+//   shallow_merge   the greedy highest-degree codebook construction (Eq. 11-13), all
+//                   rounds on the device, one workgroup per problem
 //   shallow_overflow  re-points tokens whose entry fell beyond the codebook cap
 #include <math.h>
 #include <string.h>
@@ -36,7 +37,6 @@ constexpr int kGramThreads = 256;
 constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad
 constexpr int kStageBytes = kStageCols * kLdsRow;
 
-constexpr int kMergeThreads = 256;
 constexpr int kCounters = 16;     // ints per ut
 enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4, C_ROUNDS = 5 };
 
@@ -49,11 +49,10 @@ struct ShallowParams {
   _Float16 *Xh;            // [UT][n][128] unit vectors
   double *m64;             // [UT][n]
   uint32_t *G;             // [UT][n][Wp]
-  int *deg, *status, *slot, *cand, *dying, *pick_vert, *rank, *rank_vert;   // [UT][n]
-  uint32_t *key, *m1, *pick_key;                                             // [UT][n]
+  int *deg0, *slot, *alive, *cand, *dying, *pick_vert, *rank, *rank_vert;   // [UT][n]
+  uint16_t *nbr;           // [UT][n][kListCap] neighbour lists of the sparse rows
+  uint32_t *key, *gone, *m1, *pick_key;                                      // [UT][n]
   int *counters;           // [UT][kCounters]
-  unsigned *bar;           // [groups]
-  int *err;                // [1] set if a bounded wait expired
   uint32_t *fix;           // [UT][fix_cap] deferred pairs, b << 16 | a
   unsigned *fix_count;     // [UT]
   unsigned fix_cap;        // per ut
@@ -64,9 +63,6 @@ struct ShallowParams {
   int32_t *n_codes[2], *n_found[2], *ref[2];
   float *mag[2];
   int32_t *deg_out[2];     // optional initial degrees
-  // merge launch shape
-  int blocks_per_group, n_groups;
-  unsigned spin_limit;
 };
 
 __device__ __forceinline__ const char *x_row(const ShallowParams &p, int ut, int a) {
@@ -239,6 +235,13 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       af[rb][ks] = a < n ? M::load(Xh + (size_t)a * 256, ks, g) : M::zero();
   }
 
+  uint32_t rowmask[2] = {0, 0};
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (arow0 + 32 * rb + mma_row(v, g) < n) rowmask[rb] |= 1u << v;
+
   const int col_begin = J * kChunkCols;
   const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
   const int nstages = (col_end - col_begin + kStageCols - 1) / kStageCols;
@@ -313,13 +316,8 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
           const int i = b - arow0;
           if (i >= 0 && i < 64 && ((i & 7) >> 2) == g) q[i >> 5] |= 1u << (4 * ((i & 31) >> 3) + (i & 3));
         }
-        if (arow0 + 64 > n) {                             // tokens a beyond the sequence
-#pragma unroll
-          for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-              if (arow0 + 32 * rb + mma_row(v, g) >= n) q[rb] &= ~(1u << v);
-        }
+        q[0] &= rowmask[0];                               // tokens a beyond the sequence
+        q[1] &= rowmask[1];
         const uint32_t own = q[0] | (q[1] << 16);
         const uint32_t other = __shfl_xor(own, 32);
         const uint32_t mine = (own >> (16 * g)) & 0xFFFFu, theirs = (other >> (16 * g)) & 0xFFFFu;
@@ -364,6 +362,53 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
   }
 }
 
+// ---------------------------------------------------------------- degrees and neighbour lists
+// One wave per row of G: degree (Eq. 10) and, for rows of at most kListCap neighbours, the
+// neighbour indices as a compact uint16 list, so that the merge rounds touch a few hundred
+// bytes per token instead of the whole bitmap row.  Denser rows keep using the bitmap.
+constexpr int kListCap = 128;
+
+__global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
+  const int ut = blockIdx.y, n = p.n, Wp = p.Wp;
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int row0 = (blockIdx.x * 4 + wave) * 4;
+  for (int v = row0; v < row0 + 4 && v < n; ++v) {
+    const u4 *row = reinterpret_cast<const u4 *>(p.G + ((size_t)ut * n + v) * Wp);
+    int c = 0;
+    for (int w4 = lane; w4 < Wp / 4; w4 += kWave) {
+      const u4 q = row[w4];
+      c += __popc(q[0]) + __popc(q[1]) + __popc(q[2]) + __popc(q[3]);
+    }
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int x = __shfl_up(incl, o);
+      if (lane >= o) incl += x;
+    }
+    const int deg = __shfl(incl, 63);
+    if (lane == 0) {
+      const size_t i = (size_t)ut * n + v;
+      p.deg0[i] = deg;
+      if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = deg;
+    }
+    if (deg <= kListCap) {
+      uint16_t *dst = p.nbr + ((size_t)ut * n + v) * kListCap + (incl - c);
+      for (int w4 = lane; w4 < Wp / 4; w4 += kWave) {
+        const u4 q = row[w4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          uint32_t bits = q[j];
+          while (bits) {
+            const int t = __builtin_ctz(bits);
+            bits &= bits - 1;
+            *dst++ = (uint16_t)((w4 * 4 + j) * 32 + t);
+          }
+        }
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------- greedy merge
 // Exact parallel form of the loop of Alg. 1.  With key(v) = (degree among remaining
 // tokens, lower index first), the sequential loop always takes the remaining token of
@@ -373,57 +418,50 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
 // so they do not touch its neighbourhood.  Each round therefore takes every two-hop
 // maximum at once; sorting all picks by their key at pick time (which strictly decreases
 // along the sequential loop) restores the codebook order.
+//
+// One workgroup of 1024 threads per ut, so the phases of a round are separated by
+// workgroup barriers only.  The keys (degree << 16 | 0xFFFF - index, 0 once removed) live
+// in LDS when they fit: the neighbour look-ups and the degree updates of Eq. 13 are then
+// LDS gathers and LDS atomics.  Rows are handled by 16-lane segments of a wave.
+constexpr int kMergeThreads = 1024;
+constexpr int kMergeSegs = kMergeThreads / 16;
+constexpr int kKeysInLds = 36 * 1024;   // tokens whose keys fit in LDS next to the other buffers
 
-__device__ __forceinline__ bool group_barrier(const ShallowParams &p, int group, unsigned &target) {
-  __shared__ int ok_s;
-  __threadfence();
-  __syncthreads();
-  if (p.blocks_per_group == 1) return true;
-  target += (unsigned)p.blocks_per_group;
-  if (threadIdx.x == 0) {
-    unsigned *bar = p.bar + group;
-    __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned spins = 0;
-    int ok = 1;
-    while (__hip_atomic_load(bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      __builtin_amdgcn_s_sleep(4);
-      if (++spins > p.spin_limit) { ok = 0; break; }
-    }
-    if (!ok) atomicExch(p.err, 1);
-    ok_s = ok;
-  }
-  __syncthreads();
-  __threadfence();
-  return ok_s != 0;
-}
-
+// Calls f(b) for every neighbour b of token v, the work split over the 16 lanes of a segment.
 template <typename F>
-__device__ __forceinline__ void for_each_neighbour(const uint32_t *row, int Wp, F f) {
-  for (int w4 = lane_id(); w4 < Wp / 4; w4 += kWave) {
-    const u4 q = reinterpret_cast<const u4 *>(row)[w4];
+__device__ __forceinline__ void for_each_neighbour(const ShallowParams &p, size_t base, int v, int sl, F f) {
+  const int d0 = p.deg0[base + v];
+  if (d0 <= kListCap) {
+    if (sl * 8 < d0) {
+      const u4 q = *reinterpret_cast<const u4 *>(p.nbr + (base + v) * kListCap + sl * 8);
+      const int cnt = d0 - sl * 8 < 8 ? d0 - sl * 8 : 8;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint32_t bits = q[j];
-      while (bits) {
-        const int t = __builtin_ctz(bits);
-        bits &= bits - 1;
-        f((w4 * 4 + j) * 32 + t);
+      for (int j = 0; j < 8; ++j)
+        if (j < cnt) f((int)((q[j >> 1] >> (16 * (j & 1))) & 0xFFFFu));
+    }
+  } else {
+    const u4 *row = reinterpret_cast<const u4 *>(p.G + (base + v) * p.Wp);
+    for (int w4 = sl; w4 < p.Wp / 4; w4 += 16) {
+      const u4 q = row[w4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        uint32_t bits = q[j];
+        while (bits) {
+          const int t = __builtin_ctz(bits);
+          bits &= bits - 1;
+          f((w4 * 4 + j) * 32 + t);
+        }
       }
     }
   }
 }
 
-__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+__device__ __forceinline__ uint32_t seg_max(uint32_t v) {   // over a 16-lane segment
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
+  for (int o = 8; o > 0; o >>= 1) {
     const uint32_t x = __shfl_xor(v, o);
     v = x > v ? x : v;
   }
-  return v;
-}
-__device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
   return v;
 }
 
@@ -440,150 +478,163 @@ __device__ __forceinline__ void emit_code(const ShallowParams &p, int ut, int ve
   }
 }
 
-__global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) {
-  __shared__ int sh_cnt;
-  __shared__ uint32_t sh_keys[1024];
-  const int group = blockIdx.x / p.blocks_per_group, brank = blockIdx.x % p.blocks_per_group;
-  const int lane = lane_id();
-  const int gw = brank * (kMergeThreads / 64) + (threadIdx.x >> 6);
-  const int GW = p.blocks_per_group * (kMergeThreads / 64);
-  const int gt = brank * kMergeThreads + threadIdx.x, GT = p.blocks_per_group * kMergeThreads;
-  const int n = p.n, Wp = p.Wp;
-  unsigned target = 0;
-
-  for (int ut = group; ut < p.UT; ut += p.n_groups) {
-    const uint32_t *G = p.G + (size_t)ut * n * Wp;
-    int *deg = p.deg + (size_t)ut * n, *status = p.status + (size_t)ut * n, *slot = p.slot + (size_t)ut * n;
-    int *cand = p.cand + (size_t)ut * n, *dying = p.dying + (size_t)ut * n;
-    int *pick_vert = p.pick_vert + (size_t)ut * n, *rank = p.rank + (size_t)ut * n;
-    int *rank_vert = p.rank_vert + (size_t)ut * n;
-    uint32_t *key = p.key + (size_t)ut * n, *m1 = p.m1 + (size_t)ut * n, *pick_key = p.pick_key + (size_t)ut * n;
-    int *cnt = p.counters + (size_t)ut * kCounters;
-
-    // degrees, Eq. 10
-    for (int v = gw; v < n; v += GW) {
-      int c = 0;
-      for (int w4 = lane; w4 < Wp / 4; w4 += kWave) {
-        const u4 q = reinterpret_cast<const u4 *>(G + (size_t)v * Wp)[w4];
-        c += __popc(q[0]) + __popc(q[1]) + __popc(q[2]) + __popc(q[3]);
-      }
-      c = wave_sum(c);
-      if (lane == 0) {
-        deg[v] = c; status[v] = 0; slot[v] = -1;
-        if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = c;
-      }
-    }
-    if (!group_barrier(p, group, target)) return;
-
-    for (int round = 0;; ++round) {
-      // keys of the remaining tokens; count them
-      int alive = 0;
-      for (int v = gt; v < n; v += GT) {
-        uint32_t k = 0;
-        if (status[v] == 0) { k = ((uint32_t)deg[v] << 16) | (uint32_t)(0xFFFF - v); ++alive; }
-        key[v] = k;
-      }
-      if (threadIdx.x == 0) sh_cnt = 0;
-      __syncthreads();
-      alive = wave_sum(alive);
-      if (lane == 0 && alive) atomicAdd(&sh_cnt, alive);
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        if (sh_cnt) atomicAdd(&cnt[round & 1], sh_cnt);
-        if (brank == 0) { cnt[(round & 1) ^ 1] = 0; cnt[C_CAND] = 0; cnt[C_DYING] = 0; cnt[C_ROUNDS] = round; }
-      }
-      if (!group_barrier(p, group, target)) return;
-      if (__hip_atomic_load(&cnt[round & 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) break;
-
-      // one-hop maxima
-      for (int v = gw; v < n; v += GW) {
-        if (status[v] != 0) continue;
-        uint32_t m = 0;
-        for_each_neighbour(G + (size_t)v * Wp, Wp, [&](int b) { const uint32_t k = key[b]; m = k > m ? k : m; });
-        m = wave_max(m);
-        if (lane == 0) {
-          m1[v] = m;
-          if (m == key[v]) cand[atomicAdd(&cnt[C_CAND], 1)] = v;
-        }
-      }
-      if (!group_barrier(p, group, target)) return;
-
-      // two-hop maxima are picked; their remaining neighbours get the pick's slot
-      const int ncand = __hip_atomic_load(&cnt[C_CAND], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      for (int i = gw; i < ncand; i += GW) {
-        const int uvert = cand[i];
-        const uint32_t ku = key[uvert];
-        const uint32_t *row = G + (size_t)uvert * Wp;
-        uint32_t m = 0;
-        for_each_neighbour(row, Wp, [&](int b) {
-          if (key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; }
-        });
-        m = wave_max(m);
-        if (m != ku) continue;
-        int s = 0;
-        if (lane == 0) {
-          s = atomicAdd(&cnt[C_PICKS], 1);
-          pick_key[s] = ku;
-          pick_vert[s] = uvert;
-        }
-        s = __shfl(s, 0);
-        for_each_neighbour(row, Wp, [&](int b) {
-          if (key[b] != 0) {
-            slot[b] = s;
-            status[b] = 1;
-            dying[atomicAdd(&cnt[C_DYING], 1)] = b;
-          }
-        });
-      }
-      if (!group_barrier(p, group, target)) return;
-
-      // removed tokens no longer count towards their neighbours' degrees (Eq. 13)
-      const int ndying = __hip_atomic_load(&cnt[C_DYING], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      for (int i = gw; i < ndying; i += GW) {
-        const int v = dying[i];
-        for_each_neighbour(G + (size_t)v * Wp, Wp, [&](int w) {
-          if (status[w] == 0) atomicSub(&deg[w], 1);
-        });
-      }
-      if (!group_barrier(p, group, target)) return;
-    }
-
-    // codebook order: rank of each pick among all picks by decreasing key
-    const int P = __hip_atomic_load(&cnt[C_PICKS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int s0 = 0; s0 < P; s0 += GT) {
-      const int s = s0 + gt;
-      const uint32_t ks = s < P ? pick_key[s] : 0xFFFFFFFFu;
-      int r = 0;
-      for (int base = 0; base < P; base += 1024) {
-        __syncthreads();
-        for (int j = threadIdx.x; j < 1024; j += kMergeThreads) sh_keys[j] = base + j < P ? pick_key[base + j] : 0u;
-        __syncthreads();
-        const int lim = P - base < 1024 ? P - base : 1024;
-        for (int j = 0; j < lim; ++j) r += sh_keys[j] > ks;
-      }
-      if (s < P) { rank[s] = r; rank_vert[r] = pick_vert[s]; }
-    }
-    if (!group_barrier(p, group, target)) return;
-
-    const int t = ut / p.U, u = ut % p.U;
-    const int stored = P < p.cap ? P : p.cap;
-    if (gt == 0) {
-      p.n_codes[t][u] = stored;
-      if (p.n_found[t]) p.n_found[t][u] = P;
-    }
-    for (int v = gt; v < n; v += GT) {
-      const int r = rank[slot[v]];
-      p.ref[t][(size_t)u * n + v] = r;
-      if (r >= p.cap) p.ovf[atomicAdd(p.ovf_count, 1u)] = ((uint32_t)ut << 16) | (uint32_t)v;
-    }
-    for (int r = gw; r < stored; r += GW) {
-      const int vert = rank_vert[r];
-      if (p.dtype == SPINDLE_F16) emit_code<SPINDLE_F16>(p, ut, vert, r);
-      else if (p.dtype == SPINDLE_BF16) emit_code<SPINDLE_BF16>(p, ut, vert, r);
-      else emit_code<SPINDLE_F32>(p, ut, vert, r);
-    }
-    if (!group_barrier(p, group, target)) return;
+#define MERGE_TICK(k)                          \
+  if (tid == 0) {                              \
+    const long long now_ = wall_clock64();     \
+    cnt[6 + (k)] += (int)(now_ - tick_);       \
+    tick_ = now_;                              \
   }
+
+__global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  __shared__ int sh_n[4];                     // alive, candidates, dying, picks
+  __shared__ uint32_t sh_keys[1024];
+  const int ut = blockIdx.x, n = p.n, tid = threadIdx.x;
+  const int lane = lane_id(), sl = lane & 15, seg = tid >> 4, wave = tid >> 6;
+  const size_t base = (size_t)ut * n;
+  const bool keys_in_lds = n <= kKeysInLds;
+  uint32_t *key = keys_in_lds ? lds : p.key + base;
+  // removed-this-round bits: after the keys in LDS, or in a global scratch row
+  uint32_t *gone = keys_in_lds ? lds + ((n + 3) & ~3) : p.gone + base;
+  int *slot = p.slot + base, *alive = p.alive + base, *dying = p.dying + base, *cand = p.cand + base;
+  int *pick_vert = p.pick_vert + base, *rank = p.rank + base, *rank_vert = p.rank_vert + base;
+  uint32_t *m1 = p.m1 + base, *pick_key = p.pick_key + base;
+  const int *deg0 = p.deg0 + base;
+  int *cnt = p.counters + (size_t)ut * kCounters;
+  long long tick_ = 0;
+  if (tid == 0) tick_ = wall_clock64();
+
+  const int gone_words = (n + 31) / 32;
+  for (int v = tid; v < n; v += kMergeThreads) {
+    key[v] = ((uint32_t)deg0[v] << 16) | (uint32_t)(0xFFFF - v);
+    alive[v] = v;
+    slot[v] = -1;
+  }
+  for (int w = tid; w < gone_words; w += kMergeThreads) gone[w] = 0;
+  if (tid == 0) { sh_n[0] = n; sh_n[1] = 0; sh_n[2] = 0; sh_n[3] = 0; }
+  __syncthreads();
+  MERGE_TICK(0)
+
+  int round = 0;
+  for (;; ++round) {
+    const int nalive = sh_n[0];
+    if (nalive == 0) break;
+    // one-hop maxima
+    for (int i0 = seg & ~3; i0 < nalive; i0 += kMergeSegs) {   // the 4 segments of a wave stay together
+      const int i = i0 + (seg & 3);
+      const bool on = i < nalive;
+      const int v = on ? alive[i] : 0;
+      uint32_t m = 0;
+      if (on) for_each_neighbour(p, base, v, sl, [&](int b) { const uint32_t k = key[b]; m = k > m ? k : m; });
+      m = seg_max(m);
+      if (on && sl == 0) {
+        m1[v] = m;
+        if (m == key[v]) cand[atomicAdd(&sh_n[1], 1)] = v;
+      }
+    }
+    __syncthreads();
+    MERGE_TICK(2)
+    // two-hop maxima are picked; their remaining neighbours get the pick's slot
+    const int ncand = sh_n[1];
+    for (int i0 = seg & ~3; i0 < ncand; i0 += kMergeSegs) {
+      const int i = i0 + (seg & 3);
+      const bool on = i < ncand;
+      const int uvert = on ? cand[i] : 0;
+      const uint32_t ku = on ? key[uvert] : 0xFFFFFFFFu;
+      uint32_t m = 0;
+      if (on) for_each_neighbour(p, base, uvert, sl, [&](int b) {
+        if (key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; }
+      });
+      m = seg_max(m);
+      const bool picked = on && m == ku;
+      int s = 0;
+      if (picked && sl == 0) {
+        s = atomicAdd(&sh_n[3], 1);
+        pick_key[s] = ku;
+        pick_vert[s] = uvert;
+      }
+      s = __shfl(s, lane & 48);
+      if (picked) for_each_neighbour(p, base, uvert, sl, [&](int b) {
+        if (key[b] != 0) {
+          slot[b] = s;
+          atomicOr(&gone[b >> 5], 1u << (b & 31));
+          dying[atomicAdd(&sh_n[2], 1)] = b;
+        }
+      });
+    }
+    __syncthreads();
+    MERGE_TICK(4)
+    // removed tokens no longer count towards their neighbours' degrees (Eq. 13)
+    const int ndying = sh_n[2];
+    for (int i0 = seg & ~3; i0 < ndying; i0 += kMergeSegs) {
+      const int i = i0 + (seg & 3);
+      if (i < ndying) for_each_neighbour(p, base, dying[i], sl, [&](int w) {
+        if (key[w] != 0 && !((gone[w >> 5] >> (w & 31)) & 1u)) atomicSub(&key[w], 1u << 16);
+      });
+    }
+    __syncthreads();
+    MERGE_TICK(6)
+    for (int i = tid; i < ndying; i += kMergeThreads) key[dying[i]] = 0;
+    if (tid == 0) { sh_n[0] = 0; sh_n[1] = 0; sh_n[2] = 0; }
+    __syncthreads();
+    // survivors, compacted in place (each wave appends its survivors with one LDS atomic;
+    // the write index never passes the read index of a later chunk because chunks are
+    // consumed by all waves in lock step)
+    for (int i0 = 0; i0 < nalive; i0 += kMergeThreads) {
+      const int i = i0 + tid;
+      const int v = i < nalive ? alive[i] : -1;
+      const bool live = v >= 0 && key[v] != 0;
+      __syncthreads();
+      const unsigned long long mk = __ballot(live);
+      int at = 0;
+      if (lane == 0 && mk) at = atomicAdd(&sh_n[0], __popcll(mk));
+      at = __shfl(at, 0);
+      if (live) alive[at + __popcll(mk & ((1ull << lane) - 1ull))] = v;
+      __syncthreads();
+    }
+    for (int w = tid; w < gone_words; w += kMergeThreads) gone[w] = 0;
+    __syncthreads();
+    MERGE_TICK(0)
+  }
+  if (tid == 0) cnt[C_ROUNDS] = round;
+
+  // codebook order: rank of each pick among all picks by decreasing key
+  const int P = sh_n[3];
+  if (tid == 0) cnt[C_PICKS] = P;
+  for (int s0 = 0; s0 < P; s0 += kMergeThreads) {
+    const int s = s0 + tid;
+    const uint32_t ks = s < P ? pick_key[s] : 0xFFFFFFFFu;
+    int r = 0;
+    for (int b0 = 0; b0 < P; b0 += 1024) {
+      __syncthreads();
+      sh_keys[tid] = b0 + tid < P ? pick_key[b0 + tid] : 0u;
+      __syncthreads();
+      const int lim = P - b0 < 1024 ? P - b0 : 1024;
+      for (int j = 0; j < lim; ++j) r += sh_keys[j] > ks;
+    }
+    if (s < P) { rank[s] = r; rank_vert[r] = pick_vert[s]; }
+  }
+  __syncthreads();
+  MERGE_TICK(8)
+
+  const int t = ut / p.U, u = ut % p.U;
+  const int stored = P < p.cap ? P : p.cap;
+  if (tid == 0) {
+    p.n_codes[t][u] = stored;
+    if (p.n_found[t]) p.n_found[t][u] = P;
+  }
+  for (int v = tid; v < n; v += kMergeThreads) {
+    const int r = rank[slot[v]];
+    p.ref[t][(size_t)u * n + v] = r;
+    if (r >= p.cap) p.ovf[atomicAdd(p.ovf_count, 1u)] = ((uint32_t)ut << 16) | (uint32_t)v;
+  }
+  for (int r = wave; r < stored; r += kMergeThreads / 64) {
+    const int vert = rank_vert[r];
+    if (p.dtype == SPINDLE_F16) emit_code<SPINDLE_F16>(p, ut, vert, r);
+    else if (p.dtype == SPINDLE_BF16) emit_code<SPINDLE_BF16>(p, ut, vert, r);
+    else emit_code<SPINDLE_F32>(p, ut, vert, r);
+  }
+  MERGE_TICK(9)
 }
 
 // ---------------------------------------------------------------- codebook cap
@@ -645,8 +696,10 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.Xh = cv.take<_Float16>(N * kHeadDim);
   p.m64 = cv.take<double>(N);
   p.G = cv.take<uint32_t>(N * p.Wp);
-  p.deg = cv.take<int>(N);
-  p.status = cv.take<int>(N);
+  p.deg0 = cv.take<int>(N);
+  p.alive = cv.take<int>(N);
+  p.gone = cv.take<uint32_t>(N);
+  p.nbr = cv.take<uint16_t>(N * 128);
   p.slot = cv.take<int>(N);
   p.cand = cv.take<int>(N);
   p.dying = cv.take<int>(N);
@@ -660,35 +713,12 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.fix_cap = (unsigned)(32 * (size_t)n > 4096 ? 32 * (size_t)n : 4096);
   p.fix = cv.take<uint32_t>((size_t)UT * p.fix_cap);
   // everything that must start at zero sits together at the end:
-  // counters [UT][kCounters], ovf_count, err, 2 spare, bar [UT], fix_count [UT]
-  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + 2 * (size_t)UT);
+  // counters [UT][kCounters], ovf_count + 3 spare, fix_count [UT]
+  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + (size_t)UT);
   int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
   p.ovf_count = reinterpret_cast<unsigned *>(tail);
-  p.err = tail ? tail + 1 : nullptr;
-  p.bar = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
-  p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 + UT : nullptr);
+  p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
   return cv.total();
-}
-
-struct DeviceShape {
-  int cus = 0, merge_blocks_per_cu = 0;
-};
-
-spindle_status device_shape(DeviceShape &out) {
-  static DeviceShape cache[64];
-  int dev = 0;
-  SPINDLE_HIP(hipGetDevice(&dev));
-  if (dev < 0 || dev >= 64) SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "device index %d out of range", dev);
-  if (cache[dev].cus == 0) {
-    int cus = 0, occ = 0;
-    SPINDLE_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    SPINDLE_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, shallow_merge, kMergeThreads, 0));
-    if (cus < 1 || occ < 1) SPINDLE_FAIL(SPINDLE_ERR_HIP, "occupancy query returned %d CUs, %d blocks/CU", cus, occ);
-    cache[dev].merge_blocks_per_cu = occ > 4 ? 4 : occ;
-    cache[dev].cus = cus;
-  }
-  out = cache[dev];
-  return SPINDLE_OK;
 }
 
 }  // namespace
@@ -725,10 +755,12 @@ extern "C" spindle_status spindle_shallow_stats(const spindle_kv_desc *desc, int
   SPINDLE_HIP(hipMemcpy(cnt.data(), p.counters, cnt.size() * sizeof(int), hipMemcpyDeviceToHost));
   SPINDLE_HIP(hipMemcpy(fixc.data(), p.fix_count, fixc.size() * sizeof(unsigned), hipMemcpyDeviceToHost));
   for (int i = 0; i < UT; ++i) {
-    stats[4 * i + 0] = cnt[(size_t)i * kCounters + C_ROUNDS];
-    stats[4 * i + 1] = cnt[(size_t)i * kCounters + C_PICKS];
-    stats[4 * i + 2] = (int32_t)fixc[i];
-    stats[4 * i + 3] = 0;
+    stats[16 * i + 0] = cnt[(size_t)i * kCounters + C_ROUNDS];
+    stats[16 * i + 1] = cnt[(size_t)i * kCounters + C_PICKS];
+    stats[16 * i + 2] = (int32_t)fixc[i];
+    stats[16 * i + 3] = 0;
+    for (int k = 0; k < 10; ++k) stats[16 * i + 4 + k] = cnt[(size_t)i * kCounters + 6 + k] / 100;
+    stats[16 * i + 14] = stats[16 * i + 15] = 0;
   }
   return SPINDLE_OK;
 }
@@ -773,21 +805,8 @@ extern "C" spindle_status spindle_compress_shallow(
     p.n_codes[t] = n_codes_v; p.n_found[t] = n_found_v; p.ref[t] = ref_v; p.mag[t] = mag_v;
     adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
   }
-  DeviceShape ds;
-  s = device_shape(ds);
-  if (s != SPINDLE_OK) return s;
-  const int resident = ds.cus * ds.merge_blocks_per_cu;
-  int bpg = resident / p.UT;
-  if (bpg < 1) bpg = 1;
-  const int useful = (n + 15) / 16;          // no more than one wave per 4 rows
-  if (bpg > useful) bpg = useful > 0 ? useful : 1;
-  if (bpg > 64) bpg = 64;
-  p.blocks_per_group = bpg;
-  p.n_groups = resident / bpg < p.UT ? resident / bpg : p.UT;
-  p.spin_limit = 50u * 1000u * 1000u;
-
   // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = (size_t)p.UT * kCounters + 4 + 2 * (size_t)p.UT;
+  const size_t nzero = (size_t)p.UT * kCounters + 4 + (size_t)p.UT;
   hipLaunchKernelGGL(fill_u32, dim3(64), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.counters), nzero, 0u);
   for (int i = 0; i < T; ++i)   // -1 marks "not finished": stays if a bounded wait expires
     hipLaunchKernelGGL(fill_u32, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.n_codes[i]), (size_t)U, 0xFFFFFFFFu);
@@ -809,10 +828,13 @@ extern "C" spindle_status spindle_compress_shallow(
   hipLaunchKernelGGL(shallow_fixup, dim3(1024), dim3(256), 0, st, p); }
   SPINDLE_HIP(hipGetLastError());
 
-  void *args[] = {&p};
+  { ProfScope ps("shallow_lists", st);
+  hipLaunchKernelGGL(shallow_lists, dim3((n + 15) / 16, p.UT), dim3(256), 0, st, p); }
+  const size_t merge_lds = n <= kKeysInLds ? ((size_t)((n + 3) & ~3) + (n + 31) / 32) * sizeof(uint32_t) : 0;
+  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_merge),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds));
   { ProfScope ps("shallow_merge", st);
-  SPINDLE_HIP(hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&shallow_merge),
-                                         dim3(p.n_groups * p.blocks_per_group), dim3(kMergeThreads), args, 0, st)); }
+  hipLaunchKernelGGL(shallow_merge, dim3(p.UT), dim3(kMergeThreads), merge_lds, st, p); }
   { ProfScope ps("shallow_overflow", st);
   hipLaunchKernelGGL(shallow_overflow, dim3(2048), dim3(256), 0, st, p); }
 
