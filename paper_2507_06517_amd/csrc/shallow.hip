@@ -43,7 +43,7 @@ enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4, C_ROUND
 struct ShallowParams {
   const char *X[2];        // input tensors [U][n][128] in `dtype` (index = tensor slot)
   float theta[2];
-  int dtype, U, UT, n, Wp;  // Wp = words per adjacency row (multiple of 8)
+  int dtype, U, UT, n, Wp;  // Wp = words per adjacency row (multiple of 4)
   int cap;
   // workspace
   _Float16 *Xh;            // [UT][n][128] unit vectors
@@ -55,6 +55,7 @@ struct ShallowParams {
   int *counters;           // [UT][kCounters]
   uint32_t *fix;           // [UT][fix_cap] deferred pairs, b << 16 | a
   unsigned *fix_count;     // [UT]
+  unsigned *fix_overflow;  // [1] some list was full
   unsigned fix_cap;        // per ut
   uint32_t *ovf;           // [UT*n] tokens to re-point, packed ut << 16 | token
   unsigned *ovf_count;
@@ -171,27 +172,19 @@ __global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
 
 constexpr int kPairBuf = 256;   // queued pairs per wave before a flush
 
-// Moves a wave's queued pairs to the global list of its ut; when that list is full the
-// pairs are decided here (after the wave's own stores of those words have completed).
-__device__ __noinline__ void flush_pairs(const ShallowParams &p, int ut, uint32_t *buf, int count) {
+// Moves a wave's queued pairs to the global list of its ut.  When that list is full the
+// pairs are dropped and a flag is raised: shallow_gram<true> then decides every close
+// pair of every tile in place (slow, but only for inputs with an extreme number of
+// similarities within the guard band of theta).
+__device__ __noinline__ void flush_pairs(const ShallowParams &p, int ut, const uint32_t *buf, int count) {
   const int lane = lane_id();
   unsigned base = 0;
   if (lane == 0) base = atomicAdd(p.fix_count + ut, (unsigned)count);
   base = __shfl(base, 0);
   uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
-  const float theta = p.theta[ut / p.U];
-  bool fenced = false;
-  for (int i = lane; i < count; i += kWave) {
-    const uint32_t e = buf[i];
-    if (base + i < p.fix_cap) {
-      list[base + i] = e;
-    } else {
-      if (!fenced) { __threadfence(); fenced = true; }
-      const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
-      if (cos64(p, ut, a, b) > (double)theta)
-        atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
-    }
-  }
+  if (base + (unsigned)count > p.fix_cap && lane == 0) atomicExch(p.fix_overflow, 1u);
+  for (int i = lane; i < count; i += kWave)
+    if (base + i < p.fix_cap) list[base + i] = buf[i];
 }
 
 // min(m, |a|, |b|) in one instruction.  `after_a`, `after_b` must be results of ordinary VALU
@@ -204,6 +197,10 @@ __device__ __forceinline__ float min3_abs(float m, float a, float b, uint32_t af
   return r;
 }
 
+// kExact = false: the fast pass described above, one block per (row panel, column chunk).
+// kExact = true: fallback pass over the same tiles, run by a fixed grid that exits at once
+// unless a pair list overflowed; it stores no words and decides the close pairs in place.
+template <bool kExact>
 __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p) {
   typedef Mma<SPINDLE_F16> M;
   __shared__ __attribute__((aligned(16))) char stage[2 * kStageBytes];
@@ -213,43 +210,45 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   const int nJ = (n + kChunkCols - 1) / kChunkCols;
   // blocks are dealt round-robin to the 8 XCDs: give each XCD one (ut, chunk) at a time
   // and let it sweep the row panels, so the chunk is re-read from that XCD's L2
-  const int xcd = blockIdx.x & 7, s_ = blockIdx.x >> 3;
+  if (kExact && *p.fix_overflow == 0) return;
+  const int nitems = 8 * nI * ((p.UT * nJ + 7) / 8);
+  for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
+  const int xcd = item & 7, s_ = item >> 3;
   const int I = s_ % nI;
   const int pj = (s_ / nI) * 8 + xcd;
-  if (pj >= p.UT * nJ) return;
+  if (pj >= p.UT * nJ) continue;
   const int ut = pj / nJ, J = pj % nJ;
   const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
   const float band = kGuard * kUnitScale * kUnitScale;
   const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
   const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
-  const int arow0 = I * kPanelRows + 64 * wave;   // first token a of this wave
+  const int arow0 = I * kPanelRows + 64 * wave;   // first of this wave's 64 rows of G
+  const int myrow = arow0 + lane;                  // the row of G whose words this lane stores
   uint32_t *buf = pairbuf[wave];
   int nbuf = 0;                                    // wave-uniform
 
+  // unit vectors of the wave's rows: MFMA B operand (matrix columns = lanes)
   M::frag af[2][M::kSteps];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    const int a = arow0 + 32 * rb + c;
+  for (int cb = 0; cb < 2; ++cb) {
+    const int a = arow0 + 32 * cb + c;
 #pragma unroll
     for (int ks = 0; ks < M::kSteps; ++ks)
-      af[rb][ks] = a < n ? M::load(Xh + (size_t)a * 256, ks, g) : M::zero();
+      af[cb][ks] = a < n ? M::load(Xh + (size_t)a * 256, ks, g) : M::zero();
   }
-
-  uint32_t rowmask[2] = {0, 0};
+  f16v cinit;
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v)
-      if (arow0 + 32 * rb + mma_row(v, g) < n) rowmask[rb] |= 1u << v;
+  for (int v = 0; v < 16; ++v) cinit[v] = -theta_s;
 
   const int col_begin = J * kChunkCols;
   const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
-  const int nstages = (col_end - col_begin + kStageCols - 1) / kStageCols;
+  const int ntiles = (col_end - col_begin + 31) / 32;
   const int tr = threadIdx.x >> 4, tc = threadIdx.x & 15;   // 16 rows x 16 chunks per pass
-  u4 regs[4];
+  constexpr int kPasses = kStageCols / 16;
+  u4 regs[kPasses];
   auto fetch = [&](int b0) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < kPasses; ++q) {
       const int b = b0 + q * 16 + tr;
       u4 v = {0, 0, 0, 0};
       if (b < n) v = *reinterpret_cast<const u4 *>(Xh + (size_t)b * 256 + tc * 16);
@@ -258,91 +257,159 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   };
   auto stash = [&](char *dst) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) *reinterpret_cast<u4 *>(dst + (q * 16 + tr) * kLdsRow + tc * 16) = regs[q];
+    for (int q = 0; q < kPasses; ++q) *reinterpret_cast<u4 *>(dst + (q * 16 + tr) * kLdsRow + tc * 16) = regs[q];
   };
-  fetch(col_begin);
-  stash(stage);
-  __syncthreads();
-
-  uint32_t *Gut = p.G + (size_t)ut * n * p.Wp;
-  for (int s = 0; s < nstages; ++s) {
-    const int b0 = col_begin + s * kStageCols;
-    const bool more = s + 1 < nstages;
-    if (more) fetch(b0 + kStageCols);
-    const char *lds = stage + (s & 1) * kStageBytes;
+  // Staged token 16*g + v of a tile is fed to matrix row 8*(v/4) + 4*g + v%4, so that result
+  // register v of lane group g belongs to token 16*g + v and the packed sign bits come out
+  // in token order.
+  const int prow = 16 * ((c >> 2) & 1) + 4 * (c >> 3) + (c & 3);
+  const uint32_t wsel = g ? 0x07060302u : 0x01000504u;
+  // One pipeline step: the matrix cores compute the similarities of the NEXT tile (32
+  // staged tokens x this wave's 64 rows, minus theta) while the vector units turn the
+  // signs of the CURRENT tile into the word of this lane's row of G.  The two instruction
+  // streams are independent; sched_barrier pins the issue order (two matrix instructions,
+  // then a slice of vector work) so that neither unit waits for the other.
+  uint32_t *Grow = p.G + ((size_t)ut * n + (myrow < n ? myrow : 0)) * p.Wp;
+  auto step = [&](const char *lds, int ct, int bcol0, const f16v &a0, const f16v &a1, f16v &r0,
+                  f16v &r1) -> uint32_t {
+    const char *srow = lds + (ct * 32 + prow) * kLdsRow;
+    M::frag sf[4], sg[4];
 #pragma unroll
-    for (int ct = 0; ct < kStageCols / 32; ++ct) {
-      const int bcol0 = b0 + ct * 32;
-      if (bcol0 < n) {
-        f16v acc[2];
+    for (int ks = 0; ks < 4; ++ks) sf[ks] = M::load(srow, ks, g);
+    uint32_t sg0 = 0, sg1 = 0;
+    float mn = INFINITY;
+    // sign bits of elements 15..12 while the LDS reads are in flight
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+    for (int v = 15; v >= 12; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[rb][v] = -theta_s;
-        const char *brow = lds + (ct * 32 + c) * kLdsRow;
+    for (int ks = 0; ks < 4; ++ks) {
+      r0 = M::mma(sf[ks], af[0][ks], ks == 0 ? cinit : r0);
+      r1 = M::mma(sf[ks], af[1][ks], ks == 0 ? cinit : r1);
+      sg[ks] = M::load(srow, 4 + ks, g);
 #pragma unroll
-        for (int ks = 0; ks < M::kSteps; ++ks) {
-          const M::frag bf = M::load(brow, ks, g);
-          acc[0] = M::mma(af[0][ks], bf, acc[0]);
-          acc[1] = M::mma(af[1][ks], bf, acc[1]);
-        }
-        // sign bits -> bit v of sg; adjacency = cosine - theta > 0
-        uint32_t sg0 = 0, sg1 = 0;
-        float mn = INFINITY;
+      for (int v = 11 - 3 * ks; v >= 9 - 3 * ks; --v) {
+        sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+        sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+        mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    r0 = M::mma(sg[0], af[0][4], r0);
+    r1 = M::mma(sg[0], af[1][4], r1);
+    uint32_t q0 = ~sg0 & 0xFFFFu, q1 = ~sg1 & 0xFFFFu;   // bit v: staged token 16*g + v
+    // pairs too close to theta for fp16: clear their bits now, queue them for the exact
+    // decision.  Bit 16*cb + v of `rest` = close.
+    uint32_t rest = 0;
+    const bool any_close = __any(mn < band);
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(sg[1], af[0][5], r0);
+    r1 = M::mma(sg[1], af[1][5], r1);
+    if (any_close) {
+      uint32_t cm0 = 0, cm1 = 0;
 #pragma unroll
-        for (int v = 15; v >= 0; --v) {
-          sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(acc[0][v]), 31);
-          sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(acc[1][v]), 31);
-          mn = min3_abs(mn, acc[0][v], acc[1][v], sg0, sg1);
-        }
-        uint32_t q[2] = {~sg0 & 0xFFFFu, ~sg1 & 0xFFFFu};
-        const int b = bcol0 + c;
-        // pairs too close to theta for fp16: clear their bits now, queue them for the exact
-        // decision after this tile's words are stored.  Bit 16*rb + v of `rest` = close.
-        uint32_t rest = 0;
-        const bool any_close = __any(mn < band);
-        if (any_close) {
-          uint32_t cm0 = 0, cm1 = 0;
+      for (int v = 15; v >= 0; --v) {
+        cm0 = __builtin_amdgcn_alignbit(cm0, __float_as_uint(fabsf(a0[v]) - band), 31);
+        cm1 = __builtin_amdgcn_alignbit(cm1, __float_as_uint(fabsf(a1[v]) - band), 31);
+      }
+      q0 &= ~cm0;
+      q1 &= ~cm1;
+      rest = (cm0 & 0xFFFFu) | (cm1 << 16);
+    }
+    if (bcol0 < arow0 + 64 && bcol0 + 32 > arow0) {   // tile touches the diagonal: G_aa = 1
 #pragma unroll
-          for (int v = 15; v >= 0; --v) {
-            cm0 = __builtin_amdgcn_alignbit(cm0, __float_as_uint(fabsf(acc[0][v]) - band), 31);
-            cm1 = __builtin_amdgcn_alignbit(cm1, __float_as_uint(fabsf(acc[1][v]) - band), 31);
-          }
-          q[0] &= ~cm0;
-          q[1] &= ~cm1;
-          rest = (cm0 & 0xFFFFu) | (cm1 << 16);
-        }
-        if (bcol0 < arow0 + 64 && bcol0 + 32 > arow0) {   // tile touches the diagonal: G_aa = 1
-          const int i = b - arow0;
-          if (i >= 0 && i < 64 && ((i & 7) >> 2) == g) q[i >> 5] |= 1u << (4 * ((i & 31) >> 3) + (i & 3));
-        }
-        q[0] &= rowmask[0];                               // tokens a beyond the sequence
-        q[1] &= rowmask[1];
-        const uint32_t own = q[0] | (q[1] << 16);
-        const uint32_t other = __shfl_xor(own, 32);
-        const uint32_t mine = (own >> (16 * g)) & 0xFFFFu, theirs = (other >> (16 * g)) & 0xFFFFu;
-        const uint32_t word = (spread_nibbles(mine) << (4 * g)) | (spread_nibbles(theirs) << (4 * (1 - g)));
-        if (b < n) Gut[(size_t)b * p.Wp + (arow0 >> 5) + g] = word;
-        if (any_close) {
-          while (__any(rest != 0)) {
-            const bool has = rest != 0;
-            const int i = has ? __builtin_ctz(rest) : 0;
-            rest &= rest - 1;
-            const int a = arow0 + 32 * (i >> 4) + mma_row(i & 15, g);
-            const unsigned long long m = __ballot(has && a < n && b < n && a != b);
-            if (m) {                                    // wave-uniform
-              if (nbuf > kPairBuf - 64) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
-              if ((m >> lane) & 1ull) buf[nbuf + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)b << 16) | (uint32_t)a;
-              nbuf += __popcll(m);
-            }
-          }
+      for (int cb = 0; cb < 2; ++cb) {
+        const int i = arow0 + 32 * cb + c - bcol0;    // staged index of this lane's own token
+        if (i >= 0 && i < 32 && (i >> 4) == g) {
+          if (cb == 0) q0 |= 1u << (i & 15); else q1 |= 1u << (i & 15);
         }
       }
     }
-    if (more) stash(stage + ((s + 1) & 1) * kStageBytes);
-    __syncthreads();
+    if (bcol0 + 32 > n) {                             // staged tokens beyond the sequence
+      const int nv = n - bcol0 - 16 * g;
+      const uint32_t keep = nv >= 16 ? 0xFFFFu : (nv <= 0 ? 0u : (1u << nv) - 1u);
+      q0 &= keep;
+      q1 &= keep;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(sg[2], af[0][6], r0);
+    r1 = M::mma(sg[2], af[1][6], r1);
+    const uint32_t own = q0 | (q1 << 16);
+    const uint32_t other = __shfl_xor(own, 32);
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(sg[3], af[0][7], r0);
+    r1 = M::mma(sg[3], af[1][7], r1);
+    // lane group 0 keeps the word of row block 0 (low halves), group 1 that of block 1
+    const uint32_t word = __builtin_amdgcn_perm(own, other, wsel);
+    if (any_close) {
+      while (__any(rest != 0)) {
+        const bool has = rest != 0;
+        const int i = has ? __builtin_ctz(rest) : 0;
+        rest &= rest - 1;
+        const int row = arow0 + 32 * (i >> 4) + c;          // row of G
+        const int bit = bcol0 + 16 * g + (i & 15);           // staged token
+        const bool valid = has && row < n && bit < n && row != bit;
+        if (kExact) {
+          if (valid && cos64(p, ut, row, bit) > (double)p.theta[ut / p.U])
+            atomicOr(p.G + ((size_t)ut * n + row) * p.Wp + (bit >> 5), 1u << (bit & 31));
+          continue;
+        }
+        const unsigned long long m = __ballot(valid);
+        if (m) {                                    // wave-uniform
+          if (nbuf > kPairBuf - 64) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
+          if ((m >> lane) & 1ull) buf[nbuf + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)row << 16) | (uint32_t)bit;
+          nbuf += __popcll(m);
+        }
+      }
+    }
+    return word;
+  };
+
+  fetch(col_begin);
+  stash(stage);
+  __syncthreads();
+  f16v cur0, cur1, nxt0, nxt1;
+  {
+    // first tile of the chunk: nothing to pack yet
+    const char *srow = stage + prow * kLdsRow;
+    cur0 = cinit;
+    cur1 = cinit;
+#pragma unroll
+    for (int ks = 0; ks < M::kSteps; ++ks) {
+      const M::frag f = M::load(srow, ks, g);
+      cur0 = M::mma(f, af[0][ks], cur0);
+      cur1 = M::mma(f, af[1][ks], cur1);
+    }
   }
-  if (nbuf) flush_pairs(p, ut, buf, nbuf);
+  u4 words = {0, 0, 0, 0};
+  // four tiles (two stages) per trip: their words are one aligned 16-byte piece of the row.
+  // The trip is branch-free: tiles past the end of the chunk only occur at the end of the
+  // sequence, read zero vectors and give zero words.
+  for (int t0 = 0; t0 < ntiles; t0 += 4) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = t0 + j;                          // tile, stage t/2, half t&1
+      const int bcol0 = col_begin + t * 32;
+      if ((j & 1) == 0) {
+        fetch(bcol0 + kStageCols);                   // next stage, in flight during two tiles
+        words[j] = step(stage + ((t >> 1) & 1) * kStageBytes, 1, bcol0, cur0, cur1, nxt0, nxt1);
+      } else {
+        stash(stage + (((t >> 1) + 1) & 1) * kStageBytes);
+        __syncthreads();
+        words[j] = step(stage + (((t >> 1) + 1) & 1) * kStageBytes, 0, bcol0, cur0, cur1, nxt0, nxt1);
+      }
+      cur0 = nxt0;
+      cur1 = nxt1;
+    }
+    if (!kExact && myrow < n) *reinterpret_cast<u4 *>(Grow + ((col_begin + t0 * 32) >> 5)) = words;
+  }
+  if (nbuf) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
+  __syncthreads();                                 // the stage buffers are reused by the next item
+  }
 }
 
 // ---------------------------------------------------------------- exact fix-up
@@ -424,25 +491,50 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
 // in LDS when they fit: the neighbour look-ups and the degree updates of Eq. 13 are then
 // LDS gathers and LDS atomics.  Rows are handled by 16-lane segments of a wave.
 constexpr int kMergeThreads = 1024;
-constexpr int kMergeSegs = kMergeThreads / 16;
+constexpr int kSegW = 8;                 // lanes that share one row
+constexpr int kMergeSegs = kMergeThreads / kSegW;
 constexpr int kKeysInLds = 36 * 1024;   // tokens whose keys fit in LDS next to the other buffers
 
-// Calls f(b) for every neighbour b of token v, the work split over the 16 lanes of a segment.
-template <typename F>
-__device__ __forceinline__ void for_each_neighbour(const ShallowParams &p, size_t base, int v, int sl, F f) {
+// The part of a row's neighbourhood one lane of a segment looks at: up to 16 list entries,
+// or (dense rows) every eighth 16-byte piece of the bitmap row.
+struct Nbrs {
+  u4 q0, q1;
+  int cnt;        // list entries of this lane; -1: dense row, walk the bitmap
+  const u4 *row;
+};
+
+__device__ __forceinline__ Nbrs load_nbrs(const ShallowParams &p, size_t base, int v, int sl) {
+  Nbrs r;
+  r.q0 = u4{0, 0, 0, 0};
+  r.q1 = r.q0;
+  r.row = nullptr;
   const int d0 = p.deg0[base + v];
   if (d0 <= kListCap) {
-    if (sl * 8 < d0) {
-      const u4 q = *reinterpret_cast<const u4 *>(p.nbr + (base + v) * kListCap + sl * 8);
-      const int cnt = d0 - sl * 8 < 8 ? d0 - sl * 8 : 8;
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (j < cnt) f((int)((q[j >> 1] >> (16 * (j & 1))) & 0xFFFFu));
-    }
+    const int c = d0 - sl * 16;
+    r.cnt = c < 0 ? 0 : (c > 16 ? 16 : c);
+    const u4 *src = reinterpret_cast<const u4 *>(p.nbr + (base + v) * kListCap + sl * 16);
+    r.q0 = src[0];      // unconditional: the 256-byte slot exists for every row, and the loads
+    r.q1 = src[1];      // then do not wait for the degree
   } else {
-    const u4 *row = reinterpret_cast<const u4 *>(p.G + (base + v) * p.Wp);
-    for (int w4 = sl; w4 < p.Wp / 4; w4 += 16) {
-      const u4 q = row[w4];
+    r.cnt = -1;
+    r.row = reinterpret_cast<const u4 *>(p.G + (base + v) * p.Wp);
+  }
+  return r;
+}
+
+// Calls f(b) for every neighbour b in this lane's part of the row.
+template <typename F>
+__device__ __forceinline__ void for_nbrs(const ShallowParams &p, const Nbrs &r, int sl, F f) {
+  if (r.cnt >= 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < r.cnt) f((int)((r.q0[j >> 1] >> (16 * (j & 1))) & 0xFFFFu));
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (8 + j < r.cnt) f((int)((r.q1[j >> 1] >> (16 * (j & 1))) & 0xFFFFu));
+  } else {
+    for (int w4 = sl; w4 < p.Wp / 4; w4 += kSegW) {
+      const u4 q = r.row[w4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         uint32_t bits = q[j];
@@ -456,9 +548,9 @@ __device__ __forceinline__ void for_each_neighbour(const ShallowParams &p, size_
   }
 }
 
-__device__ __forceinline__ uint32_t seg_max(uint32_t v) {   // over a 16-lane segment
+__device__ __forceinline__ uint32_t seg_max(uint32_t v) {   // over a segment
 #pragma unroll
-  for (int o = 8; o > 0; o >>= 1) {
+  for (int o = kSegW / 2; o > 0; o >>= 1) {
     const uint32_t x = __shfl_xor(v, o);
     v = x > v ? x : v;
   }
@@ -490,7 +582,8 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
   __shared__ int sh_n[4];                     // alive, candidates, dying, picks
   __shared__ uint32_t sh_keys[1024];
   const int ut = blockIdx.x, n = p.n, tid = threadIdx.x;
-  const int lane = lane_id(), sl = lane & 15, seg = tid >> 4, wave = tid >> 6;
+  const int lane = lane_id(), sl = lane & (kSegW - 1), seg = tid / kSegW, wave = tid >> 6;
+  constexpr int kSegsPerWave = kWave / kSegW;
   const size_t base = (size_t)ut * n;
   const bool keys_in_lds = n <= kKeysInLds;
   uint32_t *key = keys_in_lds ? lds : p.key + base;
@@ -515,34 +608,51 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
   __syncthreads();
   MERGE_TICK(0)
 
+  // every round removes at least the token of largest key, so n rounds always suffice;
+  // the bound only guards against a corrupted adjacency matrix
   int round = 0;
-  for (;; ++round) {
+  for (; round <= n; ++round) {
     const int nalive = sh_n[0];
     if (nalive == 0) break;
-    // one-hop maxima
-    for (int i0 = seg & ~3; i0 < nalive; i0 += kMergeSegs) {   // the 4 segments of a wave stay together
-      const int i = i0 + (seg & 3);
-      const bool on = i < nalive;
-      const int v = on ? alive[i] : 0;
-      uint32_t m = 0;
-      if (on) for_each_neighbour(p, base, v, sl, [&](int b) { const uint32_t k = key[b]; m = k > m ? k : m; });
-      m = seg_max(m);
-      if (on && sl == 0) {
-        m1[v] = m;
-        if (m == key[v]) cand[atomicAdd(&sh_n[1], 1)] = v;
+    // one-hop maxima; four rows per segment in flight to overlap their list loads
+    for (int i0 = seg - seg % kSegsPerWave; i0 < nalive; i0 += 4 * kMergeSegs) {   // a wave's segments stay together
+      int vv[4];
+      bool on[4];
+      Nbrs r[4];
+      uint32_t m[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int i = i0 + seg % kSegsPerWave + k * kMergeSegs;
+        on[k] = i < nalive;
+        vv[k] = on[k] ? alive[i] : 0;
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) r[k] = load_nbrs(p, base, vv[k], sl);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        uint32_t mk = on[k] ? key[vv[k]] : 0;          // a token is its own neighbour
+        if (on[k]) for_nbrs(p, r[k], sl, [&](int b) { const uint32_t kk = key[b]; mk = kk > mk ? kk : mk; });
+        m[k] = seg_max(mk);
+      }
+      if (sl == 0) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (on[k]) { m1[vv[k]] = m[k]; if (m[k] == key[vv[k]]) cand[atomicAdd(&sh_n[1], 1)] = vv[k]; }
       }
     }
     __syncthreads();
     MERGE_TICK(2)
     // two-hop maxima are picked; their remaining neighbours get the pick's slot
     const int ncand = sh_n[1];
-    for (int i0 = seg & ~3; i0 < ncand; i0 += kMergeSegs) {
-      const int i = i0 + (seg & 3);
+    for (int i0 = seg - seg % kSegsPerWave; i0 < ncand; i0 += kMergeSegs) {
+      const int i = i0 + seg % kSegsPerWave;
       const bool on = i < ncand;
       const int uvert = on ? cand[i] : 0;
       const uint32_t ku = on ? key[uvert] : 0xFFFFFFFFu;
+      Nbrs r;
+      if (on) r = load_nbrs(p, base, uvert, sl);
       uint32_t m = 0;
-      if (on) for_each_neighbour(p, base, uvert, sl, [&](int b) {
+      if (on) for_nbrs(p, r, sl, [&](int b) {
         if (key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; }
       });
       m = seg_max(m);
@@ -553,8 +663,8 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
         pick_key[s] = ku;
         pick_vert[s] = uvert;
       }
-      s = __shfl(s, lane & 48);
-      if (picked) for_each_neighbour(p, base, uvert, sl, [&](int b) {
+      s = __shfl(s, lane & ~(kSegW - 1));
+      if (picked) for_nbrs(p, r, sl, [&](int b) {
         if (key[b] != 0) {
           slot[b] = s;
           atomicOr(&gone[b >> 5], 1u << (b & 31));
@@ -566,11 +676,21 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
     MERGE_TICK(4)
     // removed tokens no longer count towards their neighbours' degrees (Eq. 13)
     const int ndying = sh_n[2];
-    for (int i0 = seg & ~3; i0 < ndying; i0 += kMergeSegs) {
-      const int i = i0 + (seg & 3);
-      if (i < ndying) for_each_neighbour(p, base, dying[i], sl, [&](int w) {
+    for (int i0 = seg - seg % kSegsPerWave; i0 < ndying; i0 += 4 * kMergeSegs) {
+      Nbrs r[4];
+      bool on[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int i = i0 + seg % kSegsPerWave + k * kMergeSegs;
+        on[k] = i < ndying;
+        r[k] = load_nbrs(p, base, on[k] ? dying[i] : 0, sl);
+      }
+      auto drop = [&](int w) {
         if (key[w] != 0 && !((gone[w >> 5] >> (w & 31)) & 1u)) atomicSub(&key[w], 1u << 16);
-      });
+      };
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (on[k]) for_nbrs(p, r[k], sl, drop);
     }
     __syncthreads();
     MERGE_TICK(6)
@@ -597,6 +717,7 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
     MERGE_TICK(0)
   }
   if (tid == 0) cnt[C_ROUNDS] = round;
+  if (sh_n[0] != 0) return;                      // did not converge: n_codes stays -1
 
   // codebook order: rank of each pick among all picks by decreasing key
   const int P = sh_n[3];
@@ -610,6 +731,7 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
       sh_keys[tid] = b0 + tid < P ? pick_key[b0 + tid] : 0u;
       __syncthreads();
       const int lim = P - b0 < 1024 ? P - b0 : 1024;
+#pragma unroll 8
       for (int j = 0; j < lim; ++j) r += sh_keys[j] > ks;
     }
     if (s < P) { rank[s] = r; rank_vert[r] = pick_vert[s]; }
@@ -692,7 +814,7 @@ struct ShallowLayout {
 size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   Carver cv(ws);
   const size_t N = (size_t)UT * n;
-  p.Wp = ((n + 255) / 256) * 8;
+  p.Wp = ((n + 127) / 128) * 4;   // whole 16-byte pieces: shallow_gram writes every word of a row
   p.Xh = cv.take<_Float16>(N * kHeadDim);
   p.m64 = cv.take<double>(N);
   p.G = cv.take<uint32_t>(N * p.Wp);
@@ -717,6 +839,7 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.counters = cv.take<int>((size_t)UT * kCounters + 4 + (size_t)UT);
   int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
   p.ovf_count = reinterpret_cast<unsigned *>(tail);
+  p.fix_overflow = reinterpret_cast<unsigned *>(tail ? tail + 1 : nullptr);
   p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
   return cv.total();
 }
@@ -823,7 +946,9 @@ extern "C" spindle_status spindle_compress_shallow(
   const int nI = (n + kPanelRows - 1) / kPanelRows, nJ = (n + kChunkCols - 1) / kChunkCols;
   const int pairs8 = (p.UT * nJ + 7) / 8;
   { ProfScope ps("shallow_gram", st);
-  hipLaunchKernelGGL(shallow_gram, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p); }
+  hipLaunchKernelGGL(shallow_gram<false>, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p); }
+  { ProfScope ps("shallow_gram_exact", st);
+  hipLaunchKernelGGL(shallow_gram<true>, dim3(1024), dim3(kGramThreads), 0, st, p); }
   { ProfScope ps("shallow_fixup", st);
   hipLaunchKernelGGL(shallow_fixup, dim3(1024), dim3(256), 0, st, p); }
   SPINDLE_HIP(hipGetLastError());
