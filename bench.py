@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--seq-len", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (scale reference for the HBM traffic counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "shallow_gram_config4_traffic.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -79,6 +81,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # timed region: whole-step wall time, and per-kernel HIP events on the launch stream
     sb.spindle_profile(True)

@@ -31,7 +31,8 @@ constexpr float kUnitScale = 1024.f;
 constexpr float kGuard = 1.05e-3f;
 
 constexpr int kPanelRows = 256;   // rows of G's column range held in registers per block
-constexpr int kChunkCols = 1024;  // tokens streamed through LDS per block
+constexpr int kChunkCols = 1024;  // tokens per chunk: one 128-byte line of each row of G
+constexpr int kItemChunks = 4;    // chunks a block handles with the same rows in registers
 constexpr int kStageCols = 64;
 constexpr int kGramThreads = 256;
 constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad
@@ -205,9 +206,13 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   typedef Mma<SPINDLE_F16> M;
   __shared__ __attribute__((aligned(16))) char stage[2 * kStageBytes];
   __shared__ uint32_t pairbuf[kGramThreads / 64][kPairBuf];
+  // the 32 words (one 128-byte line) of each of a wave's 64 rows for the current chunk;
+  // written out as whole lines, because partially written lines cost several times their
+  // size in HBM write traffic.  Row pitch 36 words keeps 16-byte alignment.
+  __shared__ __attribute__((aligned(16))) uint32_t wstage[kGramThreads / 64][64][36];
   const int n = p.n;
   const int nI = (n + kPanelRows - 1) / kPanelRows;
-  const int nJ = (n + kChunkCols - 1) / kChunkCols;
+  const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
   // blocks are dealt round-robin to the 8 XCDs: give each XCD one (ut, chunk) at a time
   // and let it sweep the row panels, so the chunk is re-read from that XCD's L2
   if (kExact && *p.fix_overflow == 0) return;
@@ -217,13 +222,12 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   const int I = s_ % nI;
   const int pj = (s_ / nI) * 8 + xcd;
   if (pj >= p.UT * nJ) continue;
-  const int ut = pj / nJ, J = pj % nJ;
+  const int ut = pj / nJ, Jg = pj % nJ;
   const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
   const float band = kGuard * kUnitScale * kUnitScale;
   const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
   const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
   const int arow0 = I * kPanelRows + 64 * wave;   // first of this wave's 64 rows of G
-  const int myrow = arow0 + lane;                  // the row of G whose words this lane stores
   uint32_t *buf = pairbuf[wave];
   int nbuf = 0;                                    // wave-uniform
 
@@ -240,6 +244,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
 #pragma unroll
   for (int v = 0; v < 16; ++v) cinit[v] = -theta_s;
 
+  for (int J = Jg * kItemChunks; J < (Jg + 1) * kItemChunks && J * kChunkCols < n; ++J) {
   const int col_begin = J * kChunkCols;
   const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
   const int ntiles = (col_end - col_begin + 31) / 32;
@@ -269,7 +274,6 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   // signs of the CURRENT tile into the word of this lane's row of G.  The two instruction
   // streams are independent; sched_barrier pins the issue order (two matrix instructions,
   // then a slice of vector work) so that neither unit waits for the other.
-  uint32_t *Grow = p.G + ((size_t)ut * n + (myrow < n ? myrow : 0)) * p.Wp;
   auto step = [&](const char *lds, int ct, int bcol0, const f16v &a0, const f16v &a1, f16v &r0,
                   f16v &r1) -> uint32_t {
     const char *srow = lds + (ct * 32 + prow) * kLdsRow;
@@ -405,10 +409,21 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       cur0 = nxt0;
       cur1 = nxt1;
     }
-    if (!kExact && myrow < n) *reinterpret_cast<u4 *>(Grow + ((col_begin + t0 * 32) >> 5)) = words;
+    if (!kExact) *reinterpret_cast<u4 *>(&wstage[wave][lane][t0]) = words;
+  }
+  if (!kExact) {
+    const int npieces = (ntiles + 3) / 4, piece = lane & 7;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 8 + (lane >> 3);
+      const u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][r][piece * 4]);
+      if (arow0 + r < n && piece < npieces)
+        *reinterpret_cast<u4 *>(p.G + ((size_t)ut * n + arow0 + r) * p.Wp + (col_begin >> 5) + piece * 4) = v;
+    }
+  }
+  __syncthreads();                                 // the stage buffers are reused by the next chunk
   }
   if (nbuf) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
-  __syncthreads();                                 // the stage buffers are reused by the next item
   }
 }
 
@@ -943,7 +958,8 @@ extern "C" spindle_status spindle_compress_shallow(
   else if (p.dtype == SPINDLE_BF16) hipLaunchKernelGGL(shallow_prep<SPINDLE_BF16>, pgrid, dim3(256), 0, st, p);
   else hipLaunchKernelGGL(shallow_prep<SPINDLE_F32>, pgrid, dim3(256), 0, st, p); }
 
-  const int nI = (n + kPanelRows - 1) / kPanelRows, nJ = (n + kChunkCols - 1) / kChunkCols;
+  const int nI = (n + kPanelRows - 1) / kPanelRows;
+  const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
   const int pairs8 = (p.UT * nJ + 7) / 8;
   { ProfScope ps("shallow_gram", st);
   hipLaunchKernelGGL(shallow_gram<false>, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p); }
