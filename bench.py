@@ -156,7 +156,11 @@ def main():
                             "unit": "GB/s", "frac": deep_bytes / (ms_deep * 1e-3) / 1e9 / PEAK_HBM_GBS}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, wl)
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    # release device memory before interpreter shutdown
+    del deep, shallow, K, V, Q
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

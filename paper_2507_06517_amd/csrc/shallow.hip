@@ -177,7 +177,7 @@ constexpr int kPairBuf = 256;   // queued pairs per wave before a flush
 // pairs are dropped and a flag is raised: shallow_gram<true> then decides every close
 // pair of every tile in place (slow, but only for inputs with an extreme number of
 // similarities within the guard band of theta).
-__device__ __noinline__ void flush_pairs(const ShallowParams &p, int ut, const uint32_t *buf, int count) {
+__device__ __forceinline__ void flush_pairs(const ShallowParams &p, int ut, const uint32_t *buf, int count) {
   const int lane = lane_id();
   unsigned base = 0;
   if (lane == 0) base = atomicAdd(p.fix_count + ut, (unsigned)count);
