@@ -10,6 +10,7 @@
 //   shallow_lists   degrees (Eq. 10) and compact neighbour lists of the sparse rows of G
 //   shallow_merge   the greedy highest-degree codebook construction (Eq. 11-13), all
 //                   rounds on the device, one workgroup per problem
+//   shallow_emit    references in codebook order and the codebook vectors
 //   shallow_overflow  re-points tokens whose entry fell beyond the codebook cap
 #include <math.h>
 #include <string.h>
@@ -50,7 +51,7 @@ struct ShallowParams {
   _Float16 *Xh;            // [UT][n][128] unit vectors
   double *m64;             // [UT][n]
   uint32_t *G;             // [UT][n][Wp]
-  int *deg0, *slot, *alive, *cand, *dying, *pick_vert, *rank, *rank_vert;   // [UT][n]
+  int *deg0, *slot, *alive, *alive2, *cand, *dying, *pick_vert, *rank, *rank_vert;   // [UT][n]
   uint16_t *nbr;           // [UT][n][kListCap] neighbour lists of the sparse rows
   uint32_t *key, *gone, *m1, *pick_key;                                      // [UT][n]
   int *counters;           // [UT][kCounters]
@@ -471,6 +472,11 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
     if (lane == 0) {
       const size_t i = (size_t)ut * n + v;
       p.deg0[i] = deg;
+      p.key[i] = ((uint32_t)deg << 16) | (uint32_t)(0xFFFF - v);
+      p.alive[i] = v;
+      p.slot[i] = -1;
+      if ((v & 31) == 0) p.gone[(size_t)ut * n + (v >> 5)] = 0;
+      if (v == 0) p.counters[(size_t)ut * kCounters + C_ALIVE0] = n;
       if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = deg;
     }
     if (deg <= kListCap) {
@@ -501,13 +507,20 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
 // maximum at once; sorting all picks by their key at pick time (which strictly decreases
 // along the sequential loop) restores the codebook order.
 //
-// One workgroup of 1024 threads per ut, so the phases of a round are separated by
-// workgroup barriers only.  The keys (degree << 16 | 0xFFFF - index, 0 once removed) live
-// in LDS when they fit: the neighbour look-ups and the degree updates of Eq. 13 are then
-// LDS gathers and LDS atomics.  Rows are handled by 16-lane segments of a wave.
+// A round has four phases, each a loop over a list of tokens:
+//   one-hop   m1[v] = largest key in v's closed neighbourhood; v is a candidate if it is its own
+//   two-hop   a candidate whose neighbours' m1 never exceed its key is picked: its remaining
+//             neighbours get its slot, are queued as `dying` and marked in the `dead` bitmap
+//   degree    neighbours of dying tokens that stay lose one degree (Eq. 13)
+//   compact   keys of dying tokens become 0, the list of remaining tokens is rebuilt
+// The first kGridRounds rounds, where most tokens are still there, run as grid-wide kernels
+// (one launch per phase, state in global memory); the remaining rounds run in one
+// 1024-thread workgroup per problem with keys and the dead bitmap in LDS, separated by
+// workgroup barriers only.  Rows are handled by 8-lane segments, four rows in flight.
 constexpr int kMergeThreads = 1024;
 constexpr int kSegW = 8;                 // lanes that share one row
-constexpr int kMergeSegs = kMergeThreads / kSegW;
+constexpr int kGridRounds = 2;
+constexpr int kPhaseThreads = 256;
 constexpr int kKeysInLds = 36 * 1024;   // tokens whose keys fit in LDS next to the other buffers
 
 // The part of a row's neighbourhood one lane of a segment looks at: up to 16 list entries,
@@ -520,20 +533,13 @@ struct Nbrs {
 
 __device__ __forceinline__ Nbrs load_nbrs(const ShallowParams &p, size_t base, int v, int sl) {
   Nbrs r;
-  r.q0 = u4{0, 0, 0, 0};
-  r.q1 = r.q0;
-  r.row = nullptr;
   const int d0 = p.deg0[base + v];
-  if (d0 <= kListCap) {
-    const int c = d0 - sl * 16;
-    r.cnt = c < 0 ? 0 : (c > 16 ? 16 : c);
-    const u4 *src = reinterpret_cast<const u4 *>(p.nbr + (base + v) * kListCap + sl * 16);
-    r.q0 = src[0];      // unconditional: the 256-byte slot exists for every row, and the loads
-    r.q1 = src[1];      // then do not wait for the degree
-  } else {
-    r.cnt = -1;
-    r.row = reinterpret_cast<const u4 *>(p.G + (base + v) * p.Wp);
-  }
+  const u4 *src = reinterpret_cast<const u4 *>(p.nbr + (base + v) * kListCap + sl * 16);
+  r.q0 = src[0];      // unconditional: the 256-byte slot exists for every row, and the loads
+  r.q1 = src[1];      // then do not wait for the degree
+  r.row = reinterpret_cast<const u4 *>(p.G + (base + v) * p.Wp);
+  const int c = d0 - sl * 16;
+  r.cnt = d0 <= kListCap ? (c < 0 ? 0 : (c > 16 ? 16 : c)) : -1;
   return r;
 }
 
@@ -572,6 +578,178 @@ __device__ __forceinline__ uint32_t seg_max(uint32_t v) {   // over a segment
   return v;
 }
 
+// Where the state of one problem lives for the running kernel (LDS or global memory), and
+// which segments of the launch work on it: segment `seg` of `nsegs`, a wave's segments
+// being consecutive.
+struct MergeView {
+  uint32_t *key;        // (remaining degree << 16) | (0xFFFF - index); 0 once removed
+  uint32_t *dead;       // bit v set once token v has been given a slot
+  int *n_alive, *n_cand, *n_dying, *n_picks;
+  int seg, nsegs, sl;
+};
+
+__device__ __forceinline__ void phase_onehop(const ShallowParams &p, size_t base, const MergeView &w,
+                                             const int *alive, int nalive) {
+  constexpr int kPer = kWave / kSegW;
+  uint32_t *m1 = p.m1 + base;
+  int *cand = p.cand + base;
+  for (int i0 = w.seg - w.seg % kPer; i0 < nalive; i0 += 4 * w.nsegs) {
+    int vv[4];
+    bool on[4];
+    Nbrs r[4];
+    uint32_t m[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + w.seg % kPer + k * w.nsegs;
+      on[k] = i < nalive;
+      vv[k] = on[k] ? alive[i] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r[k] = load_nbrs(p, base, vv[k], w.sl);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      uint32_t mk = on[k] ? w.key[vv[k]] : 0;          // a token is its own neighbour
+      if (on[k]) for_nbrs(p, r[k], w.sl, [&](int b) { const uint32_t kk = w.key[b]; mk = kk > mk ? kk : mk; });
+      m[k] = seg_max(mk);
+    }
+    if (w.sl == 0) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (on[k]) {
+          m1[vv[k]] = m[k];
+          if (m[k] == w.key[vv[k]]) cand[atomicAdd(w.n_cand, 1)] = vv[k];
+        }
+    }
+  }
+}
+
+__device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base, const MergeView &w, int ncand) {
+  constexpr int kPer = kWave / kSegW;
+  const uint32_t *m1 = p.m1 + base;
+  const int *cand = p.cand + base;
+  int *slot = p.slot + base, *dying = p.dying + base, *pick_vert = p.pick_vert + base;
+  uint32_t *pick_key = p.pick_key + base;
+  const int lane = lane_id();
+  for (int i0 = w.seg - w.seg % kPer; i0 < ncand; i0 += w.nsegs) {
+    const int i = i0 + w.seg % kPer;
+    const bool on = i < ncand;
+    const int uvert = on ? cand[i] : 0;
+    const uint32_t ku = on ? w.key[uvert] : 0xFFFFFFFFu;
+    const Nbrs r = load_nbrs(p, base, uvert, w.sl);
+    uint32_t m = 0;
+    // remaining = key != 0 (keys only change in the later phases of the round)
+    if (on) for_nbrs(p, r, w.sl, [&](int b) {
+      if (w.key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; }
+    });
+    m = seg_max(m);
+    const bool picked = on && m == ku;
+    int s = 0;
+    if (picked && w.sl == 0) {
+      s = atomicAdd(w.n_picks, 1);
+      pick_key[s] = ku;
+      pick_vert[s] = uvert;
+    }
+    s = __shfl(s, lane & ~(kSegW - 1));
+    if (picked) for_nbrs(p, r, w.sl, [&](int b) {
+      if (w.key[b] != 0) {
+        slot[b] = s;
+        atomicOr(&w.dead[b >> 5], 1u << (b & 31));
+        dying[atomicAdd(w.n_dying, 1)] = b;
+      }
+    });
+  }
+}
+
+__device__ __forceinline__ void phase_degree(const ShallowParams &p, size_t base, const MergeView &w, int ndying) {
+  constexpr int kPer = kWave / kSegW;
+  const int *dying = p.dying + base;
+  for (int i0 = w.seg - w.seg % kPer; i0 < ndying; i0 += 4 * w.nsegs) {
+    Nbrs r[4];
+    bool on[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + w.seg % kPer + k * w.nsegs;
+      on[k] = i < ndying;
+      r[k] = load_nbrs(p, base, on[k] ? dying[i] : 0, w.sl);
+    }
+    auto drop = [&](int b) {   // tokens that stay: not marked dead (the bitmap also covers earlier rounds)
+      if (!((w.dead[b >> 5] >> (b & 31)) & 1u)) atomicSub(&w.key[b], 1u << 16);
+    };
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (on[k]) for_nbrs(p, r[k], w.sl, drop);
+  }
+}
+
+__device__ __forceinline__ MergeView global_view(const ShallowParams &p, int ut) {
+  MergeView w;
+  const size_t base = (size_t)ut * p.n;
+  int *cnt = p.counters + (size_t)ut * kCounters;
+  w.key = p.key + base;
+  w.dead = p.gone + base;
+  w.n_alive = cnt + C_ALIVE0;   // the grid kernels address the two alive counters themselves
+  w.n_cand = cnt + C_CAND;
+  w.n_dying = cnt + C_DYING;
+  w.n_picks = cnt + C_PICKS;
+  w.seg = (blockIdx.x * kPhaseThreads + threadIdx.x) / kSegW;
+  w.nsegs = gridDim.x * kPhaseThreads / kSegW;
+  w.sl = threadIdx.x & (kSegW - 1);
+  return w;
+}
+
+// Grid-wide phases of round `round` (blockIdx.y = problem).  The list of remaining tokens
+// alternates between the `alive` and `alive2` rows, its length between counters 0 and 1.
+__global__ __launch_bounds__(kPhaseThreads) void merge_onehop(ShallowParams p, int round) {
+  const int ut = blockIdx.y;
+  const size_t base = (size_t)ut * p.n;
+  const MergeView w = global_view(p, ut);
+  const int *cnt = p.counters + (size_t)ut * kCounters;
+  phase_onehop(p, base, w, (round & 1 ? p.alive2 : p.alive) + base, cnt[round & 1]);
+}
+__global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p) {
+  const int ut = blockIdx.y;
+  const MergeView w = global_view(p, ut);
+  phase_twohop(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_CAND]);
+}
+__global__ __launch_bounds__(kPhaseThreads) void merge_degree(ShallowParams p) {
+  const int ut = blockIdx.y;
+  const MergeView w = global_view(p, ut);
+  phase_degree(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_DYING]);
+}
+// keys of the dying tokens -> 0; remaining tokens -> the other list; counters for the next round
+__global__ __launch_bounds__(kPhaseThreads) void merge_compact(ShallowParams p, int round) {
+  const int ut = blockIdx.y, lane = lane_id();
+  const size_t base = (size_t)ut * p.n;
+  int *cnt = p.counters + (size_t)ut * kCounters;
+  const int nalive = cnt[round & 1];
+  const int *src = (round & 1 ? p.alive2 : p.alive) + base;
+  int *dst = (round & 1 ? p.alive : p.alive2) + base;
+  const uint32_t *dead = p.gone + base;
+  uint32_t *key = p.key + base;
+  const int stride = gridDim.x * kPhaseThreads;
+  for (int i0 = blockIdx.x * kPhaseThreads + threadIdx.x - lane; i0 < nalive; i0 += stride) {
+    const int i = i0 + lane;
+    const int v = i < nalive ? src[i] : -1;
+    const bool gone = v >= 0 && ((dead[v >> 5] >> (v & 31)) & 1u);
+    if (gone) key[v] = 0;
+    const bool live = v >= 0 && !gone;
+    const unsigned long long mk = __ballot(live);
+    int at = 0;
+    if (lane == 0 && mk) at = atomicAdd(&cnt[(round & 1) ^ 1], __popcll(mk));
+    at = __shfl(at, 0);
+    if (live) dst[at + __popcll(mk & ((1ull << lane) - 1ull))] = v;
+  }
+}
+// between rounds: the counters of the finished round start again at zero
+__global__ void merge_reset(ShallowParams p, int round) {
+  const int ut = blockIdx.x * blockDim.x + threadIdx.x;
+  if (ut >= p.UT) return;
+  int *cnt = p.counters + (size_t)ut * kCounters;
+  cnt[round & 1] = 0;
+  cnt[C_CAND] = 0;
+  cnt[C_DYING] = 0;
+}
+
 template <int DT>
 __device__ __forceinline__ void emit_code(const ShallowParams &p, int ut, int vert, int r) {
   typedef typename Elem<DT>::type T;
@@ -592,124 +770,55 @@ __device__ __forceinline__ void emit_code(const ShallowParams &p, int ut, int ve
     tick_ = now_;                              \
   }
 
+// Remaining rounds and the outputs, one workgroup per problem.
 __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   __shared__ int sh_n[4];                     // alive, candidates, dying, picks
   __shared__ uint32_t sh_keys[1024];
   const int ut = blockIdx.x, n = p.n, tid = threadIdx.x;
-  const int lane = lane_id(), sl = lane & (kSegW - 1), seg = tid / kSegW, wave = tid >> 6;
-  constexpr int kSegsPerWave = kWave / kSegW;
+  const int lane = lane_id(), wave = tid >> 6;
   const size_t base = (size_t)ut * n;
   const bool keys_in_lds = n <= kKeysInLds;
-  uint32_t *key = keys_in_lds ? lds : p.key + base;
-  // removed-this-round bits: after the keys in LDS, or in a global scratch row
-  uint32_t *gone = keys_in_lds ? lds + ((n + 3) & ~3) : p.gone + base;
-  int *slot = p.slot + base, *alive = p.alive + base, *dying = p.dying + base, *cand = p.cand + base;
-  int *pick_vert = p.pick_vert + base, *rank = p.rank + base, *rank_vert = p.rank_vert + base;
-  uint32_t *m1 = p.m1 + base, *pick_key = p.pick_key + base;
-  const int *deg0 = p.deg0 + base;
+  const int dead_words = (n + 31) / 32;
   int *cnt = p.counters + (size_t)ut * kCounters;
+  MergeView w;
+  w.key = keys_in_lds ? lds : p.key + base;
+  w.dead = keys_in_lds ? lds + ((n + 3) & ~3) : p.gone + base;
+  w.n_alive = &sh_n[0]; w.n_cand = &sh_n[1]; w.n_dying = &sh_n[2]; w.n_picks = &sh_n[3];
+  w.seg = tid / kSegW; w.nsegs = kMergeThreads / kSegW; w.sl = tid & (kSegW - 1);
+  int *slot = p.slot + base, *dying = p.dying + base;
+  int *pick_vert = p.pick_vert + base, *rank = p.rank + base, *rank_vert = p.rank_vert + base;
+  uint32_t *pick_key = p.pick_key + base;
+  // the list the last grid round left behind; this kernel compacts it in place
+  int *alive = (kGridRounds & 1 ? p.alive2 : p.alive) + base;
   long long tick_ = 0;
   if (tid == 0) tick_ = wall_clock64();
 
-  const int gone_words = (n + 31) / 32;
-  for (int v = tid; v < n; v += kMergeThreads) {
-    key[v] = ((uint32_t)deg0[v] << 16) | (uint32_t)(0xFFFF - v);
-    alive[v] = v;
-    slot[v] = -1;
+  if (keys_in_lds) {
+    for (int v = tid; v < n; v += kMergeThreads) w.key[v] = p.key[base + v];
+    for (int i = tid; i < dead_words; i += kMergeThreads) w.dead[i] = p.gone[base + i];
   }
-  for (int w = tid; w < gone_words; w += kMergeThreads) gone[w] = 0;
-  if (tid == 0) { sh_n[0] = n; sh_n[1] = 0; sh_n[2] = 0; sh_n[3] = 0; }
+  if (tid == 0) { sh_n[0] = cnt[kGridRounds & 1]; sh_n[1] = 0; sh_n[2] = 0; sh_n[3] = cnt[C_PICKS]; }
   __syncthreads();
   MERGE_TICK(0)
 
   // every round removes at least the token of largest key, so n rounds always suffice;
   // the bound only guards against a corrupted adjacency matrix
-  int round = 0;
-  for (; round <= n; ++round) {
+  int round = kGridRounds;
+  for (; round <= n + kGridRounds; ++round) {
     const int nalive = sh_n[0];
     if (nalive == 0) break;
-    // one-hop maxima; four rows per segment in flight to overlap their list loads
-    for (int i0 = seg - seg % kSegsPerWave; i0 < nalive; i0 += 4 * kMergeSegs) {   // a wave's segments stay together
-      int vv[4];
-      bool on[4];
-      Nbrs r[4];
-      uint32_t m[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int i = i0 + seg % kSegsPerWave + k * kMergeSegs;
-        on[k] = i < nalive;
-        vv[k] = on[k] ? alive[i] : 0;
-      }
-#pragma unroll
-      for (int k = 0; k < 4; ++k) r[k] = load_nbrs(p, base, vv[k], sl);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        uint32_t mk = on[k] ? key[vv[k]] : 0;          // a token is its own neighbour
-        if (on[k]) for_nbrs(p, r[k], sl, [&](int b) { const uint32_t kk = key[b]; mk = kk > mk ? kk : mk; });
-        m[k] = seg_max(mk);
-      }
-      if (sl == 0) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-          if (on[k]) { m1[vv[k]] = m[k]; if (m[k] == key[vv[k]]) cand[atomicAdd(&sh_n[1], 1)] = vv[k]; }
-      }
-    }
+    phase_onehop(p, base, w, alive, nalive);
     __syncthreads();
     MERGE_TICK(2)
-    // two-hop maxima are picked; their remaining neighbours get the pick's slot
-    const int ncand = sh_n[1];
-    for (int i0 = seg - seg % kSegsPerWave; i0 < ncand; i0 += kMergeSegs) {
-      const int i = i0 + seg % kSegsPerWave;
-      const bool on = i < ncand;
-      const int uvert = on ? cand[i] : 0;
-      const uint32_t ku = on ? key[uvert] : 0xFFFFFFFFu;
-      Nbrs r;
-      if (on) r = load_nbrs(p, base, uvert, sl);
-      uint32_t m = 0;
-      if (on) for_nbrs(p, r, sl, [&](int b) {
-        if (key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; }
-      });
-      m = seg_max(m);
-      const bool picked = on && m == ku;
-      int s = 0;
-      if (picked && sl == 0) {
-        s = atomicAdd(&sh_n[3], 1);
-        pick_key[s] = ku;
-        pick_vert[s] = uvert;
-      }
-      s = __shfl(s, lane & ~(kSegW - 1));
-      if (picked) for_nbrs(p, r, sl, [&](int b) {
-        if (key[b] != 0) {
-          slot[b] = s;
-          atomicOr(&gone[b >> 5], 1u << (b & 31));
-          dying[atomicAdd(&sh_n[2], 1)] = b;
-        }
-      });
-    }
+    phase_twohop(p, base, w, sh_n[1]);
     __syncthreads();
     MERGE_TICK(4)
-    // removed tokens no longer count towards their neighbours' degrees (Eq. 13)
     const int ndying = sh_n[2];
-    for (int i0 = seg - seg % kSegsPerWave; i0 < ndying; i0 += 4 * kMergeSegs) {
-      Nbrs r[4];
-      bool on[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int i = i0 + seg % kSegsPerWave + k * kMergeSegs;
-        on[k] = i < ndying;
-        r[k] = load_nbrs(p, base, on[k] ? dying[i] : 0, sl);
-      }
-      auto drop = [&](int w) {
-        if (key[w] != 0 && !((gone[w >> 5] >> (w & 31)) & 1u)) atomicSub(&key[w], 1u << 16);
-      };
-#pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (on[k]) for_nbrs(p, r[k], sl, drop);
-    }
+    phase_degree(p, base, w, ndying);
     __syncthreads();
     MERGE_TICK(6)
-    for (int i = tid; i < ndying; i += kMergeThreads) key[dying[i]] = 0;
+    for (int i = tid; i < ndying; i += kMergeThreads) w.key[dying[i]] = 0;
     if (tid == 0) { sh_n[0] = 0; sh_n[1] = 0; sh_n[2] = 0; }
     __syncthreads();
     // survivors, compacted in place (each wave appends its survivors with one LDS atomic;
@@ -718,7 +827,7 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
     for (int i0 = 0; i0 < nalive; i0 += kMergeThreads) {
       const int i = i0 + tid;
       const int v = i < nalive ? alive[i] : -1;
-      const bool live = v >= 0 && key[v] != 0;
+      const bool live = v >= 0 && w.key[v] != 0;
       __syncthreads();
       const unsigned long long mk = __ballot(live);
       int at = 0;
@@ -727,8 +836,6 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
       if (live) alive[at + __popcll(mk & ((1ull << lane) - 1ull))] = v;
       __syncthreads();
     }
-    for (int w = tid; w < gone_words; w += kMergeThreads) gone[w] = 0;
-    __syncthreads();
     MERGE_TICK(0)
   }
   if (tid == 0) cnt[C_ROUNDS] = round;
@@ -755,23 +862,32 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
   MERGE_TICK(8)
 
   const int t = ut / p.U, u = ut % p.U;
-  const int stored = P < p.cap ? P : p.cap;
   if (tid == 0) {
-    p.n_codes[t][u] = stored;
+    p.n_codes[t][u] = P < p.cap ? P : p.cap;
     if (p.n_found[t]) p.n_found[t][u] = P;
   }
-  for (int v = tid; v < n; v += kMergeThreads) {
+  MERGE_TICK(9)
+}
+
+// References (Eq. 12, renumbered in codebook order) and codebook entries (Eq. 11), grid-wide.
+__global__ __launch_bounds__(256) void shallow_emit(ShallowParams p) {
+  const int ut = blockIdx.y, n = p.n;
+  const size_t base = (size_t)ut * n;
+  const int t = ut / p.U, u = ut % p.U;
+  const int stored = p.n_codes[t][u];
+  if (stored < 0) return;                        // the merge did not finish
+  const int *rank = p.rank + base, *slot = p.slot + base, *rank_vert = p.rank_vert + base;
+  for (int v = blockIdx.x * 256 + threadIdx.x; v < n; v += gridDim.x * 256) {
     const int r = rank[slot[v]];
     p.ref[t][(size_t)u * n + v] = r;
     if (r >= p.cap) p.ovf[atomicAdd(p.ovf_count, 1u)] = ((uint32_t)ut << 16) | (uint32_t)v;
   }
-  for (int r = wave; r < stored; r += kMergeThreads / 64) {
+  for (int r = blockIdx.x * 4 + (threadIdx.x >> 6); r < stored; r += gridDim.x * 4) {
     const int vert = rank_vert[r];
     if (p.dtype == SPINDLE_F16) emit_code<SPINDLE_F16>(p, ut, vert, r);
     else if (p.dtype == SPINDLE_BF16) emit_code<SPINDLE_BF16>(p, ut, vert, r);
     else emit_code<SPINDLE_F32>(p, ut, vert, r);
   }
-  MERGE_TICK(9)
 }
 
 // ---------------------------------------------------------------- codebook cap
@@ -835,6 +951,7 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.G = cv.take<uint32_t>(N * p.Wp);
   p.deg0 = cv.take<int>(N);
   p.alive = cv.take<int>(N);
+  p.alive2 = cv.take<int>(N);
   p.gone = cv.take<uint32_t>(N);
   p.nbr = cv.take<uint16_t>(N * 128);
   p.slot = cv.take<int>(N);
@@ -971,11 +1088,27 @@ extern "C" spindle_status spindle_compress_shallow(
 
   { ProfScope ps("shallow_lists", st);
   hipLaunchKernelGGL(shallow_lists, dim3((n + 15) / 16, p.UT), dim3(256), 0, st, p); }
+  {
+    int gx = (n + 4 * (kPhaseThreads / kSegW) - 1) / (4 * (kPhaseThreads / kSegW));
+    if (gx > 256) gx = 256;
+    const dim3 pg(gx, p.UT);
+    for (int round = 0; round < kGridRounds; ++round) {
+      ProfScope ps("shallow_merge_grid", st);
+      hipLaunchKernelGGL(merge_onehop, pg, dim3(kPhaseThreads), 0, st, p, round);
+      hipLaunchKernelGGL(merge_twohop, pg, dim3(kPhaseThreads), 0, st, p);
+      hipLaunchKernelGGL(merge_degree, pg, dim3(kPhaseThreads), 0, st, p);
+      hipLaunchKernelGGL(merge_compact, pg, dim3(kPhaseThreads), 0, st, p, round);
+      hipLaunchKernelGGL(merge_reset, dim3((p.UT + 255) / 256), dim3(256), 0, st, p, round);
+    }
+  }
   const size_t merge_lds = n <= kKeysInLds ? ((size_t)((n + 3) & ~3) + (n + 31) / 32) * sizeof(uint32_t) : 0;
   SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_merge),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds));
   { ProfScope ps("shallow_merge", st);
   hipLaunchKernelGGL(shallow_merge, dim3(p.UT), dim3(kMergeThreads), merge_lds, st, p); }
+  { ProfScope ps("shallow_emit", st);
+  int ex = (n + 1023) / 1024;
+  hipLaunchKernelGGL(shallow_emit, dim3(ex < 64 ? ex : 64, p.UT), dim3(256), 0, st, p); }
   { ProfScope ps("shallow_overflow", st);
   hipLaunchKernelGGL(shallow_overflow, dim3(2048), dim3(256), 0, st, p); }
 
