@@ -36,8 +36,8 @@ constexpr int kChunkCols = 1024;  // tokens per chunk: one 128-byte line of each
 constexpr int kItemChunks = 4;    // chunks a block handles with the same rows in registers
 constexpr int kStageCols = 64;
 constexpr int kGramThreads = 256;
-constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad
-constexpr int kStageBytes = kStageCols * kLdsRow;
+constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad (shallow_prep)
+constexpr int kStageBytes = kStageCols * 256;   // staged tokens: unpadded rows, 16-byte pieces swizzled
 
 constexpr int kCounters = 16;     // ints per ut
 enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4, C_ROUNDS = 5 };
@@ -58,6 +58,7 @@ struct ShallowParams {
   uint32_t *fix;           // [UT][fix_cap] deferred pairs, b << 16 | a
   unsigned *fix_count;     // [UT]
   unsigned *fix_overflow;  // [1] some list was full
+  const uint32_t *zeros;   // 256 bytes of zeros (stands in for tokens past the end of the sequence)
   unsigned fix_cap;        // per ut
   uint32_t *ovf;           // [UT*n] tokens to re-point, packed ut << 16 | token
   unsigned *ovf_count;
@@ -205,7 +206,10 @@ __device__ __forceinline__ float min3_abs(float m, float a, float b, uint32_t af
 template <bool kExact>
 __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p) {
   typedef Mma<SPINDLE_F16> M;
-  __shared__ __attribute__((aligned(16))) char stage[2 * kStageBytes];
+  // two stages of 64 tokens, filled by direct global->LDS loads.  Row r keeps its 16-byte piece
+  // k at position k ^ swz(r), swz(r) = (r + 4 ((r >> 4) & 1)) & 15, so that the eight lanes of a
+  // 128-bit LDS read (eight different rows, same k) hit eight different bank groups.
+  __shared__ __attribute__((aligned(1024))) char stage[2 * kStageBytes];
   __shared__ uint32_t pairbuf[kGramThreads / 64][kPairBuf];
   // the 32 words (one 128-byte line) of each of a wave's 64 rows for the current chunk;
   // written out as whole lines, because partially written lines cost several times their
@@ -223,7 +227,13 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   const int I = s_ % nI;
   const int pj = (s_ / nI) * 8 + xcd;
   if (pj >= p.UT * nJ) continue;
-  const int ut = pj / nJ, Jg = pj % nJ;
+  // (the chunk group is rotated by ut: groups to the right hold more work, and every XCD
+  // should see all of them)
+  const int ut = pj / nJ, Jg = (pj % nJ + ut) % nJ;
+  // G is symmetric: a row panel only computes the chunks from the one holding its own
+  // tokens onwards; shallow_mirror fills the columns to the left from the transposed blocks
+  const int Jfirst = (I * kPanelRows) / kChunkCols;
+  if ((Jg + 1) * kItemChunks <= Jfirst) continue;
   const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
   const float band = kGuard * kUnitScale * kUnitScale;
   const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
@@ -245,42 +255,44 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
 #pragma unroll
   for (int v = 0; v < 16; ++v) cinit[v] = -theta_s;
 
-  for (int J = Jg * kItemChunks; J < (Jg + 1) * kItemChunks && J * kChunkCols < n; ++J) {
+  for (int J = Jg * kItemChunks > Jfirst ? Jg * kItemChunks : Jfirst; J < (Jg + 1) * kItemChunks && J * kChunkCols < n; ++J) {
   const int col_begin = J * kChunkCols;
   const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
   const int ntiles = (col_end - col_begin + 31) / 32;
-  const int tr = threadIdx.x >> 4, tc = threadIdx.x & 15;   // 16 rows x 16 chunks per pass
-  constexpr int kPasses = kStageCols / 16;
-  u4 regs[kPasses];
-  auto fetch = [&](int b0) {
+  // each wave fills 16 rows of a stage with four 1-KiB loads (4 rows x 16 pieces, lane = slot)
+  auto dma = [&](int b0, int bufsel) {
 #pragma unroll
-    for (int q = 0; q < kPasses; ++q) {
-      const int b = b0 + q * 16 + tr;
-      u4 v = {0, 0, 0, 0};
-      if (b < n) v = *reinterpret_cast<const u4 *>(Xh + (size_t)b * 256 + tc * 16);
-      regs[q] = v;
+    for (int q = 0; q < 4; ++q) {
+      const int r = (wave * 4 + q) * 4 + (lane >> 4);
+      const int k = (lane & 15) ^ ((r + 4 * ((r >> 4) & 1)) & 15);
+      const char *src = b0 + r < n ? Xh + (size_t)(b0 + r) * 256 + k * 16
+                                   : reinterpret_cast<const char *>(p.zeros) + k * 16;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void *)src,
+          (__attribute__((address_space(3))) void *)(stage + bufsel * kStageBytes + (wave * 4 + q) * 1024),
+          16, 0, 0);
     }
-  };
-  auto stash = [&](char *dst) {
-#pragma unroll
-    for (int q = 0; q < kPasses; ++q) *reinterpret_cast<u4 *>(dst + (q * 16 + tr) * kLdsRow + tc * 16) = regs[q];
   };
   // Staged token 16*g + v of a tile is fed to matrix row 8*(v/4) + 4*g + v%4, so that result
   // register v of lane group g belongs to token 16*g + v and the packed sign bits come out
   // in token order.
   const int prow = 16 * ((c >> 2) & 1) + 4 * (c >> 3) + (c & 3);
+  int soff[M::kSteps];                             // byte offset of this lane's fragment ks in tile 0 of a stage
+#pragma unroll
+  for (int ks = 0; ks < M::kSteps; ++ks)
+    soff[ks] = prow * 256 + (((2 * ks + g) ^ ((prow + 4 * ((prow >> 4) & 1)) & 15)) << 4);
   const uint32_t wsel = g ? 0x07060302u : 0x01000504u;
   // One pipeline step: the matrix cores compute the similarities of the NEXT tile (32
   // staged tokens x this wave's 64 rows, minus theta) while the vector units turn the
   // signs of the CURRENT tile into the word of this lane's row of G.  The two instruction
   // streams are independent; sched_barrier pins the issue order (two matrix instructions,
   // then a slice of vector work) so that neither unit waits for the other.
-  auto step = [&](const char *lds, int ct, int bcol0, const f16v &a0, const f16v &a1, f16v &r0,
+  auto step = [&](int bufsel, int ct, int bcol0, const f16v &a0, const f16v &a1, f16v &r0,
                   f16v &r1) -> uint32_t {
-    const char *srow = lds + (ct * 32 + prow) * kLdsRow;
+    const char *sbuf = stage + bufsel * kStageBytes + ct * 32 * 256;   // the swizzle has period 32 rows
     M::frag sf[4], sg[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) sf[ks] = M::load(srow, ks, g);
+    for (int ks = 0; ks < 4; ++ks) sf[ks] = *reinterpret_cast<const M::frag *>(sbuf + soff[ks]);
     uint32_t sg0 = 0, sg1 = 0;
     float mn = INFINITY;
     // sign bits of elements 15..12 while the LDS reads are in flight
@@ -295,7 +307,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     for (int ks = 0; ks < 4; ++ks) {
       r0 = M::mma(sf[ks], af[0][ks], ks == 0 ? cinit : r0);
       r1 = M::mma(sf[ks], af[1][ks], ks == 0 ? cinit : r1);
-      sg[ks] = M::load(srow, 4 + ks, g);
+      sg[ks] = *reinterpret_cast<const M::frag *>(sbuf + soff[4 + ks]);
 #pragma unroll
       for (int v = 11 - 3 * ks; v >= 9 - 3 * ks; --v) {
         sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
@@ -374,18 +386,17 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     return word;
   };
 
-  fetch(col_begin);
-  stash(stage);
+  dma(col_begin, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's loads have landed in LDS
   __syncthreads();
   f16v cur0, cur1, nxt0, nxt1;
   {
     // first tile of the chunk: nothing to pack yet
-    const char *srow = stage + prow * kLdsRow;
     cur0 = cinit;
     cur1 = cinit;
 #pragma unroll
     for (int ks = 0; ks < M::kSteps; ++ks) {
-      const M::frag f = M::load(srow, ks, g);
+      const M::frag f = *reinterpret_cast<const M::frag *>(stage + soff[ks]);
       cur0 = M::mma(f, af[0][ks], cur0);
       cur1 = M::mma(f, af[1][ks], cur1);
     }
@@ -393,19 +404,19 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   u4 words = {0, 0, 0, 0};
   // four tiles (two stages) per trip: their words are one aligned 16-byte piece of the row.
   // The trip is branch-free: tiles past the end of the chunk only occur at the end of the
-  // sequence, read zero vectors and give zero words.
+  // sequence, read zero vectors and give zero words.  Tile t0 + j lies in stage buffer (j >> 1) & 1.
   for (int t0 = 0; t0 < ntiles; t0 += 4) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int t = t0 + j;                          // tile, stage t/2, half t&1
-      const int bcol0 = col_begin + t * 32;
+      const int bcol0 = col_begin + (t0 + j) * 32;
+      const int buf = (j >> 1) & 1;
       if ((j & 1) == 0) {
-        fetch(bcol0 + kStageCols);                   // next stage, in flight during two tiles
-        words[j] = step(stage + ((t >> 1) & 1) * kStageBytes, 1, bcol0, cur0, cur1, nxt0, nxt1);
+        dma(bcol0 + kStageCols, buf ^ 1);            // next stage, in flight during two tiles
+        words[j] = step(buf, 1, bcol0, cur0, cur1, nxt0, nxt1);
       } else {
-        stash(stage + (((t >> 1) + 1) & 1) * kStageBytes);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        words[j] = step(stage + (((t >> 1) + 1) & 1) * kStageBytes, 0, bcol0, cur0, cur1, nxt0, nxt1);
+        words[j] = step(buf ^ 1, 0, bcol0, cur0, cur1, nxt0, nxt1);
       }
       cur0 = nxt0;
       cur1 = nxt1;
@@ -425,6 +436,101 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   __syncthreads();                                 // the stage buffers are reused by the next chunk
   }
   if (nbuf) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
+  }
+}
+
+// ---------------------------------------------------------------- mirror
+// G_ab = G_ba for the part shallow_gram leaves out: rows of the 1024-token tile TI, columns
+// of every tile TJ < TI.  One block moves half such a tile: the 64-byte pieces that hold 512
+// tokens a of the 1024 rows b of tile TJ go to LDS as two 512 x 512-bit squares, each is
+// transposed in place (32 x 32-bit blocks in registers, swapped pairwise), and row a of the
+// two squares side by side is one whole 128-byte line of G.  The two halves of a tile run on
+// the same XCD one after the other, so the second finds its half of the lines in that L2.
+constexpr int kMirrorThreads = 512;
+constexpr int kMirrorPitch = 17;                   // words per staged row: column reads hit 32 different banks
+constexpr size_t kMirrorLds = (size_t)1024 * kMirrorPitch * sizeof(uint32_t);
+
+// the 136 pairs wa <= wb < 16, as wa | wb << 8
+struct MirrorPairs {
+  uint16_t v[136];
+  constexpr MirrorPairs() : v() {
+    int t = 0;
+    for (int wb = 0; wb < 16; ++wb)
+      for (int wa = 0; wa <= wb; ++wa) v[t++] = (uint16_t)(wa | wb << 8);
+  }
+};
+__constant__ const MirrorPairs kMirrorPairs = MirrorPairs();
+
+__global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t mtile[];   // [1024][kMirrorPitch]
+  const int n = p.n, Wp = p.Wp;
+  const int T = (n + 1023) >> 10, npairs = T * (T - 1) / 2;
+  // blocks b and b + 8 are the two halves of one tile
+  const int q = (blockIdx.x >> 4) * 8 + (blockIdx.x & 7), ha = (blockIdx.x >> 3) & 1;
+  if (q >= p.UT * npairs) return;
+  const int ut = q / npairs, pair = q % npairs;
+  int TI = (int)((1.f + sqrtf(1.f + 8.f * (float)pair)) * 0.5f);
+  while (TI * (TI - 1) / 2 > pair) --TI;
+  while ((TI + 1) * TI / 2 <= pair) ++TI;
+  const int TJ = pair - TI * (TI - 1) / 2;          // 0 <= TJ < TI < T
+  uint32_t *Gu = p.G + (size_t)ut * n * Wp;
+  const int w0 = 32 * TI + 16 * ha;                 // first source word
+  // rows of tile TJ all exist (TJ < T - 1); words past the row pitch read as zero
+  {
+    u4 v[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int k = it * kMirrorThreads + threadIdx.x, r = k >> 2, c4 = k & 3;
+      v[it] = u4{0, 0, 0, 0};
+      if (w0 + 4 * c4 < Wp) v[it] = *reinterpret_cast<const u4 *>(Gu + (size_t)(1024 * TJ + r) * Wp + w0 + 4 * c4);
+    }
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int k = it * kMirrorThreads + threadIdx.x, r = k >> 2, c4 = k & 3;
+      uint32_t *d = mtile + r * kMirrorPitch + 4 * c4;
+      d[0] = v[it][0]; d[1] = v[it][1]; d[2] = v[it][2]; d[3] = v[it][3];
+    }
+  }
+  __syncthreads();
+  // square s = rows 512 s ..; its block (R, C) = rows 32 R .., word C.  The transpose of the
+  // block belongs at (C, R): a wave takes the two blocks of an unordered pair, one per
+  // 32-lane half, and writes each where the other was.  272 pairs (136 per square), 34 per
+  // wave, handled two at a time so that the lane exchanges of one hide those of the other.
+  const int lane = lane_id(), wave = threadIdx.x >> 6, h = lane >> 5, i = lane & 31;
+  for (int it = 0; it < 34; it += 2) {
+    uint32_t *src[2], *dst[2];
+    bool wr[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int idx = (it + u) * (kMirrorThreads / 64) + wave;       // < 272
+      const int sq = idx >= 136, t = idx - 136 * sq;
+      const uint32_t e = kMirrorPairs.v[t];                            // wa | wb << 8, wa <= wb < 16
+      const int wa = e & 0xFF, wb = e >> 8;
+      const int R = h ? wb : wa, C = h ? wa : wb;
+      uint32_t *sqp = mtile + sq * 512 * kMirrorPitch;
+      src[u] = sqp + (32 * R + i) * kMirrorPitch + C;
+      dst[u] = sqp + (32 * C + i) * kMirrorPitch + R;
+      wr[u] = h == 0 || wa != wb;
+    }
+    uint32_t x0 = *src[0], x1 = *src[1];
+#pragma unroll
+    for (int k = 16; k >= 1; k >>= 1) {
+      const uint32_t m = k == 16 ? 0x0000FFFFu : k == 8 ? 0x00FF00FFu : k == 4 ? 0x0F0F0F0Fu : k == 2 ? 0x33333333u : 0x55555555u;
+      const uint32_t y0 = __shfl_xor(x0, k), y1 = __shfl_xor(x1, k);
+      x0 = (i & k) ? (x0 & ~m) | ((y0 >> k) & m) : (x0 & m) | ((y0 & m) << k);
+      x1 = (i & k) ? (x1 & ~m) | ((y1 >> k) & m) : (x1 & m) | ((y1 & m) << k);
+    }
+    if (wr[0]) *dst[0] = x0;
+    if (wr[1]) *dst[1] = x1;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int k = it * kMirrorThreads + threadIdx.x, r = k >> 3, c4 = k & 7;   // row a, 16-byte piece of its line
+    const int a = 1024 * TI + 512 * ha + r;
+    const uint32_t *sp = mtile + ((c4 >> 2) * 512 + r) * kMirrorPitch + 4 * (c4 & 3);
+    const u4 v = {sp[0], sp[1], sp[2], sp[3]};
+    if (a < n) *reinterpret_cast<u4 *>(Gu + (size_t)a * Wp + 32 * TJ + 4 * c4) = v;
   }
 }
 
@@ -968,11 +1074,12 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.fix = cv.take<uint32_t>((size_t)UT * p.fix_cap);
   // everything that must start at zero sits together at the end:
   // counters [UT][kCounters], ovf_count + 3 spare, fix_count [UT]
-  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + (size_t)UT);
+  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + (size_t)UT + 68);
   int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
   p.ovf_count = reinterpret_cast<unsigned *>(tail);
   p.fix_overflow = reinterpret_cast<unsigned *>(tail ? tail + 1 : nullptr);
   p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
+  p.zeros = reinterpret_cast<const uint32_t *>(tail ? tail + ((4 + UT + 3) & ~3) : nullptr);   // 16-byte aligned
   return cv.total();
 }
 
@@ -1061,7 +1168,7 @@ extern "C" spindle_status spindle_compress_shallow(
     adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
   }
   // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = (size_t)p.UT * kCounters + 4 + (size_t)p.UT;
+  const size_t nzero = (size_t)p.UT * kCounters + 4 + (size_t)p.UT + 68;
   hipLaunchKernelGGL(fill_u32, dim3(64), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.counters), nzero, 0u);
   for (int i = 0; i < T; ++i)   // -1 marks "not finished": stays if a bounded wait expires
     hipLaunchKernelGGL(fill_u32, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.n_codes[i]), (size_t)U, 0xFFFFFFFFu);
@@ -1084,6 +1191,15 @@ extern "C" spindle_status spindle_compress_shallow(
   hipLaunchKernelGGL(shallow_gram<true>, dim3(1024), dim3(kGramThreads), 0, st, p); }
   { ProfScope ps("shallow_fixup", st);
   hipLaunchKernelGGL(shallow_fixup, dim3(1024), dim3(256), 0, st, p); }
+  {
+    const int T1k = (n + 1023) / 1024, npairs = T1k * (T1k - 1) / 2;
+    if (npairs > 0) {
+      SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_mirror),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMirrorLds));
+      ProfScope ps("shallow_mirror", st);
+      hipLaunchKernelGGL(shallow_mirror, dim3(16 * ((p.UT * npairs + 7) / 8)), dim3(kMirrorThreads), kMirrorLds, st, p);
+    }
+  }
   SPINDLE_HIP(hipGetLastError());
 
   { ProfScope ps("shallow_lists", st);
