@@ -461,6 +461,29 @@ struct MirrorPairs {
 };
 __constant__ const MirrorPairs kMirrorPairs = MirrorPairs();
 
+// One stage of the 32 x 32 bit transpose held one row per lane (lane i of a 32-lane half =
+// row i): exchange with lane i ^ k, k = 16 >> st.  Lanes with bit k clear keep their bits
+// at positions with bit k clear and take the partner's bits of those positions, moved up by
+// k; the others the mirror image.  rot = right-rotation that moves the partner's bits into
+// place (32 - k or k), keep = mask of the bits the lane keeps.
+__device__ __forceinline__ uint32_t transpose_stage(uint32_t x, int st, uint32_t rot, uint32_t keep) {
+  uint32_t y;
+  if (st == 0) {
+    y = (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x401F);                        // lane ^ 16
+  } else if (st == 1) {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x128, 0xF, 0xF, false);  // row_ror:8 = lane ^ 8
+  } else if (st == 2) {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x104, 0xF, 0x5, false);  // row_shl:4 -> lanes with bit 2 clear
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)y, (int)x, 0x114, 0xF, 0xA, false);  // row_shr:4 -> lanes with bit 2 set
+  } else if (st == 3) {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+  } else {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+  }
+  const uint32_t moved = __builtin_amdgcn_alignbit(y, y, rot);
+  return (x & keep) | (moved & ~keep);
+}
+
 __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p) {
   extern __shared__ __attribute__((aligned(16))) uint32_t mtile[];   // [1024][kMirrorPitch]
   const int n = p.n, Wp = p.Wp;
@@ -497,6 +520,14 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
   // 32-lane half, and writes each where the other was.  272 pairs (136 per square), 34 per
   // wave, handled two at a time so that the lane exchanges of one hide those of the other.
   const int lane = lane_id(), wave = threadIdx.x >> 6, h = lane >> 5, i = lane & 31;
+  uint32_t rot[5], keep[5];
+#pragma unroll
+  for (int st = 0; st < 5; ++st) {
+    const int k = 16 >> st;
+    const uint32_t m = k == 16 ? 0x0000FFFFu : k == 8 ? 0x00FF00FFu : k == 4 ? 0x0F0F0F0Fu : k == 2 ? 0x33333333u : 0x55555555u;
+    rot[st] = (i & k) ? k : 32 - k;
+    keep[st] = (i & k) ? ~m : m;
+  }
   for (int it = 0; it < 34; it += 2) {
     uint32_t *src[2], *dst[2];
     bool wr[2];
@@ -514,11 +545,9 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
     }
     uint32_t x0 = *src[0], x1 = *src[1];
 #pragma unroll
-    for (int k = 16; k >= 1; k >>= 1) {
-      const uint32_t m = k == 16 ? 0x0000FFFFu : k == 8 ? 0x00FF00FFu : k == 4 ? 0x0F0F0F0Fu : k == 2 ? 0x33333333u : 0x55555555u;
-      const uint32_t y0 = __shfl_xor(x0, k), y1 = __shfl_xor(x1, k);
-      x0 = (i & k) ? (x0 & ~m) | ((y0 >> k) & m) : (x0 & m) | ((y0 & m) << k);
-      x1 = (i & k) ? (x1 & ~m) | ((y1 >> k) & m) : (x1 & m) | ((y1 & m) << k);
+    for (int st = 0; st < 5; ++st) {
+      x0 = transpose_stage(x0, st, rot[st], keep[st]);
+      x1 = transpose_stage(x1, st, rot[st], keep[st]);
     }
     if (wr[0]) *dst[0] = x0;
     if (wr[1]) *dst[1] = x1;
