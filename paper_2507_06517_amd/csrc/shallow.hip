@@ -584,7 +584,7 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
 // One wave per row of G: degree (Eq. 10) and, for rows of at most kListCap neighbours, the
 // neighbour indices as a compact uint16 list, so that the merge rounds touch a few hundred
 // bytes per token instead of the whole bitmap row.  Denser rows keep using the bitmap.
-constexpr int kListCap = 128;
+constexpr int kListCap = 256;
 
 __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
   const int ut = blockIdx.y, n = p.n, Wp = p.Wp;
@@ -658,11 +658,11 @@ constexpr int kGridRounds = 2;
 constexpr int kPhaseThreads = 256;
 constexpr int kKeysInLds = 36 * 1024;   // tokens whose keys fit in LDS next to the other buffers
 
-// The part of a row's neighbourhood one lane of a segment looks at: up to 16 list entries,
-// or (dense rows) every eighth 16-byte piece of the bitmap row.
+// The part of a row's neighbourhood one lane of a segment looks at: up to 16 entries of
+// each half of the list, or (dense rows) every eighth 16-byte piece of the bitmap row.
 struct Nbrs {
-  u4 q0, q1;
-  int cnt;        // list entries of this lane; -1: dense row, walk the bitmap
+  u4 q[4];        // entries sl*16 .. +15 and 128 + sl*16 .. +15 of the list
+  int cnt0, cnt1; // entries of this lane in each half; cnt0 = -1: dense row, walk the bitmap
   const u4 *row;
 };
 
@@ -670,24 +670,31 @@ __device__ __forceinline__ Nbrs load_nbrs(const ShallowParams &p, size_t base, i
   Nbrs r;
   const int d0 = p.deg0[base + v];
   const u4 *src = reinterpret_cast<const u4 *>(p.nbr + (base + v) * kListCap + sl * 16);
-  r.q0 = src[0];      // unconditional: the 256-byte slot exists for every row, and the loads
-  r.q1 = src[1];      // then do not wait for the degree
+  r.q[0] = src[0];    // unconditional: the slot exists for every row, and the loads
+  r.q[1] = src[1];    // then do not wait for the degree
   r.row = reinterpret_cast<const u4 *>(p.G + (base + v) * p.Wp);
-  const int c = d0 - sl * 16;
-  r.cnt = d0 <= kListCap ? (c < 0 ? 0 : (c > 16 ? 16 : c)) : -1;
+  const int c0 = d0 - sl * 16, c1 = d0 - 128 - sl * 16;
+  r.cnt0 = d0 <= kListCap ? (c0 < 0 ? 0 : (c0 > 16 ? 16 : c0)) : -1;
+  r.cnt1 = d0 <= kListCap ? (c1 < 0 ? 0 : (c1 > 16 ? 16 : c1)) : 0;
+  if (r.cnt1 > 0) {
+    r.q[2] = src[16];
+    r.q[3] = src[17];
+  }
   return r;
 }
 
 // Calls f(b) for every neighbour b in this lane's part of the row.
 template <typename F>
 __device__ __forceinline__ void for_nbrs(const ShallowParams &p, const Nbrs &r, int sl, F f) {
-  if (r.cnt >= 0) {
+  if (r.cnt0 >= 0) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (j < r.cnt) f((int)((r.q0[j >> 1] >> (16 * (j & 1))) & 0xFFFFu));
+    for (int j = 0; j < 16; ++j)
+      if (j < r.cnt0) f((int)((r.q[j >> 3][(j >> 1) & 3] >> (16 * (j & 1))) & 0xFFFFu));
+    if (r.cnt1 > 0) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (8 + j < r.cnt) f((int)((r.q1[j >> 1] >> (16 * (j & 1))) & 0xFFFFu));
+      for (int j = 0; j < 16; ++j)
+        if (j < r.cnt1) f((int)((r.q[2 + (j >> 3)][(j >> 1) & 3] >> (16 * (j & 1))) & 0xFFFFu));
+    }
   } else {
     for (int w4 = sl; w4 < p.Wp / 4; w4 += kSegW) {
       const u4 q = r.row[w4];
@@ -728,6 +735,7 @@ __device__ __forceinline__ void phase_onehop(const ShallowParams &p, size_t base
   constexpr int kPer = kWave / kSegW;
   uint32_t *m1 = p.m1 + base;
   int *cand = p.cand + base;
+  const int lane = lane_id();
   for (int i0 = w.seg - w.seg % kPer; i0 < nalive; i0 += 4 * w.nsegs) {
     int vv[4];
     bool on[4];
@@ -747,13 +755,18 @@ __device__ __forceinline__ void phase_onehop(const ShallowParams &p, size_t base
       if (on[k]) for_nbrs(p, r[k], w.sl, [&](int b) { const uint32_t kk = w.key[b]; mk = kk > mk ? kk : mk; });
       m[k] = seg_max(mk);
     }
-    if (w.sl == 0) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (on[k]) {
-          m1[vv[k]] = m[k];
-          if (m[k] == w.key[vv[k]]) cand[atomicAdd(w.n_cand, 1)] = vv[k];
-        }
+    for (int k = 0; k < 4; ++k) {
+      const bool lead = w.sl == 0 && on[k];
+      if (lead) m1[vv[k]] = m[k];
+      const bool is_cand = lead && m[k] == w.key[vv[k]];
+      const unsigned long long mk = __ballot(is_cand);     // one counter update per wave
+      if (mk) {
+        int at = 0;
+        if (lane == __builtin_ctzll(mk)) at = atomicAdd(w.n_cand, __popcll(mk));
+        at = __shfl(at, __builtin_ctzll(mk));
+        if (is_cand) cand[at + __popcll(mk & ((1ull << lane) - 1ull))] = vv[k];
+      }
     }
   }
 }
@@ -772,24 +785,43 @@ __device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base
     const uint32_t ku = on ? w.key[uvert] : 0xFFFFFFFFu;
     const Nbrs r = load_nbrs(p, base, uvert, w.sl);
     uint32_t m = 0;
+    int rem = 0;                                    // remaining neighbours in this lane's part
     // remaining = key != 0 (keys only change in the later phases of the round)
     if (on) for_nbrs(p, r, w.sl, [&](int b) {
-      if (w.key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; }
+      if (w.key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; ++rem; }
     });
     m = seg_max(m);
     const bool picked = on && m == ku;
+    // one update of each counter per wave: picks by the segment leaders, dying tokens by all lanes
+    const unsigned long long pk = __ballot(picked && w.sl == 0);
+    if (pk == 0) continue;                           // wave-uniform
     int s = 0;
-    if (picked && w.sl == 0) {
-      s = atomicAdd(w.n_picks, 1);
-      pick_key[s] = ku;
-      pick_vert[s] = uvert;
+    {
+      int at = 0;
+      if (lane == __builtin_ctzll(pk)) at = atomicAdd(w.n_picks, __popcll(pk));
+      at = __shfl(at, __builtin_ctzll(pk));
+      if (picked && w.sl == 0) {
+        s = at + __popcll(pk & ((1ull << lane) - 1ull));
+        pick_key[s] = ku;
+        pick_vert[s] = uvert;
+      }
     }
     s = __shfl(s, lane & ~(kSegW - 1));
+    const int mine = picked ? rem : 0;
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int x = __shfl_up(incl, o);
+      if (lane >= o) incl += x;
+    }
+    int at = 0;
+    if (lane == kWave - 1) at = atomicAdd(w.n_dying, incl);
+    at = __shfl(at, kWave - 1) + incl - mine;
     if (picked) for_nbrs(p, r, w.sl, [&](int b) {
       if (w.key[b] != 0) {
         slot[b] = s;
         atomicOr(&w.dead[b >> 5], 1u << (b & 31));
-        dying[atomicAdd(w.n_dying, 1)] = b;
+        dying[at++] = b;
       }
     });
   }
@@ -826,53 +858,104 @@ __device__ __forceinline__ MergeView global_view(const ShallowParams &p, int ut)
   w.n_cand = cnt + C_CAND;
   w.n_dying = cnt + C_DYING;
   w.n_picks = cnt + C_PICKS;
-  w.seg = (blockIdx.x * kPhaseThreads + threadIdx.x) / kSegW;
-  w.nsegs = gridDim.x * kPhaseThreads / kSegW;
+  w.seg = (blockIdx.x * blockDim.x + threadIdx.x) / kSegW;
+  w.nsegs = gridDim.x * blockDim.x / kSegW;
   w.sl = threadIdx.x & (kSegW - 1);
   return w;
 }
 
 // Grid-wide phases of round `round` (blockIdx.y = problem).  The list of remaining tokens
 // alternates between the `alive` and `alive2` rows, its length between counters 0 and 1.
-__global__ __launch_bounds__(kPhaseThreads) void merge_onehop(ShallowParams p, int round) {
+// With dynamic LDS for n keys the block first copies the keys of its problem there: the
+// phase is bound by the random key look-ups, which LDS serves several times faster than L2.
+__global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, int round, int keys_in_lds) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   const int ut = blockIdx.y;
   const size_t base = (size_t)ut * p.n;
-  const MergeView w = global_view(p, ut);
+  MergeView w = global_view(p, ut);
   const int *cnt = p.counters + (size_t)ut * kCounters;
-  phase_onehop(p, base, w, (round & 1 ? p.alive2 : p.alive) + base, cnt[round & 1]);
+  const int nalive = cnt[round & 1];
+  if ((int)(blockIdx.x * blockDim.x / kSegW) >= nalive) return;      // block-uniform: no work for this block
+  if (keys_in_lds) {
+    for (int i = threadIdx.x; i < p.n; i += blockDim.x) lds[i] = p.key[base + i];
+    __syncthreads();
+    w.key = lds;
+  }
+  phase_onehop(p, base, w, (round & 1 ? p.alive2 : p.alive) + base, nalive);
 }
 __global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p) {
   const int ut = blockIdx.y;
   const MergeView w = global_view(p, ut);
   phase_twohop(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_CAND]);
 }
-__global__ __launch_bounds__(kPhaseThreads) void merge_degree(ShallowParams p) {
-  const int ut = blockIdx.y;
-  const MergeView w = global_view(p, ut);
-  phase_degree(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_DYING]);
-}
-// keys of the dying tokens -> 0; remaining tokens -> the other list; counters for the next round
-__global__ __launch_bounds__(kPhaseThreads) void merge_compact(ShallowParams p, int round) {
-  const int ut = blockIdx.y, lane = lane_id();
-  const size_t base = (size_t)ut * p.n;
+// End of a grid round.  Tokens marked dead get key 0; every other token of the list counts
+// its neighbours that are not dead (its new degree, Eq. 13: with most tokens leaving in the
+// first rounds, recounting the few that stay is cheaper than subtracting at every
+// neighbour of every leaving token), gets its new key and moves to the other list.
+__global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, int round) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];     // dead bitmap of the problem
+  constexpr int kPer = kWave / kSegW;
+  const int ut = blockIdx.y, lane = lane_id(), n = p.n;
+  const size_t base = (size_t)ut * n;
   int *cnt = p.counters + (size_t)ut * kCounters;
   const int nalive = cnt[round & 1];
+  const int seg = (blockIdx.x * blockDim.x + threadIdx.x) / kSegW, nsegs = gridDim.x * blockDim.x / kSegW;
+  const int sl = threadIdx.x & (kSegW - 1);
+  if ((int)(blockIdx.x * blockDim.x / kSegW) >= nalive) return;
+  for (int i = threadIdx.x; i < (n + 31) / 32; i += blockDim.x) lds[i] = p.gone[base + i];
+  __syncthreads();
+  const uint32_t *dead = lds;
   const int *src = (round & 1 ? p.alive2 : p.alive) + base;
   int *dst = (round & 1 ? p.alive : p.alive2) + base;
-  const uint32_t *dead = p.gone + base;
   uint32_t *key = p.key + base;
-  const int stride = gridDim.x * kPhaseThreads;
-  for (int i0 = blockIdx.x * kPhaseThreads + threadIdx.x - lane; i0 < nalive; i0 += stride) {
-    const int i = i0 + lane;
-    const int v = i < nalive ? src[i] : -1;
-    const bool gone = v >= 0 && ((dead[v >> 5] >> (v & 31)) & 1u);
-    if (gone) key[v] = 0;
-    const bool live = v >= 0 && !gone;
-    const unsigned long long mk = __ballot(live);
-    int at = 0;
-    if (lane == 0 && mk) at = atomicAdd(&cnt[(round & 1) ^ 1], __popcll(mk));
-    at = __shfl(at, 0);
-    if (live) dst[at + __popcll(mk & ((1ull << lane) - 1ull))] = v;
+  __shared__ int wave_total[kPhaseThreads / kWave], block_at;
+  const int wave = threadIdx.x / kWave;
+  // block-uniform trip count (the appends below synchronise the block): waves past the end
+  // of the list run with all lanes idle
+  for (int b0 = blockIdx.x * blockDim.x / kSegW; b0 < nalive; b0 += 4 * nsegs) {
+    const int i0 = b0 + wave * kPer;
+    int vv[4];
+    bool live[4];
+    Nbrs r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + seg % kPer + k * nsegs;
+      vv[k] = i < nalive ? src[i] : -1;
+      live[k] = vv[k] >= 0 && !((dead[vv[k] >> 5] >> (vv[k] & 31)) & 1u);
+      if (vv[k] >= 0 && !live[k] && sl == 0) key[vv[k]] = 0;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r[k] = load_nbrs(p, base, live[k] ? vv[k] : 0, sl);
+    unsigned long long mk[4];
+    int mine = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      int c = 0;
+      if (live[k]) for_nbrs(p, r[k], sl, [&](int b) { c += !((dead[b >> 5] >> (b & 31)) & 1u); });
+#pragma unroll
+      for (int o = kSegW / 2; o > 0; o >>= 1) c += __shfl_xor(c, o);
+      const bool lead = live[k] && sl == 0;
+      if (lead) key[vv[k]] = ((uint32_t)c << 16) | (uint32_t)(0xFFFF - vv[k]);
+      mk[k] = __ballot(lead);
+      mine += __popcll(mk[k]);
+    }
+    // one counter update per block and trip: same-address atomics are served one at a time
+    if (lane == 0) wave_total[wave] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int q = 0; q < kPhaseThreads / kWave; ++q) t += wave_total[q];
+      block_at = t ? atomicAdd(&cnt[(round & 1) ^ 1], t) : 0;
+    }
+    __syncthreads();
+    int at = block_at;
+    for (int q = 0; q < wave; ++q) at += wave_total[q];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (live[k] && sl == 0) dst[at + __popcll(mk[k] & ((1ull << lane) - 1ull))] = vv[k];
+      at += __popcll(mk[k]);
+    }
+    __syncthreads();                                 // wave_total is rewritten by the next trip
   }
 }
 // between rounds: the counters of the finished round start again at zero
@@ -909,7 +992,6 @@ __device__ __forceinline__ void emit_code(const ShallowParams &p, int ut, int ve
 __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   __shared__ int sh_n[4];                     // alive, candidates, dying, picks
-  __shared__ uint32_t sh_keys[1024];
   const int ut = blockIdx.x, n = p.n, tid = threadIdx.x;
   const int lane = lane_id(), wave = tid >> 6;
   const size_t base = (size_t)ut * n;
@@ -922,8 +1004,6 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
   w.n_alive = &sh_n[0]; w.n_cand = &sh_n[1]; w.n_dying = &sh_n[2]; w.n_picks = &sh_n[3];
   w.seg = tid / kSegW; w.nsegs = kMergeThreads / kSegW; w.sl = tid & (kSegW - 1);
   int *slot = p.slot + base, *dying = p.dying + base;
-  int *pick_vert = p.pick_vert + base, *rank = p.rank + base, *rank_vert = p.rank_vert + base;
-  uint32_t *pick_key = p.pick_key + base;
   // the list the last grid round left behind; this kernel compacts it in place
   int *alive = (kGridRounds & 1 ? p.alive2 : p.alive) + base;
   long long tick_ = 0;
@@ -976,24 +1056,8 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
   if (tid == 0) cnt[C_ROUNDS] = round;
   if (sh_n[0] != 0) return;                      // did not converge: n_codes stays -1
 
-  // codebook order: rank of each pick among all picks by decreasing key
   const int P = sh_n[3];
   if (tid == 0) cnt[C_PICKS] = P;
-  for (int s0 = 0; s0 < P; s0 += kMergeThreads) {
-    const int s = s0 + tid;
-    const uint32_t ks = s < P ? pick_key[s] : 0xFFFFFFFFu;
-    int r = 0;
-    for (int b0 = 0; b0 < P; b0 += 1024) {
-      __syncthreads();
-      sh_keys[tid] = b0 + tid < P ? pick_key[b0 + tid] : 0u;
-      __syncthreads();
-      const int lim = P - b0 < 1024 ? P - b0 : 1024;
-#pragma unroll 8
-      for (int j = 0; j < lim; ++j) r += sh_keys[j] > ks;
-    }
-    if (s < P) { rank[s] = r; rank_vert[r] = pick_vert[s]; }
-  }
-  __syncthreads();
   MERGE_TICK(8)
 
   const int t = ut / p.U, u = ut % p.U;
@@ -1002,6 +1066,34 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
     if (p.n_found[t]) p.n_found[t][u] = P;
   }
   MERGE_TICK(9)
+}
+
+// Codebook order: the rank of each pick among all picks of its problem by decreasing key at
+// pick time (keys are distinct: they carry the token index).
+__global__ __launch_bounds__(256) void shallow_rank(ShallowParams p) {
+  __shared__ uint32_t tile[1024];
+  const int ut = blockIdx.y;
+  const size_t base = (size_t)ut * p.n;
+  if (p.n_codes[ut / p.U][ut % p.U] < 0) return;   // construction did not finish
+  const int P = p.counters[(size_t)ut * kCounters + C_PICKS];
+  const uint32_t *pick_key = p.pick_key + base;
+  for (int s0 = blockIdx.x * 256; s0 < P; s0 += gridDim.x * 256) {
+    const int s = s0 + threadIdx.x;
+    const uint32_t ks = s < P ? pick_key[s] : 0xFFFFFFFFu;
+    int r = 0;
+    for (int b0 = 0; b0 < P; b0 += 1024) {
+      __syncthreads();
+      for (int j = threadIdx.x; j < 1024; j += 256) tile[j] = b0 + j < P ? pick_key[b0 + j] : 0u;
+      __syncthreads();
+      const int lim = P - b0 < 1024 ? P - b0 : 1024;
+#pragma unroll 8
+      for (int j = 0; j < lim; ++j) r += tile[j] > ks;
+    }
+    if (s < P) {
+      p.rank[base + s] = r;
+      p.rank_vert[base + r] = p.pick_vert[base + s];
+    }
+  }
 }
 
 // References (Eq. 12, renumbered in codebook order) and codebook entries (Eq. 11), grid-wide.
@@ -1088,7 +1180,7 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.alive = cv.take<int>(N);
   p.alive2 = cv.take<int>(N);
   p.gone = cv.take<uint32_t>(N);
-  p.nbr = cv.take<uint16_t>(N * 128);
+  p.nbr = cv.take<uint16_t>(N * kListCap);
   p.slot = cv.take<int>(N);
   p.cand = cv.take<int>(N);
   p.dying = cv.take<int>(N);
@@ -1237,12 +1329,19 @@ extern "C" spindle_status spindle_compress_shallow(
     int gx = (n + 4 * (kPhaseThreads / kSegW) - 1) / (4 * (kPhaseThreads / kSegW));
     if (gx > 256) gx = 256;
     const dim3 pg(gx, p.UT);
+    // one-hop phase: 1024-thread blocks with the keys of the problem in LDS when they fit
+    const int keys_in_lds = n <= kKeysInLds;
+    const size_t key_lds = keys_in_lds ? (size_t)((n + 3) & ~3) * sizeof(uint32_t) : 0;
+    int ox = (n + 4 * (kMergeThreads / kSegW) - 1) / (4 * (kMergeThreads / kSegW));
+    if (ox > 16) ox = 16;
+    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_onehop),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)key_lds));
+    const size_t dead_lds = (size_t)((n + 31) / 32) * sizeof(uint32_t);
     for (int round = 0; round < kGridRounds; ++round) {
       ProfScope ps("shallow_merge_grid", st);
-      hipLaunchKernelGGL(merge_onehop, pg, dim3(kPhaseThreads), 0, st, p, round);
+      hipLaunchKernelGGL(merge_onehop, dim3(ox, p.UT), dim3(kMergeThreads), key_lds, st, p, round, keys_in_lds);
       hipLaunchKernelGGL(merge_twohop, pg, dim3(kPhaseThreads), 0, st, p);
-      hipLaunchKernelGGL(merge_degree, pg, dim3(kPhaseThreads), 0, st, p);
-      hipLaunchKernelGGL(merge_compact, pg, dim3(kPhaseThreads), 0, st, p, round);
+      hipLaunchKernelGGL(merge_update, pg, dim3(kPhaseThreads), dead_lds, st, p, round);
       hipLaunchKernelGGL(merge_reset, dim3((p.UT + 255) / 256), dim3(256), 0, st, p, round);
     }
   }
@@ -1251,6 +1350,9 @@ extern "C" spindle_status spindle_compress_shallow(
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds));
   { ProfScope ps("shallow_merge", st);
   hipLaunchKernelGGL(shallow_merge, dim3(p.UT), dim3(kMergeThreads), merge_lds, st, p); }
+  { ProfScope ps("shallow_rank", st);
+  int rx = (n + 255) / 256;
+  hipLaunchKernelGGL(shallow_rank, dim3(rx < 32 ? rx : 32, p.UT), dim3(256), 0, st, p); }
   { ProfScope ps("shallow_emit", st);
   int ex = (n + 1023) / 1024;
   hipLaunchKernelGGL(shallow_emit, dim3(ex < 64 ? ex : 64, p.UT), dim3(256), 0, st, p); }
