@@ -200,6 +200,18 @@ __device__ __forceinline__ float min3_abs(float m, float a, float b, uint32_t af
   return r;
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at
+// lds_addr + 16 i (lds_addr wave-uniform).  Issued as assembly on purpose: the compiler
+// would put a wait for the load in front of every later LDS read of the kernel, since it
+// cannot tell which of them touch the destination.  Completion is the caller's business
+// (s_waitcnt vmcnt + barrier before any lane reads the destination).
+__device__ __forceinline__ void lds_dma16(const void *src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(src)
+               : "memory", "m0");
+}
+
 // kExact = false: the fast pass described above, one block per (row panel, column chunk).
 // kExact = true: fallback pass over the same tiles, run by a fixed grid that exits at once
 // unless a pair list overflowed; it stores no words and decides the close pairs in place.
@@ -207,8 +219,8 @@ template <bool kExact>
 __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p) {
   typedef Mma<SPINDLE_F16> M;
   // two stages of 64 tokens, filled by direct global->LDS loads.  Row r keeps its 16-byte piece
-  // k at position k ^ swz(r), swz(r) = (r + 4 ((r >> 4) & 1)) & 15, so that the eight lanes of a
-  // 128-bit LDS read (eight different rows, same k) hit eight different bank groups.
+  // k at position k ^ swz(r), swz(r) = (r & 7) | ((r & 16) >> 1), so that sixteen consecutive lanes
+  // of a 128-bit LDS read (sixteen different rows, same k) hit sixteen different bank groups.
   __shared__ __attribute__((aligned(1024))) char stage[2 * kStageBytes];
   __shared__ uint32_t pairbuf[kGramThreads / 64][kPairBuf];
   // the 32 words (one 128-byte line) of each of a wave's 64 rows for the current chunk;
@@ -254,25 +266,6 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   f16v cinit;
 #pragma unroll
   for (int v = 0; v < 16; ++v) cinit[v] = -theta_s;
-
-  for (int J = Jg * kItemChunks > Jfirst ? Jg * kItemChunks : Jfirst; J < (Jg + 1) * kItemChunks && J * kChunkCols < n; ++J) {
-  const int col_begin = J * kChunkCols;
-  const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
-  const int ntiles = (col_end - col_begin + 31) / 32;
-  // each wave fills 16 rows of a stage with four 1-KiB loads (4 rows x 16 pieces, lane = slot)
-  auto dma = [&](int b0, int bufsel) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = (wave * 4 + q) * 4 + (lane >> 4);
-      const int k = (lane & 15) ^ ((r + 4 * ((r >> 4) & 1)) & 15);
-      const char *src = b0 + r < n ? Xh + (size_t)(b0 + r) * 256 + k * 16
-                                   : reinterpret_cast<const char *>(p.zeros) + k * 16;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void *)src,
-          (__attribute__((address_space(3))) void *)(stage + bufsel * kStageBytes + (wave * 4 + q) * 1024),
-          16, 0, 0);
-    }
-  };
   // Staged token 16*g + v of a tile is fed to matrix row 8*(v/4) + 4*g + v%4, so that result
   // register v of lane group g belongs to token 16*g + v and the packed sign bits come out
   // in token order.
@@ -280,22 +273,52 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   int soff[M::kSteps];                             // byte offset of this lane's fragment ks in tile 0 of a stage
 #pragma unroll
   for (int ks = 0; ks < M::kSteps; ++ks)
-    soff[ks] = prow * 256 + (((2 * ks + g) ^ ((prow + 4 * ((prow >> 4) & 1)) & 15)) << 4);
-  const uint32_t wsel = g ? 0x07060302u : 0x01000504u;
-  // One pipeline step: the matrix cores compute the similarities of the NEXT tile (32
-  // staged tokens x this wave's 64 rows, minus theta) while the vector units turn the
-  // signs of the CURRENT tile into the word of this lane's row of G.  The two instruction
-  // streams are independent; sched_barrier pins the issue order (two matrix instructions,
-  // then a slice of vector work) so that neither unit waits for the other.
-  auto step = [&](int bufsel, int ct, int bcol0, const f16v &a0, const f16v &a1, f16v &r0,
-                  f16v &r1) -> uint32_t {
-    const char *sbuf = stage + bufsel * kStageBytes + ct * 32 * 256;   // the swizzle has period 32 rows
-    M::frag sf[4], sg[4];
+    soff[ks] = prow * 256 + (((2 * ks + g) ^ ((prow & 7) | ((prow & 16) >> 1))) << 4);
+  uint32_t voff[4];                                // this lane's source offset within a stage, per load
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) sf[ks] = *reinterpret_cast<const M::frag *>(sbuf + soff[ks]);
+  for (int q = 0; q < 4; ++q) {
+    const int r = (wave * 4 + q) * 4 + (lane >> 4);
+    voff[q] = (uint32_t)(r * 256 + (((lane & 15) ^ ((r & 7) | ((r & 16) >> 1))) << 4));
+  }
+  const uint32_t wsel = g ? 0x07060302u : 0x05040100u;
+  M::frag pf0, pf1;                                // fragments 0, 1 of the tile the next step multiplies
+  const uint32_t stage_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)stage;
+
+  for (int J = Jg * kItemChunks > Jfirst ? Jg * kItemChunks : Jfirst; J < (Jg + 1) * kItemChunks && J * kChunkCols < n; ++J) {
+  const int col_begin = J * kChunkCols;
+  const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
+  const int ntiles = (col_end - col_begin + 31) / 32;
+  // Stage s of the chunk = tokens col_begin + 64 s .. + 63, in buffer s & 1; tile x = half x & 1
+  // of stage x >> 1.  Each wave fills 16 rows of a stage with four 1-KiB loads (4 rows x 16
+  // pieces, lane = slot).  Rows past the end of the sequence exist (the array is padded) and
+  // are never used: their bits are masked and their pairs rejected.
+  auto dma = [&](int b0, int bufsel) {
+    const char *sbase = Xh + (size_t)b0 * 256;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lds_dma16(sbase + voff[q], stage_lds + bufsel * kStageBytes + (wave * 4 + q) * 1024);
+  };
+  auto frag_at = [&](int bufsel, int ct, int ks) -> M::frag {
+    return *reinterpret_cast<const M::frag *>(stage + bufsel * kStageBytes + ct * 32 * 256 + soff[ks]);
+  };
+  // One pipeline step: the matrix cores compute the similarities of the NEXT tile x (32
+  // staged tokens x this wave's 64 rows, minus theta) while the vector units turn the
+  // signs of the CURRENT tile (results a0, a1, first token bcol0) into the word of this
+  // lane's row of G.  The two instruction streams are independent; sched_barrier pins the
+  // issue order (two matrix instructions, then a slice of vector work).  The step starts
+  // with matrix instructions on fragments fetched during the previous step (pf0, pf1), so
+  // the matrix cores do not wait for the vector work on their previous results.
+  // (bufx, ctx) = place of tile x, (bufn, ctn) = place of tile x + 1.  With sync_fetch (x is
+  // the second half of its stage) the step also holds the block barrier after its last read
+  // of the stage, which hands the buffer to the loads of the stage after next (tokens
+  // fetch_b0 ..) and makes the next stage, loaded one barrier earlier, visible.
+  auto step = [&](int bufx, int ctx, int bufn, int ctn, bool sync_fetch, int fetch_b0, int bcol0, const f16v &a0,
+                  const f16v &a1, f16v &r0, f16v &r1) -> uint32_t {
+    M::frag f2 = frag_at(bufx, ctx, 2), f3 = frag_at(bufx, ctx, 3);
+    r0 = M::mma(pf0, af[0][0], cinit);
+    r1 = M::mma(pf0, af[1][0], cinit);
+    __builtin_amdgcn_sched_barrier(0);               // matrix instructions first: the vector work below waits for the previous tile
     uint32_t sg0 = 0, sg1 = 0;
     float mn = INFINITY;
-    // sign bits of elements 15..12 while the LDS reads are in flight
 #pragma unroll
     for (int v = 15; v >= 12; --v) {
       sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
@@ -303,29 +326,59 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
     }
     __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(pf1, af[0][1], r0);
+    r1 = M::mma(pf1, af[1][1], r1);
+    M::frag f4 = frag_at(bufx, ctx, 4), f5 = frag_at(bufx, ctx, 5);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      r0 = M::mma(sf[ks], af[0][ks], ks == 0 ? cinit : r0);
-      r1 = M::mma(sf[ks], af[1][ks], ks == 0 ? cinit : r1);
-      sg[ks] = *reinterpret_cast<const M::frag *>(sbuf + soff[4 + ks]);
-#pragma unroll
-      for (int v = 11 - 3 * ks; v >= 9 - 3 * ks; --v) {
-        sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
-        sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
-        mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+    for (int v = 11; v >= 9; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
     }
-    r0 = M::mma(sg[0], af[0][4], r0);
-    r1 = M::mma(sg[0], af[1][4], r1);
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f2, af[0][2], r0);
+    r1 = M::mma(f2, af[1][2], r1);
+    M::frag f6 = frag_at(bufx, ctx, 6), f7 = frag_at(bufx, ctx, 7);
+#pragma unroll
+    for (int v = 8; v >= 6; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f3, af[0][3], r0);
+    r1 = M::mma(f3, af[1][3], r1);
+#pragma unroll
+    for (int v = 5; v >= 3; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (sync_fetch) {
+      __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): own loads landed, own reads done
+      __builtin_amdgcn_s_barrier();
+      dma(fetch_b0, bufx);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f4, af[0][4], r0);
+    r1 = M::mma(f4, af[1][4], r1);
+    pf0 = frag_at(bufn, ctn, 0);
+    pf1 = frag_at(bufn, ctn, 1);
+#pragma unroll
+    for (int v = 2; v >= 0; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
     uint32_t q0 = ~sg0 & 0xFFFFu, q1 = ~sg1 & 0xFFFFu;   // bit v: staged token 16*g + v
     // pairs too close to theta for fp16: clear their bits now, queue them for the exact
     // decision.  Bit 16*cb + v of `rest` = close.
     uint32_t rest = 0;
     const bool any_close = __any(mn < band);
     __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(sg[1], af[0][5], r0);
-    r1 = M::mma(sg[1], af[1][5], r1);
+    r0 = M::mma(f5, af[0][5], r0);
+    r1 = M::mma(f5, af[1][5], r1);
     if (any_close) {
       uint32_t cm0 = 0, cm1 = 0;
 #pragma unroll
@@ -353,15 +406,16 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       q1 &= keep;
     }
     __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(sg[2], af[0][6], r0);
-    r1 = M::mma(sg[2], af[1][6], r1);
+    r0 = M::mma(f6, af[0][6], r0);
+    r1 = M::mma(f6, af[1][6], r1);
+    // halves[0] = the value of the lane with g = 0 of this column, halves[1] = that of g = 1
     const uint32_t own = q0 | (q1 << 16);
-    const uint32_t other = __shfl_xor(own, 32);
+    const auto halves = __builtin_amdgcn_permlane32_swap(own, own, false, false);
     __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(sg[3], af[0][7], r0);
-    r1 = M::mma(sg[3], af[1][7], r1);
+    r0 = M::mma(f7, af[0][7], r0);
+    r1 = M::mma(f7, af[1][7], r1);
     // lane group 0 keeps the word of row block 0 (low halves), group 1 that of block 1
-    const uint32_t word = __builtin_amdgcn_perm(own, other, wsel);
+    const uint32_t word = __builtin_amdgcn_perm(halves[1], halves[0], wsel);
     if (any_close) {
       while (__any(rest != 0)) {
         const bool has = rest != 0;
@@ -387,6 +441,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   };
 
   dma(col_begin, 0);
+  dma(col_begin + kStageCols, 1);
   __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's loads have landed in LDS
   __syncthreads();
   f16v cur0, cur1, nxt0, nxt1;
@@ -396,28 +451,24 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     cur1 = cinit;
 #pragma unroll
     for (int ks = 0; ks < M::kSteps; ++ks) {
-      const M::frag f = *reinterpret_cast<const M::frag *>(stage + soff[ks]);
+      const M::frag f = frag_at(0, 0, ks);
       cur0 = M::mma(f, af[0][ks], cur0);
       cur1 = M::mma(f, af[1][ks], cur1);
     }
+    pf0 = frag_at(0, 1, 0);
+    pf1 = frag_at(0, 1, 1);
   }
   u4 words = {0, 0, 0, 0};
   // four tiles (two stages) per trip: their words are one aligned 16-byte piece of the row.
   // The trip is branch-free: tiles past the end of the chunk only occur at the end of the
-  // sequence, read zero vectors and give zero words.  Tile t0 + j lies in stage buffer (j >> 1) & 1.
+  // sequence and give zero words.  Step j packs tile t0 + j and multiplies tile x = t0 + j + 1.
   for (int t0 = 0; t0 < ntiles; t0 += 4) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int bcol0 = col_begin + (t0 + j) * 32;
-      const int buf = (j >> 1) & 1;
-      if ((j & 1) == 0) {
-        dma(bcol0 + kStageCols, buf ^ 1);            // next stage, in flight during two tiles
-        words[j] = step(buf, 1, bcol0, cur0, cur1, nxt0, nxt1);
-      } else {
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        words[j] = step(buf ^ 1, 0, bcol0, cur0, cur1, nxt0, nxt1);
-      }
+      const int x = j + 1;                           // tile x of the trip (mod 4: t0 is a multiple of 4)
+      words[j] = step((x >> 1) & 1, x & 1, ((x + 1) >> 1) & 1, (x + 1) & 1, (x & 1) != 0,
+                      col_begin + (t0 + x + 3) * 32, bcol0, cur0, cur1, nxt0, nxt1);
       cur0 = nxt0;
       cur1 = nxt1;
     }
@@ -433,6 +484,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
         *reinterpret_cast<u4 *>(p.G + ((size_t)ut * n + arow0 + r) * p.Wp + (col_begin >> 5) + piece * 4) = v;
     }
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // loads issued for stages past the chunk
   __syncthreads();                                 // the stage buffers are reused by the next chunk
   }
   if (nbuf) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
@@ -1173,7 +1225,7 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   Carver cv(ws);
   const size_t N = (size_t)UT * n;
   p.Wp = ((n + 127) / 128) * 4;   // whole 16-byte pieces: shallow_gram writes every word of a row
-  p.Xh = cv.take<_Float16>(N * kHeadDim);
+  p.Xh = cv.take<_Float16>((N + 512) * kHeadDim);   // shallow_gram stages up to 5 tiles past the last token
   p.m64 = cv.take<double>(N);
   p.G = cv.take<uint32_t>(N * p.Wp);
   p.deg0 = cv.take<int>(N);
