@@ -306,15 +306,19 @@ __device__ __forceinline__ void block_scan2(int a, int b, int &oa, int &ob, int 
   __syncthreads();
 }
 
-__global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p) {
+constexpr int kSelInLds = 36 * 1024;   // pooled scores of a unit that fit in LDS
+
+__global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p, int vals_in_lds) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t sel_lds[];
   __shared__ int hist[256];
   __shared__ int wsum[kSelThreads / 64][2];
-  __shared__ uint32_t sh_prefix;
+  __shared__ uint32_t sh_prefix, sh_min, sh_max;
   __shared__ int sh_krem;
-  const int u = blockIdx.x, tid = threadIdx.x;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = lane_id();
   const int lc = p.lc;
   const float *raw = p.scores + (size_t)u * lc;
-  float *pooled = p.pooled + (size_t)u * lc;
+  // pooled scores as order-preserving unsigned keys: in LDS when they fit, else in the workspace
+  uint32_t *pooled = vals_in_lds ? sel_lds : reinterpret_cast<uint32_t *>(p.pooled + (size_t)u * lc);
   int32_t *kept = p.kept + (size_t)u * p.out_stride;
   int budget = p.budgets ? p.budgets[u] : p.budget;
   if (budget < p.lw) budget = p.lw;
@@ -322,43 +326,119 @@ __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p) {
   if (k > lc) k = lc;
   if (k > p.out_stride - p.lw) k = p.out_stride - p.lw;   // never write past the row pitch
 
-  // 1-D max pooling, window clipped to the context
+  // 1-D max pooling, window clipped to the context; smallest and largest key of the unit
+  if (tid == 0) { sh_min = 0xFFFFFFFFu; sh_max = 0u; }
+  __syncthreads();
   const int r = (p.pool - 1) / 2;
-  for (int a = tid; a < lc; a += kSelThreads) {
-    float m = raw[a];
-    const int lo = a - r < 0 ? 0 : a - r, hi = a + r >= lc ? lc - 1 : a + r;
-    for (int j = lo; j <= hi; ++j) m = fmaxf(m, raw[j]);
-    pooled[a] = m;
-    if (p.scores_out) p.scores_out[(size_t)u * lc + a] = m;
+  uint32_t mn = 0xFFFFFFFFu, mx = 0u;
+  if (vals_in_lds) {
+    // raw scores to LDS with independent coalesced loads, pooled in registers, keys back in place
+    constexpr int kPer = kSelInLds / kSelThreads;
+    float *rawl = reinterpret_cast<float *>(sel_lds);
+#pragma unroll 4
+    for (int i = 0; i < kPer; ++i) {
+      const int a = tid + i * kSelThreads;
+      if (a < lc) rawl[a] = raw[a];
+    }
+    __syncthreads();
+    float pm[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int a = tid + i * kSelThreads;
+      float m = -INFINITY;
+      if (a < lc) {
+        const int lo = a - r < 0 ? 0 : a - r, hi = a + r >= lc ? lc - 1 : a + r;
+        for (int j = lo; j <= hi; ++j) m = fmaxf(m, rawl[j]);
+      }
+      pm[i] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int a = tid + i * kSelThreads;
+      if (a < lc) {
+        const uint32_t x = orderable(pm[i]);
+        pooled[a] = x;
+        mn = x < mn ? x : mn;
+        mx = x > mx ? x : mx;
+        if (p.scores_out) p.scores_out[(size_t)u * lc + a] = pm[i];
+      }
+    }
+  } else {
+    for (int a = tid; a < lc; a += kSelThreads) {
+      float m = raw[a];
+      const int lo = a - r < 0 ? 0 : a - r, hi = a + r >= lc ? lc - 1 : a + r;
+      for (int j = lo; j <= hi; ++j) m = fmaxf(m, raw[j]);
+      const uint32_t x = orderable(m);
+      pooled[a] = x;
+      mn = x < mn ? x : mn;
+      mx = x > mx ? x : mx;
+      if (p.scores_out) p.scores_out[(size_t)u * lc + a] = m;
+    }
   }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t a = __shfl_xor(mn, o), b = __shfl_xor(mx, o);
+    mn = a < mn ? a : mn;
+    mx = b > mx ? b : mx;
+  }
+  if (lane == 0) { atomicMin(&sh_min, mn); atomicMax(&sh_max, mx); }
   __syncthreads();
 
-  // value of the k-th largest pooled score by most-significant-digit radix select
-  uint32_t prefix = 0;
-  int krem = k;   // how many still to take among the elements matching `prefix`
-  if (k > 0 && k < lc) {
-    for (int shift = 24; shift >= 0; shift -= 8) {
+  // Value of the k-th largest pooled score by most-significant-digit radix select.  The bits
+  // all keys share (scores of one unit have similar exponents) are skipped: they would send
+  // every key to the same counter.
+  uint32_t prefix = sh_max;
+  int krem = k;   // how many still to take among the keys matching `prefix`
+  if (k > 0 && k < lc && sh_min != sh_max) {
+    int bits_left = 32 - __builtin_clz(sh_min ^ sh_max);      // 1 .. 32 low bits still undecided
+    prefix = bits_left == 32 ? 0u : (sh_max >> bits_left) << bits_left;
+    while (bits_left > 0) {
+      const int w = bits_left < 8 ? bits_left : 8, shift = bits_left - w;
+      const uint32_t dmask = (1u << w) - 1u;
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
-      for (int a = tid; a < lc; a += kSelThreads) {
-        const uint32_t x = orderable(pooled[a]);
-        if (shift == 24 || (x >> (shift + 8)) == (prefix >> (shift + 8)))
-          atomicAdd(&hist[(x >> shift) & 255u], 1);
+      for (int a0 = 0; a0 < lc; a0 += kSelThreads) {
+        const int a = a0 + tid;
+        const uint32_t x = a < lc ? pooled[a] : 0u;
+        const bool in = a < lc && (bits_left == 32 || (x >> bits_left) == (prefix >> bits_left));
+        const int d = (int)((x >> shift) & dmask);
+        // the digit of the first lane that takes part is counted once for all lanes that share it
+        const unsigned long long act = __ballot(in);
+        if (act) {
+          const int d0 = __shfl(d, __builtin_ctzll(act));
+          const unsigned long long same = __ballot(in && d == d0);
+          if (lane == __builtin_ctzll(act)) atomicAdd(&hist[d0], __popcll(same));
+          if (in && d != d0) atomicAdd(&hist[d], 1);
+        }
       }
       __syncthreads();
-      if (tid == 0) {
-        int rem = krem, d = 255;
-        for (; d > 0; --d) {
-          const int cnt = hist[d];
-          if (cnt >= rem) break;
-          rem -= cnt;
+      if (tid < 64) {
+        // lane t owns counters 4t .. 4t+3; find the digit at which the count from the top reaches krem
+        const int h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+        const int mine = h0 + h1 + h2 + h3;
+        int above = mine;                                     // inclusive sum over lanes >= t
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int x = __shfl_down(above, o);
+          if (tid + o < 64) above += x;
         }
-        sh_prefix = prefix | ((uint32_t)d << shift);
-        sh_krem = rem;
+        above -= mine;                                        // keys in counters of higher lanes
+        const int hh[4] = {h0, h1, h2, h3};
+        int run = above;
+#pragma unroll
+        for (int j = 3; j >= 0; --j) {
+          if (run < krem && krem <= run + hh[j]) {
+            sh_prefix = prefix | ((uint32_t)(4 * tid + j) << shift);
+            sh_krem = krem - run;
+          }
+          run += hh[j];
+        }
       }
       __syncthreads();
       prefix = sh_prefix;
       krem = sh_krem;
+      bits_left = shift;
       __syncthreads();
     }
   }
@@ -370,7 +450,7 @@ __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p) {
     ngt = a1 > a0 ? a1 - a0 : 0;
   } else if (k > 0) {
     for (int a = a0; a < a1; ++a) {
-      const uint32_t x = orderable(pooled[a]);
+      const uint32_t x = pooled[a];
       ngt += x > prefix;
       neq += x == prefix;
     }
@@ -382,7 +462,7 @@ __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p) {
   } else if (k > 0) {
     int eq_seen = oeq, gt_seen = ogt;
     for (int a = a0; a < a1; ++a) {
-      const uint32_t x = orderable(pooled[a]);
+      const uint32_t x = pooled[a];
       if (x > prefix) {
         kept[gt_seen + (eq_seen < krem ? eq_seen : krem)] = a;
         ++gt_seen;
@@ -544,8 +624,14 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   sp.scores = L.scores; sp.pooled = L.pooled; sp.scores_out = scores_out;
   sp.budgets = budgets; sp.kept = kept_idx;
   sp.l = l; sp.lc = lc; sp.lw = lw; sp.pool = pool_kernel; sp.budget = budget; sp.out_stride = out_stride;
-  { ProfScope ps("deep_select", st);
-  hipLaunchKernelGGL(deep_select, dim3(U), dim3(kSelThreads), 0, st, sp); }
+  {
+    const int vals_in_lds = lc <= kSelInLds;
+    const size_t sel_lds = vals_in_lds ? (size_t)lc * sizeof(uint32_t) : 0;
+    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&deep_select),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_lds));
+    ProfScope ps("deep_select", st);
+    hipLaunchKernelGGL(deep_select, dim3(U), dim3(kSelThreads), sel_lds, st, sp, vals_in_lds);
+  }
 
   GatherParams gp;
   gp.K = static_cast<const char *>(K); gp.V = static_cast<const char *>(V);

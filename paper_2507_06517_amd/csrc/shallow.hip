@@ -58,7 +58,6 @@ struct ShallowParams {
   uint32_t *fix;           // [UT][fix_cap] deferred pairs, b << 16 | a
   unsigned *fix_count;     // [UT]
   unsigned *fix_overflow;  // [1] some list was full
-  const uint32_t *zeros;   // 256 bytes of zeros (stands in for tokens past the end of the sequence)
   unsigned fix_cap;        // per ut
   uint32_t *ovf;           // [UT*n] tokens to re-point, packed ut << 16 | token
   unsigned *ovf_count;
@@ -642,13 +641,18 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
   const int ut = blockIdx.y, n = p.n, Wp = p.Wp;
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int row0 = (blockIdx.x * 4 + wave) * 4;
+  constexpr int kHold = 8;                           // 16-byte pieces of a row a lane keeps: rows of up to 65536 bits
   for (int v = row0; v < row0 + 4 && v < n; ++v) {
     const u4 *row = reinterpret_cast<const u4 *>(p.G + ((size_t)ut * n + v) * Wp);
+    u4 q[kHold];                                     // the row is read once
     int c = 0;
-    for (int w4 = lane; w4 < Wp / 4; w4 += kWave) {
-      const u4 q = row[w4];
-      c += __popc(q[0]) + __popc(q[1]) + __popc(q[2]) + __popc(q[3]);
+#pragma unroll
+    for (int i = 0; i < kHold; ++i) {
+      const int w4 = lane + i * kWave;
+      q[i] = w4 < Wp / 4 ? row[w4] : u4{0, 0, 0, 0};
     }
+#pragma unroll
+    for (int i = 0; i < kHold; ++i) c += __popc(q[i][0]) + __popc(q[i][1]) + __popc(q[i][2]) + __popc(q[i][3]);
     int incl = c;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -668,11 +672,12 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
     }
     if (deg <= kListCap) {
       uint16_t *dst = p.nbr + ((size_t)ut * n + v) * kListCap + (incl - c);
-      for (int w4 = lane; w4 < Wp / 4; w4 += kWave) {
-        const u4 q = row[w4];
+#pragma unroll
+      for (int i = 0; i < kHold; ++i) {
+        const int w4 = lane + i * kWave;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          uint32_t bits = q[j];
+          uint32_t bits = q[i][j];
           while (bits) {
             const int t = __builtin_ctz(bits);
             bits &= bits - 1;
@@ -1247,12 +1252,11 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.fix = cv.take<uint32_t>((size_t)UT * p.fix_cap);
   // everything that must start at zero sits together at the end:
   // counters [UT][kCounters], ovf_count + 3 spare, fix_count [UT]
-  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + (size_t)UT + 68);
+  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + (size_t)UT);
   int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
   p.ovf_count = reinterpret_cast<unsigned *>(tail);
   p.fix_overflow = reinterpret_cast<unsigned *>(tail ? tail + 1 : nullptr);
   p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
-  p.zeros = reinterpret_cast<const uint32_t *>(tail ? tail + ((4 + UT + 3) & ~3) : nullptr);   // 16-byte aligned
   return cv.total();
 }
 
@@ -1341,7 +1345,7 @@ extern "C" spindle_status spindle_compress_shallow(
     adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
   }
   // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = (size_t)p.UT * kCounters + 4 + (size_t)p.UT + 68;
+  const size_t nzero = (size_t)p.UT * kCounters + 4 + (size_t)p.UT;
   hipLaunchKernelGGL(fill_u32, dim3(64), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.counters), nzero, 0u);
   for (int i = 0; i < T; ++i)   // -1 marks "not finished": stays if a bounded wait expires
     hipLaunchKernelGGL(fill_u32, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.n_codes[i]), (size_t)U, 0xFFFFFFFFu);

@@ -17,7 +17,7 @@ def test_config1_fp32_with_cap(oracle):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
-@pytest.mark.parametrize("l", [1, 31, 33, 257, 300, 1100])
+@pytest.mark.parametrize("l", [1, 31, 33, 257, 300, 1100, 2500])
 def test_small_ragged(oracle, dtype, l):
     L = wl.small_random(7, dtype, B=1, H=2, l=l, lw=1, cap=max(1, l // 5), n_centroids=6, noise_frac=0.3)
     parity.check_shallow_layer(oracle, L)
