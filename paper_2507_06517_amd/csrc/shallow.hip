@@ -53,6 +53,8 @@ struct ShallowParams {
   uint32_t *G;             // [UT][n][Wp]
   int *deg0, *slot, *alive, *alive2, *cand, *dying, *pick_vert, *rank, *rank_vert;   // [UT][n]
   uint16_t *nbr;           // [UT][n][kListCap] neighbour lists of the sparse rows
+  uint8_t *gone8;          // [UT][n16] 1 once a token has been given a slot (grid rounds of the merge); n16 = n rounded up to 16
+  int n16;
   uint32_t *key, *gone, *m1, *pick_key;                                      // [UT][n]
   int *counters;           // [UT][kCounters]
   uint32_t *fix;           // [UT][fix_cap] deferred pairs, b << 16 | a
@@ -79,14 +81,22 @@ __device__ double dot64(const char *ra, const char *rb) {
   typedef typename Elem<DT>::type T;
   constexpr int per = 16 / sizeof(T);
   double acc = 0.0;
-  for (int ch = 0; ch < kHeadDim / per; ++ch) {
-    const u4 va = reinterpret_cast<const u4 *>(ra)[ch];
-    const u4 vb = reinterpret_cast<const u4 *>(rb)[ch];
-    const T *ea = reinterpret_cast<const T *>(&va);
-    const T *eb = reinterpret_cast<const T *>(&vb);
+  constexpr int kBatch = 8;                          // pieces of each row in flight
+  for (int c0 = 0; c0 < kHeadDim / per; c0 += kBatch) {
+    u4 va[kBatch], vb[kBatch];
 #pragma unroll
-    for (int i = 0; i < per; ++i)
-      acc += (double)Elem<DT>::to_float(ea[i]) * (double)Elem<DT>::to_float(eb[i]);
+    for (int i = 0; i < kBatch; ++i) {
+      va[i] = reinterpret_cast<const u4 *>(ra)[c0 + i];
+      vb[i] = reinterpret_cast<const u4 *>(rb)[c0 + i];
+    }
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const T *ea = reinterpret_cast<const T *>(&va[i]);
+      const T *eb = reinterpret_cast<const T *>(&vb[i]);
+#pragma unroll
+      for (int j = 0; j < per; ++j)
+        acc += (double)Elem<DT>::to_float(ea[j]) * (double)Elem<DT>::to_float(eb[j]);
+    }
   }
   return acc;
 }
@@ -616,18 +626,17 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
 
 // ---------------------------------------------------------------- exact fix-up
 __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
+  const int ut = blockIdx.y;                         // all problems side by side: each list is short
   const unsigned stride = gridDim.x * blockDim.x;
-  for (int ut = 0; ut < p.UT; ++ut) {
-    unsigned count = p.fix_count[ut];
-    if (count > p.fix_cap) count = p.fix_cap;
-    const uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
-    const double theta = (double)p.theta[ut / p.U];
-    for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-      const uint32_t e = list[i];
-      const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
-      if (cos64(p, ut, a, b) > theta)
-        atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
-    }
+  unsigned count = p.fix_count[ut];
+  if (count > p.fix_cap) count = p.fix_cap;
+  const uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
+  const double theta = (double)p.theta[ut / p.U];
+  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const uint32_t e = list[i];
+    const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
+    if (cos64(p, ut, a, b) > theta)
+      atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
   }
 }
 
@@ -666,7 +675,7 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
       p.key[i] = ((uint32_t)deg << 16) | (uint32_t)(0xFFFF - v);
       p.alive[i] = v;
       p.slot[i] = -1;
-      if ((v & 31) == 0) p.gone[(size_t)ut * n + (v >> 5)] = 0;
+      p.gone8[(size_t)ut * p.n16 + v] = 0;
       if (v == 0) p.counters[(size_t)ut * kCounters + C_ALIVE0] = n;
       if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = deg;
     }
@@ -828,6 +837,8 @@ __device__ __forceinline__ void phase_onehop(const ShallowParams &p, size_t base
   }
 }
 
+// kBytes: `dead` is the byte array of the grid rounds (plain stores); else the bitmap of the tail
+template <bool kBytes>
 __device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base, const MergeView &w, int ncand) {
   constexpr int kPer = kWave / kSegW;
   const uint32_t *m1 = p.m1 + base;
@@ -877,7 +888,8 @@ __device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base
     if (picked) for_nbrs(p, r, w.sl, [&](int b) {
       if (w.key[b] != 0) {
         slot[b] = s;
-        atomicOr(&w.dead[b >> 5], 1u << (b & 31));
+        if (kBytes) reinterpret_cast<uint8_t *>(w.dead)[b] = 1;
+        else atomicOr(&w.dead[b >> 5], 1u << (b & 31));
         dying[at++] = b;
       }
     });
@@ -910,7 +922,7 @@ __device__ __forceinline__ MergeView global_view(const ShallowParams &p, int ut)
   const size_t base = (size_t)ut * p.n;
   int *cnt = p.counters + (size_t)ut * kCounters;
   w.key = p.key + base;
-  w.dead = p.gone + base;
+  w.dead = reinterpret_cast<uint32_t *>(p.gone8 + (size_t)ut * p.n16);
   w.n_alive = cnt + C_ALIVE0;   // the grid kernels address the two alive counters themselves
   w.n_cand = cnt + C_CAND;
   w.n_dying = cnt + C_DYING;
@@ -943,14 +955,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, i
 __global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p) {
   const int ut = blockIdx.y;
   const MergeView w = global_view(p, ut);
-  phase_twohop(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_CAND]);
+  phase_twohop<true>(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_CAND]);
 }
 // End of a grid round.  Tokens marked dead get key 0; every other token of the list counts
 // its neighbours that are not dead (its new degree, Eq. 13: with most tokens leaving in the
 // first rounds, recounting the few that stay is cheaper than subtracting at every
 // neighbour of every leaving token), gets its new key and moves to the other list.
 __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, int round) {
-  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];     // dead bitmap of the problem
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];     // dead flags of the problem, one byte per token
   constexpr int kPer = kWave / kSegW;
   const int ut = blockIdx.y, lane = lane_id(), n = p.n;
   const size_t base = (size_t)ut * n;
@@ -959,9 +971,12 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
   const int seg = (blockIdx.x * blockDim.x + threadIdx.x) / kSegW, nsegs = gridDim.x * blockDim.x / kSegW;
   const int sl = threadIdx.x & (kSegW - 1);
   if ((int)(blockIdx.x * blockDim.x / kSegW) >= nalive) return;
-  for (int i = threadIdx.x; i < (n + 31) / 32; i += blockDim.x) lds[i] = p.gone[base + i];
+  {
+    const u4 *src8 = reinterpret_cast<const u4 *>(p.gone8 + (size_t)ut * p.n16);
+    for (int i = threadIdx.x; i < p.n16 / 16; i += blockDim.x) reinterpret_cast<u4 *>(lds)[i] = src8[i];
+  }
   __syncthreads();
-  const uint32_t *dead = lds;
+  const uint8_t *dead = reinterpret_cast<const uint8_t *>(lds);
   const int *src = (round & 1 ? p.alive2 : p.alive) + base;
   int *dst = (round & 1 ? p.alive : p.alive2) + base;
   uint32_t *key = p.key + base;
@@ -978,7 +993,7 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
     for (int k = 0; k < 4; ++k) {
       const int i = i0 + seg % kPer + k * nsegs;
       vv[k] = i < nalive ? src[i] : -1;
-      live[k] = vv[k] >= 0 && !((dead[vv[k] >> 5] >> (vv[k] & 31)) & 1u);
+      live[k] = vv[k] >= 0 && !dead[vv[k]];
       if (vv[k] >= 0 && !live[k] && sl == 0) key[vv[k]] = 0;
     }
 #pragma unroll
@@ -988,7 +1003,7 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       int c = 0;
-      if (live[k]) for_nbrs(p, r[k], sl, [&](int b) { c += !((dead[b >> 5] >> (b & 31)) & 1u); });
+      if (live[k]) for_nbrs(p, r[k], sl, [&](int b) { c += !dead[b]; });
 #pragma unroll
       for (int o = kSegW / 2; o > 0; o >>= 1) c += __shfl_xor(c, o);
       const bool lead = live[k] && sl == 0;
@@ -1068,7 +1083,15 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
 
   if (keys_in_lds) {
     for (int v = tid; v < n; v += kMergeThreads) w.key[v] = p.key[base + v];
-    for (int i = tid; i < dead_words; i += kMergeThreads) w.dead[i] = p.gone[base + i];
+  }
+  {
+    // the grid rounds keep one byte per token; this kernel works on a bitmap
+    const uint8_t *g8 = p.gone8 + (size_t)ut * p.n16;
+    for (int i = tid; i < dead_words; i += kMergeThreads) {
+      uint32_t word = 0;
+      for (int j = 0; j < 32 && 32 * i + j < n; ++j) word |= (uint32_t)(g8[32 * i + j] != 0) << j;
+      w.dead[i] = word;
+    }
   }
   if (tid == 0) { sh_n[0] = cnt[kGridRounds & 1]; sh_n[1] = 0; sh_n[2] = 0; sh_n[3] = cnt[C_PICKS]; }
   __syncthreads();
@@ -1083,7 +1106,7 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
     phase_onehop(p, base, w, alive, nalive);
     __syncthreads();
     MERGE_TICK(2)
-    phase_twohop(p, base, w, sh_n[1]);
+    phase_twohop<false>(p, base, w, sh_n[1]);
     __syncthreads();
     MERGE_TICK(4)
     const int ndying = sh_n[2];
@@ -1237,6 +1260,8 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.alive = cv.take<int>(N);
   p.alive2 = cv.take<int>(N);
   p.gone = cv.take<uint32_t>(N);
+  p.n16 = (n + 15) & ~15;
+  p.gone8 = cv.take<uint8_t>((size_t)UT * p.n16);
   p.nbr = cv.take<uint16_t>(N * kListCap);
   p.slot = cv.take<int>(N);
   p.cand = cv.take<int>(N);
@@ -1367,7 +1392,7 @@ extern "C" spindle_status spindle_compress_shallow(
   { ProfScope ps("shallow_gram_exact", st);
   hipLaunchKernelGGL(shallow_gram<true>, dim3(1024), dim3(kGramThreads), 0, st, p); }
   { ProfScope ps("shallow_fixup", st);
-  hipLaunchKernelGGL(shallow_fixup, dim3(1024), dim3(256), 0, st, p); }
+  hipLaunchKernelGGL(shallow_fixup, dim3(128, p.UT), dim3(256), 0, st, p); }
   {
     const int T1k = (n + 1023) / 1024, npairs = T1k * (T1k - 1) / 2;
     if (npairs > 0) {
@@ -1392,7 +1417,9 @@ extern "C" spindle_status spindle_compress_shallow(
     if (ox > 16) ox = 16;
     SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_onehop),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)key_lds));
-    const size_t dead_lds = (size_t)((n + 31) / 32) * sizeof(uint32_t);
+    const size_t dead_lds = (size_t)p.n16;
+    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_update),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)dead_lds));
     for (int round = 0; round < kGridRounds; ++round) {
       ProfScope ps("shallow_merge_grid", st);
       hipLaunchKernelGGL(merge_onehop, dim3(ox, p.UT), dim3(kMergeThreads), key_lds, st, p, round, keys_in_lds);
