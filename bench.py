@@ -110,7 +110,8 @@ def main():
     per_kernel = {}
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
-    kernel_ms = {k: float(np.mean(v)) for k, v in per_kernel.items()}
+    # per step: some kernels are launched several times per step (merge rounds)
+    kernel_ms = {k: float(np.sum(v)) / args.steps for k, v in per_kernel.items()}
 
     st = shallow.stats()
     n_codes = {t: shallow.out[f"n_found_{t}"].cpu().numpy().ravel().tolist() for t in ("k", "v")}
