@@ -511,17 +511,6 @@ constexpr int kMirrorThreads = 512;
 constexpr int kMirrorPitch = 17;                   // words per staged row: column reads hit 32 different banks
 constexpr size_t kMirrorLds = (size_t)1024 * kMirrorPitch * sizeof(uint32_t);
 
-// the 136 pairs wa <= wb < 16, as wa | wb << 8
-struct MirrorPairs {
-  uint16_t v[136];
-  constexpr MirrorPairs() : v() {
-    int t = 0;
-    for (int wb = 0; wb < 16; ++wb)
-      for (int wa = 0; wa <= wb; ++wa) v[t++] = (uint16_t)(wa | wb << 8);
-  }
-};
-__constant__ const MirrorPairs kMirrorPairs = MirrorPairs();
-
 // One stage of the 32 x 32 bit transpose held one row per lane (lane i of a 32-lane half =
 // row i): exchange with lane i ^ k, k = 16 >> st.  Lanes with bit k clear keep their bits
 // at positions with bit k clear and take the partner's bits of those positions, moved up by
@@ -580,7 +569,7 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
   // block belongs at (C, R): a wave takes the two blocks of an unordered pair, one per
   // 32-lane half, and writes each where the other was.  272 pairs (136 per square), 34 per
   // wave, handled two at a time so that the lane exchanges of one hide those of the other.
-  const int lane = lane_id(), wave = threadIdx.x >> 6, h = lane >> 5, i = lane & 31;
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), h = lane >> 5, i = lane & 31;
   uint32_t rot[5], keep[5];
 #pragma unroll
   for (int st = 0; st < 5; ++st) {
@@ -596,8 +585,9 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
     for (int u = 0; u < 2; ++u) {
       const int idx = (it + u) * (kMirrorThreads / 64) + wave;       // < 272
       const int sq = idx >= 136, t = idx - 136 * sq;
-      const uint32_t e = kMirrorPairs.v[t];                            // wa | wb << 8, wa <= wb < 16
-      const int wa = e & 0xFF, wb = e >> 8;
+      // t -> the t-th pair wa <= wb < 16: rows r and 15 - r of the triangle hold 17 pairs together
+      const int r = t / 17, c = t - 17 * r;
+      const int wa = c < 16 - r ? r : 15 - r, wb = c < 16 - r ? r + c : c - 1;
       const int R = h ? wb : wa, C = h ? wa : wb;
       uint32_t *sqp = mtile + sq * 512 * kMirrorPitch;
       src[u] = sqp + (32 * R + i) * kMirrorPitch + C;
