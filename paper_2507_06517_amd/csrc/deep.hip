@@ -283,29 +283,6 @@ __device__ __forceinline__ uint32_t orderable(float f) {
   return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 
-// exclusive scan of (a, b) over the block; returns this thread's offsets and the totals
-__device__ __forceinline__ void block_scan2(int a, int b, int &oa, int &ob, int &ta, int &tb,
-                                            int (*wsum)[2]) {
-  const int lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  int ia = a, ib = b;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int xa = __shfl_up(ia, o), xb = __shfl_up(ib, o);
-    if (lane >= o) { ia += xa; ib += xb; }
-  }
-  if (lane == 63) { wsum[wave][0] = ia; wsum[wave][1] = ib; }
-  __syncthreads();
-  int pa = 0, pb = 0;
-  ta = 0; tb = 0;
-  for (int w = 0; w < nw; ++w) {
-    if (w < wave) { pa += wsum[w][0]; pb += wsum[w][1]; }
-    ta += wsum[w][0]; tb += wsum[w][1];
-  }
-  oa = pa + ia - a;
-  ob = pb + ib - b;
-  __syncthreads();
-}
-
 constexpr int kSelInLds = 36 * 1024;   // pooled scores of a unit that fit in LDS
 
 __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p, int vals_in_lds) {
@@ -335,13 +312,18 @@ __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p, int v
     // raw scores to LDS with independent coalesced loads, pooled in registers, keys back in place
     constexpr int kPer = kSelInLds / kSelThreads;
     float *rawl = reinterpret_cast<float *>(sel_lds);
-#pragma unroll 4
+    float pm[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {                 // all loads of the thread in flight together
+      const int a = tid + i * kSelThreads;
+      pm[i] = a < lc ? raw[a] : 0.f;
+    }
+#pragma unroll
     for (int i = 0; i < kPer; ++i) {
       const int a = tid + i * kSelThreads;
-      if (a < lc) rawl[a] = raw[a];
+      if (a < lc) rawl[a] = pm[i];
     }
     __syncthreads();
-    float pm[kPer];
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
       const int a = tid + i * kSelThreads;
@@ -442,34 +424,39 @@ __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p, int v
       __syncthreads();
     }
   }
-  // ordered compaction: everything above the threshold, then the first `krem` equal to it
-  const int per = (lc + kSelThreads - 1) / kSelThreads;
-  const int a0 = tid * per, a1 = (a0 + per < lc) ? a0 + per : lc;
-  int ngt = 0, neq = 0;
+  // ordered compaction: everything above the threshold, then the first `krem` equal to it.
+  // Each wave owns a contiguous run of positions and walks it 64 at a time (coalesced,
+  // conflict-free); ranks within a step come from ballots, the offset of the wave from a
+  // count pass and a scan over the waves.
   if (k >= lc) {
-    ngt = a1 > a0 ? a1 - a0 : 0;
+    for (int a = tid; a < lc; a += kSelThreads) kept[a] = a;
   } else if (k > 0) {
-    for (int a = a0; a < a1; ++a) {
-      const uint32_t x = pooled[a];
-      ngt += x > prefix;
-      neq += x == prefix;
+    constexpr int kWaves = kSelThreads / 64;
+    const int wave = tid >> 6;
+    const int run = (((lc + kWaves - 1) / kWaves) + 63) & ~63;
+    const int w0 = wave * run, w1 = w0 + run < lc ? w0 + run : lc;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int ngt = 0, neq = 0;                              // wave-uniform
+    for (int a0 = w0; a0 < w1; a0 += 64) {
+      const int a = a0 + lane;
+      const uint32_t x = a < w1 ? pooled[a] : 0u;
+      ngt += __popcll(__ballot(a < w1 && x > prefix));
+      neq += __popcll(__ballot(a < w1 && x == prefix));
     }
-  }
-  int ogt, oeq, tgt, teq;
-  block_scan2(ngt, neq, ogt, oeq, tgt, teq, wsum);
-  if (k >= lc) {
-    for (int a = a0; a < a1; ++a) kept[a] = a;
-  } else if (k > 0) {
-    int eq_seen = oeq, gt_seen = ogt;
-    for (int a = a0; a < a1; ++a) {
-      const uint32_t x = pooled[a];
-      if (x > prefix) {
-        kept[gt_seen + (eq_seen < krem ? eq_seen : krem)] = a;
-        ++gt_seen;
-      } else if (x == prefix) {
-        if (eq_seen < krem) kept[gt_seen + eq_seen] = a;
-        ++eq_seen;
-      }
+    if (lane == 0) { wsum[wave][0] = ngt; wsum[wave][1] = neq; }
+    __syncthreads();
+    int gt_seen = 0, eq_seen = 0;
+    for (int w = 0; w < wave; ++w) { gt_seen += wsum[w][0]; eq_seen += wsum[w][1]; }
+    for (int a0 = w0; a0 < w1; a0 += 64) {
+      const int a = a0 + lane;
+      const uint32_t x = a < w1 ? pooled[a] : 0u;
+      const bool gt = a < w1 && x > prefix, eq = a < w1 && x == prefix;
+      const unsigned long long mgt = __ballot(gt), meq = __ballot(eq);
+      const int gt_before = gt_seen + __popcll(mgt & below), eq_before = eq_seen + __popcll(meq & below);
+      if (gt) kept[gt_before + (eq_before < krem ? eq_before : krem)] = a;
+      else if (eq && eq_before < krem) kept[gt_before + eq_before] = a;
+      gt_seen += __popcll(mgt);
+      eq_seen += __popcll(meq);
     }
   }
   for (int b = tid; b < p.lw; b += kSelThreads) kept[k + b] = lc + b;
