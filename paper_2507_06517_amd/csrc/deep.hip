@@ -2,8 +2,8 @@
 //
 // Kernels, all enqueued on the caller's stream:
 //   deep_pass<.., false>  window logits by MFMA, per-row softmax statistics (Eq. 1)
-//   deep_combine          merges the per-chunk statistics into (max, 1/sum) per query row
-//   deep_pass<.., true>   recomputes the logits, forms softmax weights, sums them over
+//   deep_pass<.., true>   merges the per-chunk statistics into (max, 1/sum) per query row,
+//                         recomputes the logits, forms softmax weights, sums them over
 //                         the window queries and the GQA group (Eq. 2, 3)
 //   deep_select           max-pool, radix select of the k largest, ordered compaction (Eq. 7)
 //   deep_gather           K_out = K[kept], V_out = V[kept]
@@ -25,7 +25,6 @@ struct DeepParams {
   const char *K;       // [U][l][128] elements
   const char *Q;       // [U][R][128] elements (R = hn*lw rows, head-major)
   float2 *partial;     // [U][nchunks][Rpad] (max, sum) per chunk of keys
-  float2 *stats;       // [U][Rpad] (max, 1/sum)
   float *scores;       // [U][lc] group-averaged accumulated attention
   int l, lc, lw, hn, R, Rpad, nchunks;
   float sc2;           // scale * log2(e): logits are kept in base-2 units
@@ -94,6 +93,33 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
       qf[rb][ks] = row < p.R ? M::load(Qunit + (size_t)row * M::kRowBytes, ks, g) : M::zero();
   }
 
+  // accumulate pass: (max, 1/sum) of every query row from the per-chunk statistics of the
+  // first pass, merged in chunk order by one thread per row (every block of the unit does
+  // the same sum in the same order)
+  __shared__ float2 row_stats[ACCUM ? 256 : 1];
+  if (ACCUM) {
+    if ((int)threadIdx.x < p.Rpad) {
+      const int row = threadIdx.x;
+      const float2 *part = p.partial + (size_t)u * p.nchunks * p.Rpad + row;
+      float m = -INFINITY, z = 0.f;
+#pragma unroll 8
+      for (int ch = 0; ch < p.nchunks; ++ch) {
+        const float2 e = part[(size_t)ch * p.Rpad];
+        if (e.y > 0.f) {
+          if (e.x > m) {
+            z = z * __builtin_amdgcn_exp2f(m - e.x) + e.y;
+            m = e.x;
+          } else {
+            z += e.y * __builtin_amdgcn_exp2f(e.x - m);
+          }
+        }
+      }
+      const bool ok = row < p.R && z > 0.f;
+      row_stats[row] = make_float2(ok ? m : 0.f, ok ? 1.f / z : 0.f);
+    }
+    __syncthreads();
+  }
+
   // per-row state of this lane: stats pass (reference, sum); accumulate pass (max, weight)
   float s0[2][16], s1[2][16];
 #pragma unroll
@@ -102,7 +128,7 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
     for (int v = 0; v < 16; ++v) {
       if (ACCUM) {
         const int row = 64 * wr + 32 * rb + mma_row(v, g);
-        const float2 st = p.stats[(size_t)u * p.Rpad + row];
+        const float2 st = row_stats[row];
         s0[rb][v] = st.x;
         s1[rb][v] = st.y;
       } else {
@@ -247,23 +273,6 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
       p.partial[((size_t)u * p.nchunks + chunk) * p.Rpad + row] = make_float2(m, z);
     }
   }
-}
-
-__global__ void deep_combine(DeepParams p, int U) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= U * p.Rpad) return;
-  const int u = i / p.Rpad, row = i % p.Rpad;
-  float m = -INFINITY;
-  for (int ch = 0; ch < p.nchunks; ++ch)
-    m = fmaxf(m, p.partial[((size_t)u * p.nchunks + ch) * p.Rpad + row].x);
-  float z = 0.f;
-  if (m > -INFINITY)
-    for (int ch = 0; ch < p.nchunks; ++ch) {
-      const float2 e = p.partial[((size_t)u * p.nchunks + ch) * p.Rpad + row];
-      if (e.y > 0.f) z += e.y * __builtin_amdgcn_exp2f(e.x - m);
-    }
-  const bool ok = row < p.R && z > 0.f;
-  p.stats[i] = make_float2(ok ? m : 0.f, ok ? 1.f / z : 0.f);
 }
 
 // ---------------------------------------------------------------- pool + top-k
@@ -492,7 +501,7 @@ __global__ __launch_bounds__(256) void deep_gather(GatherParams p) {
 
 // ---------------------------------------------------------------- host side
 struct DeepLayout {
-  float2 *partial, *stats;
+  float2 *partial;
   float *scores, *pooled;
   size_t bytes;
 };
@@ -503,7 +512,6 @@ DeepLayout deep_layout(void *ws, int U, int l, int lw, int Rpad) {
   const int nchunks = (l + kKeysPerBlock - 1) / kKeysPerBlock;
   const int lc = l - lw;
   L.partial = cv.take<float2>((size_t)U * nchunks * Rpad);
-  L.stats = cv.take<float2>((size_t)U * Rpad);
   L.scores = cv.take<float>((size_t)U * (lc > 0 ? lc : 1));
   L.pooled = cv.take<float>((size_t)U * (lc > 0 ? lc : 1));
   L.bytes = cv.total();
@@ -523,9 +531,6 @@ spindle_status launch_passes(const DeepParams &p, int U, hipStream_t st) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_acc));
   { ProfScope ps("deep_stats", st);
   hipLaunchKernelGGL((deep_pass<DT, WR, false>), dim3(p.nchunks, U), dim3(kDeepThreads), smem_stats, st, p); }
-  const int total = U * p.Rpad;
-  { ProfScope ps("deep_combine", st);
-  hipLaunchKernelGGL(deep_combine, dim3((total + 255) / 256), dim3(256), 0, st, p, U); }
   if (p.lc > 0) {
     const int nacc = (p.lc + kKeysPerBlock - 1) / kKeysPerBlock;
     ProfScope ps("deep_accumulate", st);
@@ -595,7 +600,6 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   p.K = static_cast<const char *>(K);
   p.Q = static_cast<const char *>(Qw);
   p.partial = L.partial;
-  p.stats = L.stats;
   p.scores = L.scores;
   p.l = l; p.lc = lc; p.lw = lw; p.hn = desc->group_size; p.R = R; p.Rpad = Rpad;
   p.nchunks = (l + kKeysPerBlock - 1) / kKeysPerBlock;

@@ -531,7 +531,9 @@ __device__ __forceinline__ uint32_t transpose_stage(uint32_t x, int st, uint32_t
     y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
   }
   const uint32_t moved = __builtin_amdgcn_alignbit(y, y, rot);
-  return (x & keep) | (moved & ~keep);
+  uint32_t r;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(keep), "v"(x), "v"(moved));   // (x & keep) | (moved & ~keep)
+  return r;
 }
 
 __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p) {
@@ -578,20 +580,23 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
     rot[st] = (i & k) ? k : 32 - k;
     keep[st] = (i & k) ? ~m : m;
   }
+  const int lane_off = i * kMirrorPitch;             // word offset of this lane's row within a block
   for (int it = 0; it < 34; it += 2) {
     uint32_t *src[2], *dst[2];
     bool wr[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
+      // everything up to the choice between the two blocks of the pair is wave-uniform
       const int idx = (it + u) * (kMirrorThreads / 64) + wave;       // < 272
       const int sq = idx >= 136, t = idx - 136 * sq;
       // t -> the t-th pair wa <= wb < 16: rows r and 15 - r of the triangle hold 17 pairs together
       const int r = t / 17, c = t - 17 * r;
       const int wa = c < 16 - r ? r : 15 - r, wb = c < 16 - r ? r + c : c - 1;
-      const int R = h ? wb : wa, C = h ? wa : wb;
-      uint32_t *sqp = mtile + sq * 512 * kMirrorPitch;
-      src[u] = sqp + (32 * R + i) * kMirrorPitch + C;
-      dst[u] = sqp + (32 * C + i) * kMirrorPitch + R;
+      const int base = sq * 512 * kMirrorPitch;
+      const int at_ab = base + 32 * wa * kMirrorPitch + wb;             // block (wa, wb)
+      const int at_ba = base + 32 * wb * kMirrorPitch + wa;             // block (wb, wa)
+      src[u] = mtile + (h ? at_ba : at_ab) + lane_off;
+      dst[u] = mtile + (h ? at_ab : at_ba) + lane_off;
       wr[u] = h == 0 || wa != wb;
     }
     uint32_t x0 = *src[0], x1 = *src[1];

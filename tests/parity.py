@@ -138,10 +138,10 @@ def check_shallow_unit(orc, X64, theta, cap, dtype, g, t, b, h, full_adj=True):
     return o
 
 
-def check_shallow_layer(orc, L: wl.Layer, cap=None, units=None, tensors=("k", "v"), g=None):
+def check_shallow_layer(orc, L: wl.Layer, cap=None, units=None, tensors=("k", "v"), g=None, debug=True):
     cap = cap or L.max_codes
     if g is None:
-        g = gpu_shallow(L, cap, tensors=tensors)
+        g = gpu_shallow(L, cap, debug=debug, tensors=tensors)
     B, H, l, d = L.K.shape
     todo = units if units is not None else [(b, h) for b in range(B) for h in range(H)]
     from concurrent.futures import ThreadPoolExecutor

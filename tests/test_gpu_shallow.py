@@ -24,6 +24,15 @@ def test_small_ragged(oracle, dtype, l):
     parity.check_shallow_layer(oracle, L, cap=l)
 
 
+@pytest.mark.parametrize("l,n_centroids", [(1100, 6), (2500, 6), (2500, 40), (3300, 64)])
+def test_without_adjacency_export(oracle, l, n_centroids):
+    # no adjacency output requested: the lower triangle of G is only written when some row has
+    # more neighbours than a list holds (few centroids), else the lists are built from the
+    # transposed tiles alone (many centroids)
+    L = wl.small_random(12, "f16", B=1, H=2, l=l, lw=1, cap=l, n_centroids=n_centroids, noise_frac=0.3)
+    parity.check_shallow_layer(oracle, L, debug=False)
+
+
 def test_threshold_extremes_and_single_tensor(oracle):
     L = wl.small_random(8, "f16", B=1, H=1, l=200, lw=1, cap=200)
     L.theta_k, L.theta_v = 1.0, -1.5
