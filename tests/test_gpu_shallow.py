@@ -64,6 +64,18 @@ def test_duplicates_and_zero_vectors(oracle):
     assert len(set(g["ref_k"][0, 0, 100:150].tolist() + [g["ref_k"][0, 0, 7]])) == 1
 
 
+def test_cut_tokens_with_many_equidistant_entries(oracle):
+    # zero vectors have cosine 0 with every entry: when their own entry is cut, every stored entry
+    # ties, the candidate lists of the matrix-core search run full and the exhaustive search must
+    # give entry 0; near-duplicates of one token, cut as well, must all land on the same entry
+    L = wl.small_random(13, "f16", B=1, H=1, l=700, lw=1, cap=40, n_centroids=60, noise_frac=0.5)
+    L.K[0, 0, 300:310] = 0
+    L.V[0, 0, 5] = 0
+    res, g = parity.check_shallow_layer(oracle, L)
+    assert res[0]["n_codes_uncapped"] > 40
+    assert (g["ref_k"][0, 0, 300:310] == 0).all()
+
+
 def test_config2(oracle):
     res, g = parity.check_shallow_layer(oracle, wl.config2(0))
     print("config2 codes", [o["n_codes_uncapped"] for o in res])
