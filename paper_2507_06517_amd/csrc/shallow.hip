@@ -1405,9 +1405,17 @@ __global__ __launch_bounds__(256) void shallow_overflow(ShallowParams p) {
   }
 }
 
-__global__ void fill_u32(uint32_t *dst, size_t count, uint32_t v) {
-  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
-    dst[i] = v;
+// What must hold before the first kernel of a call: counters, list counts and flags zero,
+// n_codes = -1 ("not finished"), codebooks zero.  One launch for all of it.
+__global__ __launch_bounds__(256) void shallow_init(ShallowParams p, size_t nzero, size_t cwords, int T) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x, i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t *z = reinterpret_cast<uint32_t *>(p.counters);
+  for (size_t i = i0; i < nzero; i += stride) z[i] = 0u;
+  for (int t = 0; t < T; ++t) {
+    for (size_t i = i0; i < (size_t)p.U; i += stride) p.n_codes[t][i] = -1;
+    u4 *c = reinterpret_cast<u4 *>(p.C[t]);               // 16-byte aligned, a multiple of 16 bytes per row
+    for (size_t i = i0; i < cwords / 4; i += stride) c[i] = u4{0, 0, 0, 0};
+  }
 }
 
 // Copies the rows of G without their padding words.
@@ -1547,12 +1555,8 @@ extern "C" spindle_status spindle_compress_shallow(
   }
   // zero: counters, list counts, error flag, barriers; codebooks
   const size_t nzero = (size_t)p.UT * kCounters + 4 + 2 * (size_t)p.UT;
-  hipLaunchKernelGGL(fill_u32, dim3(64), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.counters), nzero, 0u);
-  for (int i = 0; i < T; ++i)   // -1 marks "not finished": stays if a bounded wait expires
-    hipLaunchKernelGGL(fill_u32, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.n_codes[i]), (size_t)U, 0xFFFFFFFFu);
   const size_t cwords = (size_t)U * max_codes * kHeadDim * dtype_bytes(p.dtype) / 4;
-  for (int i = 0; i < T; ++i)
-    hipLaunchKernelGGL(fill_u32, dim3(1024), dim3(256), 0, st, reinterpret_cast<uint32_t *>(p.C[i]), cwords, 0u);
+  hipLaunchKernelGGL(shallow_init, dim3(1024), dim3(256), 0, st, p, nzero, cwords, T);
 
   const dim3 pgrid((n + 63) / 64, p.UT);
   { ProfScope ps("shallow_prep", st);
