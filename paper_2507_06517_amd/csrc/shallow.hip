@@ -2,16 +2,24 @@
 //
 // Kernels, all enqueued on the caller's stream; ut = tensor * units + unit indexes one
 // independent (batch, kv-head, K|V) problem of n tokens:
+//   shallow_init    counters, flags and outputs that must start from a known value
 //   shallow_prep    magnitudes (Eq. 8) in double precision, unit vectors rounded to fp16
 //   shallow_gram    cosine similarity tiles by fp16 MFMA, thresholded and bit-packed
-//                   into the adjacency matrix G (Eq. 4, 9); pairs whose fp16 similarity
-//                   lies within kGuard of theta are deferred to shallow_fixup
+//                   into the adjacency matrix G (Eq. 4, 9), upper triangle only; pairs whose
+//                   fp16 similarity lies within kGuard of theta are deferred to shallow_fixup
+//                   (shallow_gram<true>: in-place fallback when a pair list overflows)
 //   shallow_fixup   exact double-precision decision for the deferred pairs
+//   shallow_mirror  lower triangle of G by bit transposition
 //   shallow_lists   degrees (Eq. 10) and compact neighbour lists of the sparse rows of G
-//   shallow_merge   the greedy highest-degree codebook construction (Eq. 11-13), all
-//                   rounds on the device, one workgroup per problem
+//   merge_onehop, merge_twohop, merge_update, merge_reset
+//                   the first rounds of the greedy highest-degree codebook construction
+//                   (Eq. 11-13) in its exact parallel form, one launch per phase
+//   shallow_merge   the remaining rounds, one workgroup per problem
+//   shallow_rank    codebook order of the picked tokens
 //   shallow_emit    references in codebook order and the codebook vectors
-//   shallow_overflow  re-points tokens whose entry fell beyond the codebook cap
+//   shallow_assign, shallow_assign_exact, shallow_overflow
+//                   tokens whose entry fell beyond the codebook cap go to the nearest
+//                   stored entry
 #include <math.h>
 #include <string.h>
 
@@ -1147,31 +1155,86 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
   MERGE_TICK(9)
 }
 
-// Codebook order: the rank of each pick among all picks of its problem by decreasing key at
-// pick time (keys are distinct: they carry the token index).
-__global__ __launch_bounds__(256) void shallow_rank(ShallowParams p) {
-  __shared__ uint32_t tile[1024];
-  const int ut = blockIdx.y;
+// Codebook order: the picks of a problem sorted by decreasing key at pick time (keys are
+// distinct: they carry the token index).  One workgroup per problem: least-significant-digit
+// radix sort, four stable passes of 8 bits over (key, pick number) pairs that ping-pong
+// between two pairs of arrays left free by the merge.  A pass counts the digits, then walks
+// the items in order, 1024 at a time: lanes with the same digit find each other with eight
+// ballots, waves exchange their digit counts through LDS.
+constexpr int kRankThreads = 1024;
+
+__global__ __launch_bounds__(kRankThreads) void shallow_rank(ShallowParams p) {
+  constexpr int kWaves = kRankThreads / 64;
+  __shared__ int base_of[256];                       // next output position of each digit
+  __shared__ int wave_cnt[kWaves][256];              // items of each digit per wave in the current tile
+  __shared__ int scan_tmp[256];
+  const int ut = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
   const size_t base = (size_t)ut * p.n;
-  if (p.n_codes[ut / p.U][ut % p.U] < 0) return;   // construction did not finish
+  if (p.n_codes[ut / p.U][ut % p.U] < 0) return;     // construction did not finish
   const int P = p.counters[(size_t)ut * kCounters + C_PICKS];
-  const uint32_t *pick_key = p.pick_key + base;
-  for (int s0 = blockIdx.x * 256; s0 < P; s0 += gridDim.x * 256) {
-    const int s = s0 + threadIdx.x;
-    const uint32_t ks = s < P ? pick_key[s] : 0xFFFFFFFFu;
-    int r = 0;
-    for (int b0 = 0; b0 < P; b0 += 1024) {
+  uint32_t *keyA = p.pick_key + base, *keyB = p.m1 + base;
+  uint32_t *valA = reinterpret_cast<uint32_t *>(p.cand + base), *valB = reinterpret_cast<uint32_t *>(p.dying + base);
+  for (int s = tid; s < P; s += kRankThreads) valA[s] = (uint32_t)s;
+  __syncthreads();
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 8 * pass;
+    const uint32_t *kin = pass & 1 ? keyB : keyA, *vin = pass & 1 ? valB : valA;
+    uint32_t *kout = pass & 1 ? keyA : keyB, *vout = pass & 1 ? valA : valB;
+    // digit 255 - byte: larger keys first
+    if (tid < 256) base_of[tid] = 0;
+    __syncthreads();
+    for (int s = tid; s < P; s += kRankThreads) atomicAdd(&base_of[255 - ((kin[s] >> shift) & 255u)], 1);
+    __syncthreads();
+    // exclusive prefix sum over the 256 counters
+    if (tid < 256) scan_tmp[tid] = base_of[tid];
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+      int x = 0;
+      if (tid < 256 && tid >= o) x = scan_tmp[tid - o];
       __syncthreads();
-      for (int j = threadIdx.x; j < 1024; j += 256) tile[j] = b0 + j < P ? pick_key[b0 + j] : 0u;
+      if (tid < 256) scan_tmp[tid] += x;
       __syncthreads();
-      const int lim = P - b0 < 1024 ? P - b0 : 1024;
-#pragma unroll 8
-      for (int j = 0; j < lim; ++j) r += tile[j] > ks;
     }
-    if (s < P) {
-      p.rank[base + s] = r;
-      p.rank_vert[base + r] = p.pick_vert[base + s];
+    if (tid < 256) base_of[tid] = scan_tmp[tid] - base_of[tid];
+    __syncthreads();
+    for (int s0 = 0; s0 < P; s0 += kRankThreads) {
+      const int s = s0 + tid;
+      const bool on = s < P;
+      const uint32_t k = on ? kin[s] : 0u, v = on ? vin[s] : 0u;
+      const int d = on ? 255 - (int)((k >> shift) & 255u) : 256;      // 256: no item
+      for (int j = tid; j < kWaves * 256; j += kRankThreads) (&wave_cnt[0][0])[j] = 0;
+      // lanes of the wave with the same digit
+      unsigned long long peers = __ballot(on);
+#pragma unroll
+      for (int bit = 0; bit < 8; ++bit) {
+        const unsigned long long m = __ballot((d >> bit) & 1);
+        peers &= ((d >> bit) & 1) ? m : ~m;
+      }
+      const int before = __popcll(peers & ((1ull << lane) - 1ull));
+      __syncthreads();                                // counters cleared
+      if (on && before == 0) wave_cnt[wave][d] = __popcll(peers);
+      __syncthreads();
+      if (on) {
+        int at = base_of[d] + before;
+        for (int w = 0; w < wave; ++w) at += wave_cnt[w][d];
+        kout[at] = k;
+        vout[at] = v;
+      }
+      __syncthreads();
+      if (tid < 256) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) t += wave_cnt[w][tid];
+        base_of[tid] += t;
+      }
+      __syncthreads();
     }
+  }
+  // four passes: the sorted pairs are back in the first pair of arrays
+  for (int r = tid; r < P; r += kRankThreads) {
+    const int s = (int)valA[r];
+    p.rank[base + s] = r;
+    p.rank_vert[base + r] = p.pick_vert[base + s];
   }
 }
 
@@ -1614,8 +1677,7 @@ extern "C" spindle_status spindle_compress_shallow(
   { ProfScope ps("shallow_merge", st);
   hipLaunchKernelGGL(shallow_merge, dim3(p.UT), dim3(kMergeThreads), merge_lds, st, p); }
   { ProfScope ps("shallow_rank", st);
-  int rx = (n + 255) / 256;
-  hipLaunchKernelGGL(shallow_rank, dim3(rx < 32 ? rx : 32, p.UT), dim3(256), 0, st, p); }
+  hipLaunchKernelGGL(shallow_rank, dim3(p.UT), dim3(kRankThreads), 0, st, p); }
   { ProfScope ps("shallow_emit", st);
   int ex = (n + 1023) / 1024;
   hipLaunchKernelGGL(shallow_emit, dim3(ex < 64 ? ex : 64, p.UT), dim3(256), 0, st, p); }
