@@ -158,10 +158,11 @@ spindle_status spindle_compress_shallow(const spindle_kv_desc *desc, const void 
  * shape: for each of the batch * n_kv_heads * n_tensors problems i (all K units first,
  * then all V units), with s = stats + 16*i: s[0] = rounds of the parallel codebook
  * construction, s[1] = codebook entries found, s[2] = token pairs whose adjacency was
- * decided in double precision, s[4..13] = microseconds one block of the problem spent in
- * the phases of the construction (keys, wait, one-hop, wait, two-hop, wait, degree update,
- * wait, ordering, output), others 0.  `stats` is a HOST buffer of
- * 16 * batch * n_kv_heads * n_tensors int32.  Waits for `stream`.
+ * decided in double precision, s[4..13] = microseconds the workgroup that runs the later
+ * rounds of the problem spent in their phases (s[4] loading keys and compacting the list of
+ * remaining tokens, s[6] one-hop maxima, s[8] two-hop maxima and picks, s[10] degree updates,
+ * s[12], s[13] bookkeeping; the odd slots in between are unused), others 0.  `stats` is a HOST
+ * buffer of 16 * batch * n_kv_heads * n_tensors int32.  Waits for `stream`.
  */
 spindle_status spindle_shallow_stats(const spindle_kv_desc *desc, int32_t n_tensors,
                                      const void *workspace, void *stream, int32_t *stats);
