@@ -55,6 +55,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--seq-len", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=["config4", "config5"], default="config4",
+                    help="config4 = the benchmark configuration; config5 = one layer of the batch-4 bf16 stack "
+                         "(half of the tokens isolated noise, codebook cut to --cap): a secondary figure")
+    ap.add_argument("--cap", type=int, default=4096, help="budget = codebook cap of --workload config5")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (scale reference for the HBM traffic counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "shallow_gram_config4_traffic.json"))
@@ -68,7 +72,7 @@ def main():
     sb.lib()
     torch.cuda.set_device(0)
 
-    L = wl.config4(0, seq_len=args.seq_len)
+    L = wl.config4(0, seq_len=args.seq_len) if args.workload == "config4" else wl.config5_layer(0, args.cap)
     K, V, Q = (sb.to_device(x, L.dtype) for x in (L.K, L.V, L.Qw))
     deep = sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, want_scores=False)
     shallow = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)
@@ -126,7 +130,7 @@ def main():
     gram_ms = kernel_ms.get("shallow_gram", float("nan"))
     achieved = gram_flop / (gram_ms * 1e-3) / 1e12
     traffic = None
-    if os.path.exists(args.traffic_json):
+    if args.workload == "config4" and os.path.exists(args.traffic_json):
         try:
             traffic = json.load(open(args.traffic_json)).get("hbm_bytes_per_launch")
         except Exception:
@@ -137,10 +141,14 @@ def main():
         "unit": "tokens/s/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"configs[3]: Mistral-7B-shaped layer, 8 KV heads x 4 Q heads, head_dim 128, "
-                               f"seq_len {L.seq_len}, fp16, 256 drifting clusters; deep: window 64, pool 7, "
-                               f"budget 2048; shallow: K and V, theta 0.98/0.95, cap 2048; batch 1"},
+        "dtype": L.dtype, "data": "synthetic",
+        "config": {"workload": (f"configs[3]: Mistral-7B-shaped layer, 8 KV heads x 4 Q heads, head_dim 128, "
+                                f"seq_len {L.seq_len}, fp16, 256 drifting clusters; deep: window 64, pool 7, "
+                                f"budget 2048; shallow: K and V, theta 0.98/0.95, cap 2048; batch 1")
+                   if args.workload == "config4" else
+                   (f"configs[4], one layer: batch 4, 8 KV heads x 4 Q heads, head_dim 128, seq_len {L.seq_len}, "
+                    f"bf16, half clustered / half noise; deep: window 64, pool 15, budget {L.budget}; "
+                    f"shallow: K and V, theta 0.98/0.95, cap {L.max_codes}")},
         "deep_ms": ms_deep, "shallow_ms": ms_shallow,
         "deep_tokens_per_s": tokens / (ms_deep * 1e-3), "shallow_tokens_per_s": tokens / (ms_shallow * 1e-3),
         "kernel_ms": kernel_ms,
