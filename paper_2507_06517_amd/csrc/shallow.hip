@@ -924,6 +924,34 @@ __device__ __forceinline__ void phase_degree(const ShallowParams &p, size_t base
   }
 }
 
+// Eq. 13 the other way round: every token of the list counts its neighbours that are still
+// there (dead bitmap).  Cheaper than phase_degree when more tokens left than stayed.
+__device__ __forceinline__ void phase_recount(const ShallowParams &p, size_t base, const MergeView &w,
+                                              const int *alive, int nalive) {
+  constexpr int kPer = kWave / kSegW;
+  for (int i0 = w.seg - w.seg % kPer; i0 < nalive; i0 += 4 * w.nsegs) {
+    int vv[4];
+    bool on[4];
+    Nbrs r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + w.seg % kPer + k * w.nsegs;
+      on[k] = i < nalive;
+      vv[k] = on[k] ? alive[i] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r[k] = load_nbrs(p, base, vv[k], w.sl);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      int c = 0;
+      if (on[k]) for_nbrs(p, r[k], w.sl, [&](int b) { c += !((w.dead[b >> 5] >> (b & 31)) & 1u); });
+#pragma unroll
+      for (int o = kSegW / 2; o > 0; o >>= 1) c += __shfl_xor(c, o);
+      if (on[k] && w.sl == 0) w.key[vv[k]] = ((uint32_t)c << 16) | (uint32_t)(0xFFFF - vv[k]);
+    }
+  }
+}
+
 __device__ __forceinline__ MergeView global_view(const ShallowParams &p, int ut) {
   MergeView w;
   const size_t base = (size_t)ut * p.n;
@@ -1117,9 +1145,6 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
     __syncthreads();
     MERGE_TICK(4)
     const int ndying = sh_n[2];
-    phase_degree(p, base, w, ndying);
-    __syncthreads();
-    MERGE_TICK(6)
     for (int i = tid; i < ndying; i += kMergeThreads) w.key[dying[i]] = 0;
     if (tid == 0) { sh_n[0] = 0; sh_n[1] = 0; sh_n[2] = 0; }
     __syncthreads();
@@ -1139,6 +1164,12 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
       __syncthreads();
     }
     MERGE_TICK(0)
+    // degrees of the survivors (Eq. 13): subtract at the neighbours of the tokens that left,
+    // or recount at the tokens that stayed, whichever list is shorter
+    if (ndying <= nalive - ndying) phase_degree(p, base, w, ndying);
+    else phase_recount(p, base, w, alive, nalive - ndying);
+    __syncthreads();
+    MERGE_TICK(6)
   }
   if (tid == 0) cnt[C_ROUNDS] = round;
   if (sh_n[0] != 0) return;                      // did not converge: n_codes stays -1
