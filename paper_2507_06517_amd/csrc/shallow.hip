@@ -845,7 +845,8 @@ __device__ __forceinline__ void phase_onehop(const ShallowParams &p, size_t base
 }
 
 // kBytes: `dead` is the byte array of the grid rounds (plain stores); else the bitmap of the tail
-template <bool kBytes>
+// kFlight: candidates a segment works on at once
+template <bool kBytes, int kFlight>
 __device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base, const MergeView &w, int ncand) {
   constexpr int kPer = kWave / kSegW;
   const uint32_t *m1 = p.m1 + base;
@@ -853,53 +854,71 @@ __device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base
   int *slot = p.slot + base, *dying = p.dying + base, *pick_vert = p.pick_vert + base;
   uint32_t *pick_key = p.pick_key + base;
   const int lane = lane_id();
-  for (int i0 = w.seg - w.seg % kPer; i0 < ncand; i0 += w.nsegs) {
-    const int i = i0 + w.seg % kPer;
-    const bool on = i < ncand;
-    const int uvert = on ? cand[i] : 0;
-    const uint32_t ku = on ? w.key[uvert] : 0xFFFFFFFFu;
-    const Nbrs r = load_nbrs(p, base, uvert, w.sl);
-    uint32_t m = 0;
-    int rem = 0;                                    // remaining neighbours in this lane's part
-    // remaining = key != 0 (keys only change in the later phases of the round)
-    if (on) for_nbrs(p, r, w.sl, [&](int b) {
-      if (w.key[b] != 0) { const uint32_t k = m1[b]; m = k > m ? k : m; ++rem; }
-    });
-    m = seg_max(m);
-    const bool picked = on && m == ku;
-    // one update of each counter per wave: picks by the segment leaders, dying tokens by all lanes
-    const unsigned long long pk = __ballot(picked && w.sl == 0);
-    if (pk == 0) continue;                           // wave-uniform
-    int s = 0;
-    {
-      int at = 0;
-      if (lane == __builtin_ctzll(pk)) at = atomicAdd(w.n_picks, __popcll(pk));
-      at = __shfl(at, __builtin_ctzll(pk));
-      if (picked && w.sl == 0) {
-        s = at + __popcll(pk & ((1ull << lane) - 1ull));
-        pick_key[s] = ku;
-        pick_vert[s] = uvert;
-      }
-    }
-    s = __shfl(s, lane & ~(kSegW - 1));
-    const int mine = picked ? rem : 0;
-    int incl = mine;
+  for (int i0 = w.seg - w.seg % kPer; i0 < ncand; i0 += kFlight * w.nsegs) {
+    int uv[kFlight], rem[kFlight];
+    bool on[kFlight];
+    uint32_t ku[kFlight], m[kFlight];
+    Nbrs r[kFlight];
 #pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-      const int x = __shfl_up(incl, o);
-      if (lane >= o) incl += x;
+    for (int k = 0; k < kFlight; ++k) {
+      const int i = i0 + w.seg % kPer + k * w.nsegs;
+      on[k] = i < ncand;
+      uv[k] = on[k] ? cand[i] : 0;
     }
-    int at = 0;
-    if (lane == kWave - 1) at = atomicAdd(w.n_dying, incl);
-    at = __shfl(at, kWave - 1) + incl - mine;
-    if (picked) for_nbrs(p, r, w.sl, [&](int b) {
-      if (w.key[b] != 0) {
-        slot[b] = s;
-        if (kBytes) reinterpret_cast<uint8_t *>(w.dead)[b] = 1;
-        else atomicOr(&w.dead[b >> 5], 1u << (b & 31));
-        dying[at++] = b;
+#pragma unroll
+    for (int k = 0; k < kFlight; ++k) {
+      ku[k] = on[k] ? w.key[uv[k]] : 0xFFFFFFFFu;
+      r[k] = load_nbrs(p, base, uv[k], w.sl);
+    }
+#pragma unroll
+    for (int k = 0; k < kFlight; ++k) {
+      uint32_t mk = 0;
+      int rk = 0;                                    // remaining neighbours in this lane's part
+      // remaining = key != 0 (keys only change in the later phases of the round)
+      if (on[k]) for_nbrs(p, r[k], w.sl, [&](int b) {
+        if (w.key[b] != 0) { const uint32_t q = m1[b]; mk = q > mk ? q : mk; ++rk; }
+      });
+      m[k] = seg_max(mk);
+      rem[k] = rk;
+    }
+#pragma unroll
+    for (int k = 0; k < kFlight; ++k) {
+      const bool picked = on[k] && m[k] == ku[k];
+      // one update of each counter per wave: picks by the segment leaders, dying tokens by all lanes
+      const unsigned long long pk = __ballot(picked && w.sl == 0);
+      if (pk != 0) {                                 // wave-uniform
+        int s = 0;
+        {
+          int at = 0;
+          if (lane == __builtin_ctzll(pk)) at = atomicAdd(w.n_picks, __popcll(pk));
+          at = __shfl(at, __builtin_ctzll(pk));
+          if (picked && w.sl == 0) {
+            s = at + __popcll(pk & ((1ull << lane) - 1ull));
+            pick_key[s] = ku[k];
+            pick_vert[s] = uv[k];
+          }
+        }
+        s = __shfl(s, lane & ~(kSegW - 1));
+        const int mine = picked ? rem[k] : 0;
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+          const int x = __shfl_up(incl, o);
+          if (lane >= o) incl += x;
+        }
+        int at = 0;
+        if (lane == kWave - 1) at = atomicAdd(w.n_dying, incl);
+        at = __shfl(at, kWave - 1) + incl - mine;
+        if (picked) for_nbrs(p, r[k], w.sl, [&](int b) {
+          if (w.key[b] != 0) {
+            slot[b] = s;
+            if (kBytes) reinterpret_cast<uint8_t *>(w.dead)[b] = 1;
+            else atomicOr(&w.dead[b >> 5], 1u << (b & 31));
+            dying[at++] = b;
+          }
+        });
       }
-    });
+    }
   }
 }
 
@@ -990,7 +1009,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, i
 __global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p) {
   const int ut = blockIdx.y;
   const MergeView w = global_view(p, ut);
-  phase_twohop<true>(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_CAND]);
+  phase_twohop<true, 4>(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_CAND]);
 }
 // End of a grid round.  Tokens marked dead get key 0; every other token of the list counts
 // its neighbours that are not dead (its new degree, Eq. 13: with most tokens leaving in the
@@ -1141,7 +1160,7 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
     phase_onehop(p, base, w, alive, nalive);
     __syncthreads();
     MERGE_TICK(2)
-    phase_twohop<false>(p, base, w, sh_n[1]);
+    phase_twohop<false, 2>(p, base, w, sh_n[1]);
     __syncthreads();
     MERGE_TICK(4)
     const int ndying = sh_n[2];
