@@ -1136,14 +1136,25 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
   if (tid == 0) tick_ = wall_clock64();
 
   if (keys_in_lds) {
-    for (int v = tid; v < n; v += kMergeThreads) w.key[v] = p.key[base + v];
+    if ((n & 3) == 0) {                               // rows of the key array are then 16-byte aligned
+      const u4 *src = reinterpret_cast<const u4 *>(p.key + base);
+      for (int i = tid; i < n / 4; i += kMergeThreads) reinterpret_cast<u4 *>(w.key)[i] = src[i];
+    } else {
+      for (int v = tid; v < n; v += kMergeThreads) w.key[v] = p.key[base + v];
+    }
   }
   {
-    // the grid rounds keep one byte per token; this kernel works on a bitmap
-    const uint8_t *g8 = p.gone8 + (size_t)ut * p.n16;
+    // the grid rounds keep one byte (0 or 1) per token; this kernel works on a bitmap
+    const u4 *g8 = reinterpret_cast<const u4 *>(p.gone8 + (size_t)ut * p.n16);   // 16-byte aligned rows of n16 bytes
     for (int i = tid; i < dead_words; i += kMergeThreads) {
       uint32_t word = 0;
-      for (int j = 0; j < 32 && 32 * i + j < n; ++j) word |= (uint32_t)(g8[32 * i + j] != 0) << j;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const u4 q = 2 * i + h < p.n16 / 16 ? g8[2 * i + h] : u4{0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)                    // four 0/1 bytes -> four bits
+          word |= (((q[j] & 0x01010101u) * 0x01020408u) >> 24 & 0xFu) << (16 * h + 4 * j);
+      }
       w.dead[i] = word;
     }
   }
