@@ -38,6 +38,11 @@ namespace {
 // adds < 1e-6 and the fp32 accumulation of 128 exact products < 1e-5.
 constexpr float kUnitScale = 1024.f;
 constexpr float kGuard = 1.05e-3f;
+// shallow_gram uses the measured rounding error of the two vectors instead of that worst case:
+// |fp16 MFMA cosine - exact cosine| <= err_a (1 + err_b) + err_b + kGuardSlack, where the
+// slack covers the fp32 accumulation (< 1.6e-5 even with truncation) and fp16 subnormal
+// components should the matrix cores flush them (< 8e-6).
+constexpr float kGuardSlack = 3e-5f;
 
 constexpr int kPanelRows = 256;   // rows of G's column range held in registers per block
 constexpr int kChunkCols = 1024;  // tokens per chunk: one 128-byte line of each row of G
@@ -58,6 +63,8 @@ struct ShallowParams {
   // workspace
   _Float16 *Xh;            // [UT][n][128] unit vectors
   double *m64;             // [UT][n]
+  float *err;              // [UT][n] distance of the stored fp16 unit vector from the exact one (units of the norm)
+  unsigned *echunk;        // [UT][ceil(n/1024)] largest err of each 1024-token chunk (float bits)
   uint32_t *G;             // [UT][n][Wp]
   int *deg0, *slot, *alive, *alive2, *cand, *dying, *pick_vert, *rank, *rank_vert;   // [UT][n]
   uint16_t *nbr;           // [UT][n][kListCap] neighbour lists of the sparse rows
@@ -137,6 +144,8 @@ __global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
   constexpr int tpr = row_bytes / 16;
   __shared__ __attribute__((aligned(16))) char tile_in[kRows * lds_row];
   __shared__ __attribute__((aligned(16))) char tile_out[kRows * kLdsRow];
+  __shared__ float row_err[kRows];
+  __shared__ double row_inv[kRows];
   const int ut = blockIdx.y, t = ut / p.U;
   const int row0 = blockIdx.x * kRows;
   for (int i = threadIdx.x; i < kRows * tpr; i += 256) {
@@ -163,17 +172,46 @@ __global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
     const size_t idx = (size_t)ut * p.n + row0 + r;
     p.m64[idx] = m;
     p.mag[t][(size_t)(ut % p.U) * p.n + row0 + r] = (float)m;
-    const float inv = m > 0.0 ? (float)((double)kUnitScale / m) : 0.f;
-    for (int ch = 0; ch < tpr; ++ch) {
+    row_inv[r] = m > 0.0 ? (double)kUnitScale / m : 0.0;
+  } else if (threadIdx.x < kRows) {
+    row_inv[threadIdx.x] = 0.0;                      // rows past the end of the sequence
+  }
+  __syncthreads();
+  {
+    // four threads per row: fp16 unit vector (x 2^10) and its distance from the exact one
+    const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
+    constexpr int per = 16 / sizeof(T);
+    const double inv64 = row_inv[r];
+    const float inv = (float)inv64;
+    double e2 = 0.0;                                   // squared distance stored - exact, scaled units
+    for (int ch = part * (tpr / 4); ch < (part + 1) * (tpr / 4); ++ch) {
       const u4 v = *reinterpret_cast<const u4 *>(tile_in + r * lds_row + ch * 16);
       const T *e = reinterpret_cast<const T *>(&v);
 #pragma unroll
-      for (int i = 0; i < per; ++i)
-        reinterpret_cast<_Float16 *>(tile_out + r * kLdsRow)[ch * per + i] =
-            (_Float16)(Elem<DT>::to_float(e[i]) * inv);
+      for (int i = 0; i < per; ++i) {
+        const _Float16 hv = (_Float16)(Elem<DT>::to_float(e[i]) * inv);
+        reinterpret_cast<_Float16 *>(tile_out + r * kLdsRow)[ch * per + i] = hv;
+        const double d = (double)(float)hv - (double)Elem<DT>::to_float(e[i]) * inv64;
+        e2 += d * d;
+      }
+    }
+    e2 += __shfl_xor(e2, 1);
+    e2 += __shfl_xor(e2, 2);
+    if (part == 0 && row0 + r < p.n) {
+      // rounded up: the double-precision evaluation above is good to 1e-15, the cast to 6e-8
+      const float ev = (float)(sqrt(e2) / (double)kUnitScale) * (1.f + 1e-6f) + 1e-12f;
+      p.err[(size_t)ut * p.n + row0 + r] = ev;
+      row_err[r] = ev;
     }
   }
   __syncthreads();
+  if (threadIdx.x < kRows) {                         // one update of the chunk's maximum per block
+    float mx = row0 + (int)threadIdx.x < p.n ? row_err[threadIdx.x] : 0.f;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (threadIdx.x == 0)
+      atomicMax(p.echunk + (size_t)ut * ((p.n + kChunkCols - 1) / kChunkCols) + row0 / kChunkCols, __float_as_uint(mx));
+  }
   for (int i = threadIdx.x; i < kRows * 16; i += 256) {
     const int r = i / 16, ch = i % 16;
     if (row0 + r < p.n)
@@ -268,7 +306,6 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   const int Jfirst = (I * kPanelRows) / kChunkCols;
   if ((Jg + 1) * kItemChunks <= Jfirst) continue;
   const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
-  const float band = kGuard * kUnitScale * kUnitScale;
   const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
   const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
   const int arow0 = I * kPanelRows + 64 * wave;   // first of this wave's 64 rows of G
@@ -283,6 +320,12 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
 #pragma unroll
     for (int ks = 0; ks < M::kSteps; ++ks)
       af[cb][ks] = a < n ? M::load(Xh + (size_t)a * 256, ks, g) : M::zero();
+  }
+  float erow[2];                                   // rounding error of the stored vectors of this lane's two rows
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    const int a = arow0 + 32 * cb + c;
+    erow[cb] = a < n ? p.err[(size_t)ut * n + a] : 0.f;
   }
   f16v cinit;
 #pragma unroll
@@ -309,6 +352,11 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   const int col_begin = J * kChunkCols;
   const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
   const int ntiles = (col_end - col_begin + 31) / 32;
+  // guard band of this lane's two rows against the tokens of the chunk (scaled units)
+  const float ech = __uint_as_float(p.echunk[(size_t)ut * ((n + kChunkCols - 1) / kChunkCols) + J]);
+  const float band0 = (erow[0] * (1.f + ech) + ech + kGuardSlack) * (kUnitScale * kUnitScale);
+  const float band1 = (erow[1] * (1.f + ech) + ech + kGuardSlack) * (kUnitScale * kUnitScale);
+  const float band = fmaxf(band0, band1);
   // Stage s of the chunk = tokens col_begin + 64 s .. + 63, in buffer s & 1; tile x = half x & 1
   // of stage x >> 1.  Each wave fills 16 rows of a stage with four 1-KiB loads (4 rows x 16
   // pieces, lane = slot).  Rows past the end of the sequence exist (the array is padded) and
@@ -404,8 +452,8 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       uint32_t cm0 = 0, cm1 = 0;
 #pragma unroll
       for (int v = 15; v >= 0; --v) {
-        cm0 = __builtin_amdgcn_alignbit(cm0, __float_as_uint(fabsf(a0[v]) - band), 31);
-        cm1 = __builtin_amdgcn_alignbit(cm1, __float_as_uint(fabsf(a1[v]) - band), 31);
+        cm0 = __builtin_amdgcn_alignbit(cm0, __float_as_uint(fabsf(a0[v]) - band0), 31);
+        cm1 = __builtin_amdgcn_alignbit(cm1, __float_as_uint(fabsf(a1[v]) - band1), 31);
       }
       q0 &= ~cm0;
       q1 &= ~cm1;
@@ -1559,6 +1607,7 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.Wp = ((n + 127) / 128) * 4;   // whole 16-byte pieces: shallow_gram writes every word of a row
   p.Xh = cv.take<_Float16>((N + 512) * kHeadDim);   // shallow_gram stages up to 5 tiles past the last token
   p.m64 = cv.take<double>(N);
+  p.err = cv.take<float>(N);
   p.G = cv.take<uint32_t>(N * p.Wp);
   p.deg0 = cv.take<int>(N);
   p.alive = cv.take<int>(N);
@@ -1583,13 +1632,15 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.fix_cap = (unsigned)(32 * (size_t)n > 4096 ? 32 * (size_t)n : 4096);
   p.fix = cv.take<uint32_t>((size_t)UT * p.fix_cap);
   // everything that must start at zero sits together at the end:
-  // counters [UT][kCounters], ovf_count + 3 spare, fix_count [UT], ovf_cnt [UT]
-  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + 2 * (size_t)UT);
+  // counters [UT][kCounters], ovf_count + 3 spare, fix_count [UT], ovf_cnt [UT], echunk [UT][chunks]
+  const size_t nchunk = (size_t)((n + kChunkCols - 1) / kChunkCols);
+  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + 2 * (size_t)UT + (size_t)UT * nchunk);
   int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
   p.ovf_count = reinterpret_cast<unsigned *>(tail);
   p.fix_overflow = reinterpret_cast<unsigned *>(tail ? tail + 1 : nullptr);
   p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
   p.ovf_cnt = reinterpret_cast<unsigned *>(tail ? tail + 4 + UT : nullptr);
+  p.echunk = reinterpret_cast<unsigned *>(tail ? tail + 4 + 2 * (size_t)UT : nullptr);
   return cv.total();
 }
 
@@ -1678,7 +1729,7 @@ extern "C" spindle_status spindle_compress_shallow(
     adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
   }
   // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = (size_t)p.UT * kCounters + 4 + 2 * (size_t)p.UT;
+  const size_t nzero = (size_t)p.UT * kCounters + 4 + 2 * (size_t)p.UT + (size_t)p.UT * ((n + kChunkCols - 1) / kChunkCols);
   const size_t cwords = (size_t)U * max_codes * kHeadDim * dtype_bytes(p.dtype) / 4;
   hipLaunchKernelGGL(shallow_init, dim3(1024), dim3(256), 0, st, p, nzero, cwords, T);
 
