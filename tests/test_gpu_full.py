@@ -83,3 +83,36 @@ def test_config5_layer(oracle, budget):
         assert (g[f"n_codes_{t}"] == budget).all()
         assert g[f"ref_{t}"].min() >= 0 and g[f"ref_{t}"].max() < budget
     print("config5 codes found", [o["n_codes_uncapped"] for o in res], flush=True)
+
+
+def test_max_seq_len_codebook(oracle):
+    # the longest sequence the codebook path takes (token indices are 16 bits wide), with a
+    # ragged last tile: sampled rows of G and their degrees against the oracle, then the
+    # oracle's merge run on the library's G must give the library's codebook and references
+    n = 65535
+    L = wl.small_random(21, "f16", B=1, H=1, l=n, lw=1, cap=n, n_centroids=2000, noise_frac=0.1)
+    g = parity.gpu_shallow(L, tensors=("k",))
+    X = wl.to_f64(L.K[0, 0], L.dtype)
+    theta = float(np.float32(L.theta_k))
+    m = oracle.magnitudes(X)
+    rng = np.random.default_rng(1)
+    rows = [0, 1, 1023, 1024, 32767, 32768, 65472, n - 1] + rng.integers(0, n, size=24).tolist()
+    for a in rows:
+        row = oracle.adjacency_row(X, theta, int(a), m)
+        assert np.array_equal(g["adj_k"][0, 0, a], row), f"row {a} of G differs"
+        assert g["deg_k"][0, 0, a] == sum(bin(int(w)).count("1") for w in row)
+    picks, ref = oracle.merge(g["adj_k"][0, 0])
+    assert g["n_found_k"][0, 0] == len(picks) and g["n_codes_k"][0, 0] == len(picks)
+    assert np.array_equal(g["ref_k"][0, 0], ref), "code assignment differs from the oracle's merge of the same G"
+    assert np.array_equal(g["mag_k"][0, 0], m.astype(np.float32))
+    parity.check_codebook_vectors(g["C_k"][0, 0, :len(picks)], X[picks] / m[picks, None], L.dtype)
+    print("n = 65535:", len(picks), "codebook entries", flush=True)
+
+
+def test_long_ragged_deep(oracle):
+    # a context longer than what the selection kernel keeps in LDS, not a multiple of any tile
+    L = wl.small_random(22, "f16", B=1, H=2, l=100003, hn=4, lw=64, pool=7, budget=4096, cap=64, n_centroids=300)
+    rep = parity.check_deep_layer(oracle, L)
+    print("l = 100003 deep", rep, flush=True)
+    L2 = wl.small_random(23, "bf16", B=1, H=1, l=40001, hn=4, lw=16, pool=15, budget=40001 - 5, cap=64, n_centroids=100)
+    parity.check_deep_layer(oracle, L2)                 # nearly everything is kept
