@@ -1048,7 +1048,12 @@ __global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, i
   const int nalive = cnt[round & 1];
   if ((int)(blockIdx.x * blockDim.x / kSegW) >= nalive) return;      // block-uniform: no work for this block
   if (keys_in_lds) {
-    for (int i = threadIdx.x; i < p.n; i += blockDim.x) lds[i] = p.key[base + i];
+    if ((p.n & 3) == 0) {                             // rows of the key array are then 16-byte aligned
+      const u4 *src = reinterpret_cast<const u4 *>(p.key + base);
+      for (int i = threadIdx.x; i < p.n / 4; i += blockDim.x) reinterpret_cast<u4 *>(lds)[i] = src[i];
+    } else {
+      for (int i = threadIdx.x; i < p.n; i += blockDim.x) lds[i] = p.key[base + i];
+    }
     __syncthreads();
     w.key = lds;
   }
