@@ -52,6 +52,7 @@ constexpr int kGramThreads = 256;
 constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad (shallow_prep)
 constexpr int kStageBytes = kStageCols * 256;   // staged tokens: unpadded rows, 16-byte pieces swizzled
 
+constexpr int kSegCap = 512;      // edges a wave may record per chunk (64 rows x 1024 columns)
 constexpr int kCounters = 16;     // ints per ut
 enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4, C_ROUNDS = 5 };
 
@@ -75,6 +76,14 @@ struct ShallowParams {
   uint32_t *fix;           // [UT][fix_cap] deferred pairs, b << 16 | a
   unsigned *fix_count;     // [UT]
   unsigned *fix_overflow;  // [1] some list was full
+  // set bits of the computed part of G as (row << 16 | column), one segment per (problem, chunk,
+  // row panel, wave): segment ((ut * nJc + J) * nI + I) * 4 + w, kSegCap entries
+  uint32_t *edges;
+  unsigned *ecount;        // entries of each segment
+  uint32_t *fedges;        // [UT][fix_cap] pairs shallow_fixup found adjacent, row << 16 | column
+  unsigned *fecount;       // [UT]
+  unsigned *need_full;     // [1] an edge segment ran full or a row has more neighbours than a list holds:
+                           //     degrees and lists are then taken from the complete bitmap
   unsigned fix_cap;        // per ut
   uint32_t *ovf;           // [UT][n] tokens whose codebook entry was cut, per problem
   unsigned *ovf_cnt;       // [UT] their number
@@ -291,7 +300,10 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
   // blocks are dealt round-robin to the 8 XCDs: give each XCD one (ut, chunk) at a time
   // and let it sweep the row panels, so the chunk is re-read from that XCD's L2
-  if (kExact && *p.fix_overflow == 0) return;
+  if (kExact) {
+    if (*p.fix_overflow == 0) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(p.need_full, 1u);   // bits set here leave no edge records
+  }
   const int nitems = 8 * nI * ((p.UT * nJ + 7) / 8);
   for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
   const int xcd = item & 7, s_ = item >> 3;
@@ -545,12 +557,39 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   }
   if (!kExact) {
     const int npieces = (ntiles + 3) / 4, piece = lane & 7;
-#pragma unroll
+    // the set bits also go out as (row, column) records, a segment per wave and chunk: sparse
+    // graphs get their neighbour lists from these without another pass over G
+    const int nJc = (n + kChunkCols - 1) / kChunkCols;
+    const size_t seg = (((size_t)ut * nJc + J) * nI + I) * 4 + wave;
+    uint32_t *eseg = p.edges + seg * kSegCap;
+    int ecnt = 0;                                    // wave-uniform
+    const unsigned long long below = (1ull << lane) - 1ull;
     for (int it = 0; it < 8; ++it) {
       const int r = it * 8 + (lane >> 3);
-      const u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][r][piece * 4]);
-      if (arow0 + r < n && piece < npieces)
+      u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][r][piece * 4]);
+      const bool live = arow0 + r < n && piece < npieces;
+      if (live)
         *reinterpret_cast<u4 *>(p.G + ((size_t)ut * n + arow0 + r) * p.Wp + (col_begin >> 5) + piece * 4) = v;
+      if (!live) v = u4{0, 0, 0, 0};
+      // every pass takes one bit of each lane that still has some
+      for (;;) {
+        const bool has = (v[0] | v[1] | v[2] | v[3]) != 0;
+        const unsigned long long mk = __ballot(has);
+        if (mk == 0) break;
+        if (has) {
+          const int j = v[0] ? 0 : v[1] ? 1 : v[2] ? 2 : 3;
+          const uint32_t w = v[j];
+          const int t = __builtin_ctz(w);
+          v[j] = w & (w - 1);
+          const int at = ecnt + __popcll(mk & below);
+          if (at < kSegCap) eseg[at] = ((uint32_t)(arow0 + r) << 16) | (uint32_t)(col_begin + piece * 128 + j * 32 + t);
+        }
+        ecnt += __popcll(mk);
+      }
+    }
+    if (lane == 0) {
+      p.ecount[seg] = (unsigned)(ecnt < kSegCap ? ecnt : kSegCap);
+      if (ecnt > kSegCap) atomicOr(p.need_full, 1u);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);              // loads issued for stages past the chunk
@@ -596,8 +635,9 @@ __device__ __forceinline__ uint32_t transpose_stage(uint32_t x, int st, uint32_t
   return r;
 }
 
-__global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p) {
+__global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p, int force) {
   extern __shared__ __attribute__((aligned(16))) uint32_t mtile[];   // [1024][kMirrorPitch]
+  if (!force && *p.need_full == 0) return;         // sparse graph: the lists came from the edge records
   const int n = p.n, Wp = p.Wp;
   const int T = (n + 1023) >> 10, npairs = T * (T - 1) / 2;
   // blocks b and b + 8 are the two halves of one tile
@@ -690,8 +730,17 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
   for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
     const uint32_t e = list[i];
     const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
-    if (cos64(p, ut, a, b) > theta)
-      atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+    const bool adj = cos64(p, ut, a, b) > theta;
+    if (adj) atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+    // ... and as a record for the neighbour lists (one counter update per wave)
+    const unsigned long long mk = __ballot(adj);
+    if (mk) {
+      const int lane = lane_id();
+      unsigned at = 0;
+      if (lane == __builtin_ctzll(mk)) at = atomicAdd(p.fecount + ut, (unsigned)__popcll(mk));
+      at = __shfl(at, __builtin_ctzll(mk));
+      if (adj) p.fedges[(size_t)ut * p.fix_cap + at + __popcll(mk & ((1ull << lane) - 1ull))] = e;
+    }
   }
 }
 
@@ -701,7 +750,8 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
 // bytes per token instead of the whole bitmap row.  Denser rows keep using the bitmap.
 constexpr int kListCap = 256;
 
-__global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
+__global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force) {
+  if (!force && *p.need_full == 0) return;         // sparse graph: done by shallow_edge_lists
   const int ut = blockIdx.y, n = p.n, Wp = p.Wp;
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int row0 = (blockIdx.x * 4 + wave) * 4;
@@ -750,6 +800,79 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p) {
         }
       }
     }
+  }
+}
+
+// ---------------------------------------------------------------- lists from edge records
+// Sparse graphs: degrees (Eq. 10) and neighbour lists straight from the records of set bits
+// shallow_gram and shallow_fixup left, without reading G.  One block per panel of 256 rows.
+// A record (a, b) of the panel's own segments puts b on the list of a.  G is symmetric and
+// only computed from each row's own 1024-token tile on, so a record (a', b) of an earlier
+// panel with b in a later tile also puts a' on the list of b: the block scans the segments
+// of all earlier tiles' panels for its own tile and keeps the records that end in its rows
+// (inside a tile both orientations were computed and recorded).  Fill counts live in LDS;
+// the order of a list is whatever the LDS atomics make it, which no consumer depends on.
+// A row with more than kListCap neighbours, or a segment that ran full, raises need_full:
+// shallow_mirror and shallow_lists then redo everything from the bitmap.
+constexpr int kEdgeThreads = 1024;
+
+__global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams p, int force) {
+  __shared__ int cursor[kPanelRows];
+  if (force || *p.need_full != 0) return;
+  const int n = p.n, I = blockIdx.x, ut = blockIdx.y;
+  const int nI = (n + kPanelRows - 1) / kPanelRows, nJc = (n + kChunkCols - 1) / kChunkCols;
+  const int row0 = I * kPanelRows, Jm = row0 / kChunkCols;
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+  uint16_t *lists = p.nbr + ((size_t)ut * n + row0) * kListCap;
+  if (tid < kPanelRows) cursor[tid] = 0;
+  __syncthreads();
+  auto add = [&](int row, int other) {
+    const int r = row - row0;
+    const int pos = atomicAdd(&cursor[r], 1);
+    if (pos < kListCap) lists[(size_t)r * kListCap + pos] = (uint16_t)other;
+  };
+  const int nown = 4 * (nJc - Jm);                   // (chunk, wave) segments of this panel
+  const int nin = 16 * Jm;                           // (panel, wave) segments of earlier tiles for this tile
+  for (int k = wave; k < nown + nin; k += kEdgeThreads / 64) {
+    const bool own = k < nown;
+    const int kk = own ? k : k - nown;
+    const int J = own ? Jm + (kk >> 2) : Jm;
+    const int Ip = own ? I : kk >> 2;
+    const size_t seg = (((size_t)ut * nJc + J) * nI + Ip) * 4 + (kk & 3);
+    const unsigned cn = p.ecount[seg];
+    const int cnt = cn < (unsigned)kSegCap ? (int)cn : kSegCap;
+    const uint32_t *e = p.edges + seg * kSegCap;
+    for (int i = lane; i < cnt; i += kWave) {
+      const uint32_t rec = e[i];
+      const int a = (int)(rec >> 16), b = (int)(rec & 0xFFFFu);
+      if (own) add(a, b);
+      else if (b >= row0 && b < row0 + kPanelRows) add(b, a);
+    }
+  }
+  {
+    // pairs decided in double precision: (row, column) records of the whole problem
+    const unsigned fn = p.fecount[ut];
+    const int fc = (int)(fn < p.fix_cap ? fn : p.fix_cap);
+    const uint32_t *fe = p.fedges + (size_t)ut * p.fix_cap;
+    for (int i = tid; i < fc; i += kEdgeThreads) {
+      const uint32_t rec = fe[i];
+      const int a = (int)(rec >> 16), b = (int)(rec & 0xFFFFu);
+      if (a >= row0 && a < row0 + kPanelRows) add(a, b);
+      if ((a >> 10) != (b >> 10) && b >= row0 && b < row0 + kPanelRows) add(b, a);   // other tile: recorded once
+    }
+  }
+  __syncthreads();
+  if (tid < kPanelRows && row0 + tid < n) {
+    const int v = row0 + tid, deg = cursor[tid];
+    const size_t i = (size_t)ut * n + v;
+    p.deg0[i] = deg;
+    p.key[i] = ((uint32_t)deg << 16) | (uint32_t)(0xFFFF - v);
+    p.alive[i] = v;
+    p.slot[i] = -1;
+    p.gone8[(size_t)ut * p.n16 + v] = 0;
+    if (v == 0) p.counters[(size_t)ut * kCounters + C_ALIVE0] = n;
+    if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = deg;
+    if (deg > kListCap) atomicOr(p.need_full, 1u);
   }
 }
 
@@ -1636,16 +1759,25 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.ccand = cv.take<uint2>(N * 2 * kCandCap);
   p.fix_cap = (unsigned)(32 * (size_t)n > 4096 ? 32 * (size_t)n : 4096);
   p.fix = cv.take<uint32_t>((size_t)UT * p.fix_cap);
+  p.fedges = cv.take<uint32_t>((size_t)UT * p.fix_cap);
+  {
+    const size_t nI = (size_t)((n + kPanelRows - 1) / kPanelRows), nJc = (size_t)((n + kChunkCols - 1) / kChunkCols);
+    p.edges = cv.take<uint32_t>((size_t)UT * nJc * nI * 4 * kSegCap);
+    p.ecount = cv.take<unsigned>((size_t)UT * nJc * nI * 4);
+  }
   // everything that must start at zero sits together at the end:
-  // counters [UT][kCounters], ovf_count + 3 spare, fix_count [UT], ovf_cnt [UT], echunk [UT][chunks]
+  // counters [UT][kCounters], ovf_count, fix_overflow, need_full + 1 spare, fix_count [UT], ovf_cnt [UT],
+  // fecount [UT], echunk [UT][chunks]
   const size_t nchunk = (size_t)((n + kChunkCols - 1) / kChunkCols);
-  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + 2 * (size_t)UT + (size_t)UT * nchunk);
+  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + 3 * (size_t)UT + (size_t)UT * nchunk);
   int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
   p.ovf_count = reinterpret_cast<unsigned *>(tail);
   p.fix_overflow = reinterpret_cast<unsigned *>(tail ? tail + 1 : nullptr);
   p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
   p.ovf_cnt = reinterpret_cast<unsigned *>(tail ? tail + 4 + UT : nullptr);
-  p.echunk = reinterpret_cast<unsigned *>(tail ? tail + 4 + 2 * (size_t)UT : nullptr);
+  p.fecount = reinterpret_cast<unsigned *>(tail ? tail + 4 + 2 * (size_t)UT : nullptr);
+  p.echunk = reinterpret_cast<unsigned *>(tail ? tail + 4 + 3 * (size_t)UT : nullptr);
+  p.need_full = reinterpret_cast<unsigned *>(tail ? tail + 2 : nullptr);
   return cv.total();
 }
 
@@ -1734,7 +1866,7 @@ extern "C" spindle_status spindle_compress_shallow(
     adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
   }
   // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = (size_t)p.UT * kCounters + 4 + 2 * (size_t)p.UT + (size_t)p.UT * ((n + kChunkCols - 1) / kChunkCols);
+  const size_t nzero = (size_t)p.UT * kCounters + 4 + 3 * (size_t)p.UT + (size_t)p.UT * ((n + kChunkCols - 1) / kChunkCols);
   const size_t cwords = (size_t)U * max_codes * kHeadDim * dtype_bytes(p.dtype) / 4;
   hipLaunchKernelGGL(shallow_init, dim3(1024), dim3(256), 0, st, p, nzero, cwords, T);
 
@@ -1754,18 +1886,22 @@ extern "C" spindle_status spindle_compress_shallow(
   { ProfScope ps("shallow_fixup", st);
   hipLaunchKernelGGL(shallow_fixup, dim3(128, p.UT), dim3(256), 0, st, p); }
   {
+    // sparse graphs: lists from the edge records; otherwise (or when the caller wants the
+    // adjacency matrix) the lower triangle is written and the lists come from the bitmap
+    const int force = adj[0] || adj[1];
+    { ProfScope ps("shallow_edge_lists", st);
+    hipLaunchKernelGGL(shallow_edge_lists, dim3((n + kPanelRows - 1) / kPanelRows, p.UT), dim3(kEdgeThreads), 0, st, p, force); }
     const int T1k = (n + 1023) / 1024, npairs = T1k * (T1k - 1) / 2;
     if (npairs > 0) {
       SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_mirror),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMirrorLds));
       ProfScope ps("shallow_mirror", st);
-      hipLaunchKernelGGL(shallow_mirror, dim3(16 * ((p.UT * npairs + 7) / 8)), dim3(kMirrorThreads), kMirrorLds, st, p);
+      hipLaunchKernelGGL(shallow_mirror, dim3(16 * ((p.UT * npairs + 7) / 8)), dim3(kMirrorThreads), kMirrorLds, st, p, force);
     }
+    SPINDLE_HIP(hipGetLastError());
+    { ProfScope ps("shallow_lists", st);
+    hipLaunchKernelGGL(shallow_lists, dim3((n + 15) / 16, p.UT), dim3(256), 0, st, p, force); }
   }
-  SPINDLE_HIP(hipGetLastError());
-
-  { ProfScope ps("shallow_lists", st);
-  hipLaunchKernelGGL(shallow_lists, dim3((n + 15) / 16, p.UT), dim3(256), 0, st, p); }
   {
     int gx = (n + 4 * (kPhaseThreads / kSegW) - 1) / (4 * (kPhaseThreads / kSegW));
     if (gx > 256) gx = 256;

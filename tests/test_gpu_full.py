@@ -107,6 +107,12 @@ def test_max_seq_len_codebook(oracle):
     assert np.array_equal(g["mag_k"][0, 0], m.astype(np.float32))
     parity.check_codebook_vectors(g["C_k"][0, 0, :len(picks)], X[picks] / m[picks, None], L.dtype)
     print("n = 65535:", len(picks), "codebook entries", flush=True)
+    # without the adjacency output the lists come from the edge records instead of the bitmap:
+    # same references and codebook as the run checked above
+    g2 = parity.gpu_shallow(L, debug=False, tensors=("k",))
+    assert g2["n_codes_k"][0, 0] == len(picks)
+    assert np.array_equal(g2["ref_k"][0, 0], ref)
+    assert np.array_equal(g2["C_k"][0, 0], g["C_k"][0, 0])
 
 
 def test_long_ragged_deep(oracle):
