@@ -805,22 +805,26 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force)
 
 // ---------------------------------------------------------------- lists from edge records
 // Sparse graphs: degrees (Eq. 10) and neighbour lists straight from the records of set bits
-// shallow_gram and shallow_fixup left, without reading G.  One block per panel of 256 rows.
+// shallow_gram and shallow_fixup left, without reading G.  One block per panel of 256 rows;
+// the first 128 entries of every list are collected in LDS and written out in whole pieces.
 // A record (a, b) of the panel's own segments puts b on the list of a.  G is symmetric and
 // only computed from each row's own 1024-token tile on, so a record (a', b) of an earlier
 // panel with b in a later tile also puts a' on the list of b: the block scans the segments
-// of all earlier tiles' panels for its own tile and keeps the records that end in its rows
+// of all earlier tiles' panels for its own chunk and keeps the records that end in its rows
 // (inside a tile both orientations were computed and recorded).  Fill counts live in LDS;
 // the order of a list is whatever the LDS atomics make it, which no consumer depends on.
 // A row with more than kListCap neighbours, or a segment that ran full, raises need_full:
 // shallow_mirror and shallow_lists then redo everything from the bitmap.
 constexpr int kEdgeThreads = 1024;
+constexpr int kEdgeLds = 128;                      // list entries per row collected in LDS; later ones go straight to memory
 
 __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams p, int force) {
   __shared__ int cursor[kPanelRows];
+  __shared__ __attribute__((aligned(16))) uint16_t part[kPanelRows][kEdgeLds];
   if (force || *p.need_full != 0) return;
-  const int n = p.n, I = blockIdx.x, ut = blockIdx.y;
+  const int n = p.n, ut = blockIdx.y;
   const int nI = (n + kPanelRows - 1) / kPanelRows, nJc = (n + kChunkCols - 1) / kChunkCols;
+  const int I = nI - 1 - (int)blockIdx.x;            // panels with more segments to scan first
   const int row0 = I * kPanelRows, Jm = row0 / kChunkCols;
   const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
   uint16_t *lists = p.nbr + ((size_t)ut * n + row0) * kListCap;
@@ -829,24 +833,41 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
   auto add = [&](int row, int other) {
     const int r = row - row0;
     const int pos = atomicAdd(&cursor[r], 1);
-    if (pos < kListCap) lists[(size_t)r * kListCap + pos] = (uint16_t)other;
+    if (pos < kEdgeLds) part[r][pos] = (uint16_t)other;
+    else if (pos < kListCap) lists[(size_t)r * kListCap + pos] = (uint16_t)other;
   };
   const int nown = 4 * (nJc - Jm);                   // (chunk, wave) segments of this panel
-  const int nin = 16 * Jm;                           // (panel, wave) segments of earlier tiles for this tile
-  for (int k = wave; k < nown + nin; k += kEdgeThreads / 64) {
-    const bool own = k < nown;
-    const int kk = own ? k : k - nown;
-    const int J = own ? Jm + (kk >> 2) : Jm;
-    const int Ip = own ? I : kk >> 2;
-    const size_t seg = (((size_t)ut * nJc + J) * nI + Ip) * 4 + (kk & 3);
-    const unsigned cn = p.ecount[seg];
-    const int cnt = cn < (unsigned)kSegCap ? (int)cn : kSegCap;
-    const uint32_t *e = p.edges + seg * kSegCap;
-    for (int i = lane; i < cnt; i += kWave) {
-      const uint32_t rec = e[i];
-      const int a = (int)(rec >> 16), b = (int)(rec & 0xFFFFu);
-      if (own) add(a, b);
-      else if (b >= row0 && b < row0 + kPanelRows) add(b, a);
+  const int nin = 16 * Jm;                           // (panel, wave) segments of earlier tiles for this tile's chunk
+  constexpr int kBatch = 4;                          // segments a wave has in flight
+  for (int k0 = wave * kBatch; k0 < nown + nin; k0 += (kEdgeThreads / 64) * kBatch) {
+    const uint32_t *e[kBatch];
+    int cnt[kBatch];
+    bool own[kBatch];
+    int most = 0;
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int k = k0 + u;
+      own[u] = k < nown;
+      const int kk = own[u] ? k : k - nown;
+      const int J = own[u] ? Jm + (kk >> 2) : Jm;
+      const int Ip = own[u] ? I : kk >> 2;
+      const size_t seg = (((size_t)ut * nJc + J) * nI + Ip) * 4 + (kk & 3);
+      const unsigned cn = k < nown + nin ? p.ecount[seg] : 0u;
+      cnt[u] = cn < (unsigned)kSegCap ? (int)cn : kSegCap;
+      e[u] = p.edges + seg * kSegCap;
+      most = cnt[u] > most ? cnt[u] : most;
+    }
+    for (int i0 = 0; i0 < most; i0 += kWave) {
+      uint32_t rec[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) rec[u] = i0 + lane < cnt[u] ? e[u][i0 + lane] : 0xFFFFFFFFu;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        if (i0 + lane < cnt[u]) {
+          const int a = (int)(rec[u] >> 16), b = (int)(rec[u] & 0xFFFFu);
+          if (own[u]) add(a, b);
+          else if (b >= row0 && b < row0 + kPanelRows) add(b, a);
+        }
     }
   }
   {
@@ -862,6 +883,13 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
     }
   }
   __syncthreads();
+  // the collected part of each list goes out in 16-byte pieces
+  for (int k = tid; k < kPanelRows * (kEdgeLds / 8); k += kEdgeThreads) {
+    const int r = k / (kEdgeLds / 8), piece = k % (kEdgeLds / 8);
+    const int have = cursor[r] < kEdgeLds ? cursor[r] : kEdgeLds;
+    if (row0 + r < n && piece * 8 < have)
+      *reinterpret_cast<u4 *>(lists + (size_t)r * kListCap + piece * 8) = *reinterpret_cast<const u4 *>(&part[r][piece * 8]);
+  }
   if (tid < kPanelRows && row0 + tid < n) {
     const int v = row0 + tid, deg = cursor[tid];
     const size_t i = (size_t)ut * n + v;
