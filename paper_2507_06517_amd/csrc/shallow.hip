@@ -8,9 +8,11 @@
 //                   into the adjacency matrix G (Eq. 4, 9), upper triangle only; pairs whose
 //                   fp16 similarity lies within kGuard of theta are deferred to shallow_fixup
 //                   (shallow_gram<true>: in-place fallback when a pair list overflows)
-//   shallow_fixup   exact double-precision decision for the deferred pairs
-//   shallow_mirror  lower triangle of G by bit transposition
-//   shallow_lists   degrees (Eq. 10) and compact neighbour lists of the sparse rows of G
+//   shallow_fixup   exact double-precision decision for the deferred pairs;
+//                   every set bit is also left as a (row, column) record
+//   shallow_edge_lists  degrees (Eq. 10) and neighbour lists from those records
+//   shallow_mirror  lower triangle of G by bit transposition     } only when the caller wants G,
+//   shallow_lists   degrees and neighbour lists from the rows of G } or the records do not suffice
 //   merge_onehop, merge_twohop, merge_update, merge_reset
 //                   the first rounds of the greedy highest-degree codebook construction
 //                   (Eq. 11-13) in its exact parallel form, one launch per phase
