@@ -48,6 +48,35 @@ def cpu_baseline(L, wl, sample_n=12288):
                       f"1 of {2 * units} K/V units ({t_sh_sample:.2f} s), scaled by units and by (l/{sample_n})^2"}
 
 
+def time_reconstruct(torch, sb, L, shallow, reps=20):
+    """Eq. 14 on the step's own output (K and V of every unit), outside the timed step: a gather and
+    scale bound by HBM.  Algorithmic bytes per token: one row written, index and magnitude read;
+    the codebook (cap rows per unit) is read once."""
+    o = shallow.out
+    units = L.batch * L.n_kv_heads
+    outs = {t: torch.empty((L.batch, L.n_kv_heads, L.seq_len, L.head_dim), dtype=o["C_k"].dtype,
+                           device=o["C_k"].device) for t in ("k", "v")}
+
+    def once():
+        for t in ("k", "v"):
+            sb.spindle_reconstruct(units, L.seq_len, L.head_dim, sb._DT[L.dtype], L.max_codes,
+                                   o[f"C_{t}"], o[f"ref_{t}"], o[f"mag_{t}"], outs[t])
+    once()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        once()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    esz = outs["k"].element_size()
+    nbytes = 2 * units * (L.seq_len * (L.head_dim * esz + 8) + L.max_codes * L.head_dim * esz)
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"ms_k_and_v": ms, "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": gbs / PEAK_HBM_GBS, "tokens_per_s": L.batch * L.seq_len / (ms * 1e-3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,6 +192,13 @@ def main():
     deep_bytes = units * (L.seq_len * L.head_dim * 2 + 2 * 2 * L.budget * L.head_dim * 2 + 3 * 4 * L.seq_len)
     out["deep_roofline"] = {"bound": "hbm", "achieved": deep_bytes / (ms_deep * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": deep_bytes / (ms_deep * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    out["reconstruct"] = time_reconstruct(torch, sb, L, shallow)
+    # Eq. 15 on this layer: eviction alone (r1) and replacement alone (r2 r3), each on the full layer
+    stored = int(shallow.out["n_codes_k"].sum().item() + shallow.out["n_codes_v"].sum().item())
+    bits = 8 * torch.empty(0, dtype=sb.torch_dtype(L.dtype)).element_size()
+    r1 = sb.spindle_reserve_ratio(2 * units * min(L.budget, L.seq_len), 2 * units * L.seq_len, 1, L.head_dim, 16, bits)[0]
+    _, r2, r3, r23 = sb.spindle_reserve_ratio(2 * units * L.seq_len, 2 * units * L.seq_len, stored, L.head_dim, 16, bits)
+    out["reserve_ratio"] = {"eviction_r1": r1, "replacement_r2": r2, "r3": r3, "replacement_r2_r3": r23}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, wl)
     print(json.dumps(out), flush=True)

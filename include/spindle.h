@@ -177,6 +177,40 @@ spindle_status spindle_reconstruct(int32_t units, int32_t seq_len, int32_t head_
                                    const float *mag, void *out, void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Host helpers (plain arithmetic on the host, no GPU work)                    */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Sec. "Attention Weight Based Token Eviction", Eq. 5-6 and the unnumbered equation before
+ * them: layer-wise budgets.  With l_c = seq_len - window and r_c = (reserve_ratio * seq_len -
+ * window) / l_c (clamped to [0, 1]), alpha = (1 + beta) / 2:
+ *   r_c <= beta          every layer gets r_c,
+ *   beta < r_c <= alpha  layer 0 gets 2 r_c - beta, the last layer beta,
+ *   alpha < r_c          layer 0 gets 1, the last layer 2 r_c - 1
+ * (the printed "0.05" is beta and the printed "1 - 2 r_c" is read as 2 r_c - 1, which keeps the
+ * mean at r_c and is continuous at alpha); layers in between are interpolated linearly (Eq. 6).
+ *   budgets  HOST buffer of n_layers int32: window + floor(r_c(layer) * l_c + 0.5), the
+ *            `budget` argument of spindle_compress_deep (it counts the window).
+ *   ratios   optional HOST buffer of n_layers doubles: r_c(layer).
+ * Errors: INVALID_ARG for n_layers < 1, window < 1, window > seq_len, beta outside [0, 1],
+ * reserve_ratio outside [0, 1] or a null `budgets`.
+ */
+spindle_status spindle_layer_budgets(double reserve_ratio, int32_t seq_len, int32_t window,
+                                     int32_t n_layers, double beta, int32_t *budgets, double *ratios);
+
+/*
+ * Sec. "Experiments", Eq. 15: reserve ratio of one layer, r = r1 * r2 * r3 with
+ *   r1 = kept_tokens / total_tokens           (eviction; token counts summed over heads, K and V)
+ *   r2 = codebook_entries / kept_tokens       (replacement; entries of the K and V codebooks)
+ *   r3 = (head_dim + index_bits / elem_bits + 1) / head_dim   (one index and one magnitude per
+ *        token, in units of cache elements; the printed fraction is garbled and read this way).
+ * `out` is a HOST buffer of 4 doubles: r1, r2, r3, r.  Errors: INVALID_ARG for counts < 1,
+ * kept_tokens > total_tokens, codebook_entries > kept_tokens or a null `out`.
+ */
+spindle_status spindle_reserve_ratio(int64_t kept_tokens, int64_t total_tokens, int64_t codebook_entries,
+                                     int32_t head_dim, int32_t index_bits, int32_t elem_bits, double *out);
+
+/* ------------------------------------------------------------------------- */
 /* Per-kernel timing (measurement aid for the roofline figures)                */
 /* ------------------------------------------------------------------------- */
 

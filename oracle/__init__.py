@@ -70,6 +70,8 @@ def lib():
         L.oracle_reconstruct.restype = None
         L.oracle_layer_ratios.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int, C.c_double, _f64p]
         L.oracle_layer_ratios.restype = None
+        L.oracle_reserve_ratio.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int, C.c_int, C.c_int, _f64p]
+        L.oracle_reserve_ratio.restype = None
         _lib = L
     return _lib
 
@@ -225,4 +227,10 @@ def reconstruct(Cb, ref, mag):
 def layer_ratios(r, l, lw, m, beta=0.05):
     out = np.empty(m, dtype=np.float64)
     lib().oracle_layer_ratios(float(r), int(l), int(lw), int(m), float(beta), out)
+    return out
+
+
+def reserve_ratio(kept, total, entries, dh=128, int_bit=16, key_bit=16):
+    out = np.empty(4, dtype=np.float64)
+    lib().oracle_reserve_ratio(float(kept), float(total), float(entries), int(dh), int(int_bit), int(key_bit), out)
     return out

@@ -391,3 +391,18 @@ void oracle_layer_ratios(double r, int l, int lw, int m, double beta, double *rc
     for (int lam = 0; lam < m; ++lam)
         rc_out[lam] = m > 1 ? r0 + (r1 - r0) / (double)(m - 1) * lam : rc;
 }
+
+/*
+ * Sec. "Experiments", Eq. 15: reserve ratio of one layer.  r1 = share of the tokens kept by
+ * eviction, r2 = codebook entries per kept token, r3 = storage of a replaced token relative
+ * to its d_h elements (one index of int_bit bits and one magnitude of one element on top;
+ * the printed fraction is garbled and read as (d_h + int_bit / key_bit + 1) / d_h).
+ * out = {r1, r2, r3, r1 r2 r3}.
+ */
+void oracle_reserve_ratio(double kept, double total, double entries, int dh, int int_bit, int key_bit, double *out)
+{
+    out[0] = kept / total;
+    out[1] = entries / kept;
+    out[2] = (dh + (double)int_bit / key_bit + 1.0) / dh;
+    out[3] = out[0] * out[1] * out[2];
+}

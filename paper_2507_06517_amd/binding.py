@@ -24,7 +24,8 @@ NORM_PAPER, NORM_NONE = 0, 1
 _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
-           "spindle_compress_shallow", "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile", "spindle_profile_read",
+           "spindle_compress_shallow", "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
+           "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_profile_read",
            "spindle_last_error", "spindle_version"]
 
 
@@ -60,7 +61,10 @@ def lib():
         L.spindle_profile_read.argtypes = [C.c_char_p, C.POINTER(C.c_float), i32]
         L.spindle_profile_read.restype = C.c_int32
         L.spindle_shallow_stats.argtypes = [C.POINTER(KvDesc), i32, vp, vp, C.POINTER(C.c_int32)]
-        for name in EXPORTS[:7]:
+        L.spindle_layer_budgets.argtypes = [C.c_double, i32, i32, i32, C.c_double, C.POINTER(C.c_int32),
+                                            C.POINTER(C.c_double)]
+        L.spindle_reserve_ratio.argtypes = [C.c_int64, C.c_int64, C.c_int64, i32, i32, i32, C.POINTER(C.c_double)]
+        for name in EXPORTS[:9]:
             getattr(L, name).restype = C.c_int
         L.spindle_last_error.restype = C.c_char_p
         L.spindle_version.restype = C.c_uint32
@@ -152,6 +156,23 @@ def spindle_shallow_stats(desc, n_tensors, workspace, stream=None):
 def spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, Cb, ref, mag, out, stream=None):
     _check(lib().spindle_reconstruct(units, seq_len, head_dim, dtype, max_codes, _ptr(Cb), _ptr(ref),
                                      _ptr(mag), _ptr(out), stream if stream is not None else _stream()))
+
+
+def spindle_layer_budgets(reserve_ratio, seq_len, window, n_layers, beta=0.05):
+    """Returns (budgets int32 [n_layers], ratios float64 [n_layers])."""
+    budgets = (C.c_int32 * n_layers)()
+    ratios = (C.c_double * n_layers)()
+    _check(lib().spindle_layer_budgets(float(reserve_ratio), int(seq_len), int(window), int(n_layers), float(beta),
+                                       budgets, ratios))
+    return np.array(budgets[:], dtype=np.int32), np.array(ratios[:], dtype=np.float64)
+
+
+def spindle_reserve_ratio(kept_tokens, total_tokens, codebook_entries, head_dim=128, index_bits=16, elem_bits=16):
+    """Returns (r1, r2, r3, r) of one layer."""
+    out = (C.c_double * 4)()
+    _check(lib().spindle_reserve_ratio(int(kept_tokens), int(total_tokens), int(codebook_entries), int(head_dim),
+                                       int(index_bits), int(elem_bits), out))
+    return tuple(out[:])
 
 
 def spindle_profile(enable: bool) -> None:

@@ -91,6 +91,52 @@ extern "C" int32_t spindle_profile_read(char *names, float *ms, int32_t max) {
   return n;
 }
 
+// Layer-wise budgets, Eq. 5-6 (Sec. "Attention Weight Based Token Eviction").
+extern "C" spindle_status spindle_layer_budgets(double reserve_ratio, int32_t seq_len, int32_t window,
+                                                int32_t n_layers, double beta, int32_t *budgets, double *ratios) {
+  if (!budgets) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "budgets is NULL");
+  if (n_layers < 1 || window < 1 || window > seq_len)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "need n_layers >= 1 and 1 <= window <= seq_len");
+  if (!(beta >= 0.0 && beta <= 1.0) || !(reserve_ratio >= 0.0 && reserve_ratio <= 1.0))
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "beta and reserve_ratio must lie in [0, 1]");
+  const int context = seq_len - window;
+  double mean = context > 0 ? (reserve_ratio * seq_len - window) / context : 0.0;
+  mean = mean < 0.0 ? 0.0 : (mean > 1.0 ? 1.0 : mean);
+  const double knee = 0.5 * (1.0 + beta);
+  double first = mean, last = mean;                       // at or below the floor: flat
+  if (mean > knee) {
+    first = 1.0;
+    last = 2.0 * mean - 1.0;
+  } else if (mean > beta) {
+    first = 2.0 * mean - beta;
+    last = beta;
+  }
+  for (int layer = 0; layer < n_layers; ++layer) {
+    const double t = n_layers > 1 ? (double)layer / (double)(n_layers - 1) : 0.0;
+    const double share = n_layers > 1 ? first + (last - first) * t : mean;
+    if (ratios) ratios[layer] = share;
+    long kept = (long)(share * context + 0.5);
+    kept = kept < 0 ? 0 : (kept > context ? context : kept);
+    budgets[layer] = window + (int32_t)kept;
+  }
+  return SPINDLE_OK;
+}
+
+// Reserve ratio of a layer, Eq. 15 (Sec. "Experiments").
+extern "C" spindle_status spindle_reserve_ratio(int64_t kept_tokens, int64_t total_tokens, int64_t codebook_entries,
+                                                int32_t head_dim, int32_t index_bits, int32_t elem_bits, double *out) {
+  if (!out) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "out is NULL");
+  if (kept_tokens < 1 || total_tokens < 1 || codebook_entries < 1 || head_dim < 1 || index_bits < 1 || elem_bits < 1)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "counts and widths must be >= 1");
+  if (kept_tokens > total_tokens || codebook_entries > kept_tokens)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "need codebook_entries <= kept_tokens <= total_tokens");
+  out[0] = (double)kept_tokens / (double)total_tokens;
+  out[1] = (double)codebook_entries / (double)kept_tokens;
+  out[2] = ((double)head_dim + (double)index_bits / (double)elem_bits + 1.0) / (double)head_dim;
+  out[3] = out[0] * out[1] * out[2];
+  return SPINDLE_OK;
+}
+
 extern "C" const char *spindle_last_error(void) { return spindle::g_error; }
 
 extern "C" uint32_t spindle_version(void) { return (0u << 16) | 1u; }

@@ -122,3 +122,26 @@ def test_long_ragged_deep(oracle):
     print("l = 100003 deep", rep, flush=True)
     L2 = wl.small_random(23, "bf16", B=1, H=1, l=40001, hn=4, lw=16, pool=15, budget=40001 - 5, cap=64, n_centroids=100)
     parity.check_deep_layer(oracle, L2)                 # nearly everything is kept
+
+
+def test_eviction_then_codebook_on_the_kept_tokens(oracle):
+    # composed use: the codebook is built over what the eviction kept (window included).  The
+    # oracle selects rows with its own kept indices; the library works on its own gathered rows.
+    L = wl.config2(0)
+    p64, kept64 = parity.oracle_deep(oracle, L)
+    kept, Ko, Vo, _ = parity.gpu_deep(L)
+    B, H, l, d = L.K.shape
+    assert np.array_equal(kept[..., :L.budget], kept64)
+    kept_layer = wl.Layer(L.dtype, np.ascontiguousarray(Ko[:, :, :L.budget]),
+                          np.ascontiguousarray(Vo[:, :, :L.budget]), L.Qw, L.group_size, L.window, L.pool,
+                          L.budget, 256)
+    g = parity.gpu_shallow(kept_layer, 256)
+    for t, X, theta in (("k", L.K, L.theta_k), ("v", L.V, L.theta_v)):
+        for h in range(H):
+            X64 = wl.to_f64(X[0, h][kept64[0, h]], L.dtype)
+            parity.check_shallow_unit(oracle, X64, theta, 256, L.dtype, g, t, 0, h)
+    # Eq. 15 for this layer from the counts of both stages
+    from paper_2507_06517_amd import binding as sb
+    stored = int(g["n_codes_k"].sum() + g["n_codes_v"].sum())
+    r1, r2, r3, r = sb.spindle_reserve_ratio(2 * H * L.budget, 2 * H * l, stored, d, 16, 16)
+    assert r1 == L.budget / l and 0 < r2 <= 256 / L.budget and abs(r - r1 * r2 * (d + 2) / d) < 1e-15
