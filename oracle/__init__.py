@@ -68,6 +68,9 @@ def lib():
         L.oracle_shallow_unit.restype = C.c_int
         L.oracle_reconstruct.argtypes = [_f64p, _i32p, _f64p, C.c_int, C.c_int, _f64p]
         L.oracle_reconstruct.restype = None
+        L.oracle_decode_merge.argtypes = [_f64p, C.c_int, C.c_int, _f64p, C.c_int, C.c_double, C.c_int, C.c_int,
+                                          _f64p, _i32p, _f64p, _i32p]
+        L.oracle_decode_merge.restype = C.c_int
         L.oracle_layer_ratios.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int, C.c_double, _f64p]
         L.oracle_layer_ratios.restype = None
         L.oracle_reserve_ratio.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int, C.c_int, C.c_int, _f64p]
@@ -214,6 +217,26 @@ def shallow_layer(X, theta, cap, threads=8):
     units = [(b, h) for b in range(B) for h in range(H)]
     with ThreadPoolExecutor(max_workers=threads) as ex:
         return list(ex.map(lambda u: shallow_unit(X[u[0], u[1]], theta, cap), units))
+
+
+def decode_merge(X, Cb, theta, cap, literal=False):
+    """Decode-time merge of the new tokens X [m, d] into the stored codebook Cb [nc, d] (float64
+    values of the stored rows).  Returns dict(mag, ref, C_new (rows appended), n_found (entries
+    needed in total), n_codes (entries stored afterwards), n_matched)."""
+    X = _c(X)
+    m, d = X.shape
+    Cb = _c(Cb).reshape(-1, d)
+    nc = Cb.shape[0]
+    mag = np.empty(m, dtype=np.float64)
+    ref = np.full(max(m, 1), -1, dtype=np.int32)
+    C_new = np.zeros((max(m, 1), d), dtype=np.float64)
+    nm = np.zeros(1, dtype=np.int32)
+    Cin = Cb if nc else np.zeros((1, d), dtype=np.float64)
+    found = lib().oracle_decode_merge(X, m, d, Cin, nc, float(theta), int(cap), int(bool(literal)),
+                                      mag, ref, C_new, nm)
+    stored = max(nc, min(found, cap))
+    return dict(mag=mag, ref=ref[:m].copy(), C_new=C_new[:stored - nc].copy(), n_found=found,
+                n_codes=stored, n_matched=int(nm[0]))
 
 
 def reconstruct(Cb, ref, mag):

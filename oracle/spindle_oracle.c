@@ -361,6 +361,69 @@ int oracle_shallow_unit(const double *X, int n, int d, double theta, int cap, in
     return nc;
 }
 
+/*
+ * Decode-time merge (Sec. "Similarity Based Token Replacement", the paragraph after
+ * Eq. 14): tokens generated after the prefill first look for a codebook entry to merge
+ * with, with theta as the threshold; the tokens that find none get a codebook of their
+ * own by the same construction (Alg. 1), appended to the existing one.
+ *   X [m][d] new tokens, C_in [nc][d] the stored entries as they are stored (unit
+ *   vectors up to the rounding of their storage type).
+ * READINGS: an entry c suits token a if cos(x_a, C_c) > theta (strict, as Eq. 9), with the
+ * cosine of Eq. 4 taken between the raw token and the stored row, the row's own norm in
+ * the denominator; among several suitable entries the one of highest cosine is taken,
+ * lowest index on ties.  Alg. 1 runs on the unmatched tokens in their original order; its
+ * entries get the indices nc, nc + 1, ... in pick order.  Entries that do not fit into
+ * `cap` rows are not stored and their tokens keep ref = -1; the return value (entries
+ * needed in total) tells the caller.
+ *   mag [m], ref [m], C_new [m][d] (rows actually stored: min(picks, max(cap - nc, 0))),
+ *   *n_matched = tokens that merged with an existing entry.
+ * Returns nc + number of new picks.
+ */
+int oracle_decode_merge(const double *X, int m, int d, const double *C_in, int nc, double theta,
+                        int cap, int literal, double *mag, int32_t *ref, double *C_new, int32_t *n_matched)
+{
+    double *cn = (double *)malloc(sizeof(double) * (size_t)(nc + 1));
+    oracle_magnitudes(X, m, d, mag);
+    oracle_magnitudes(C_in, nc, d, cn);
+    int32_t *rest = (int32_t *)malloc(sizeof(int32_t) * (size_t)(m + 1));
+    int nr = 0, matched = 0;
+    for (int a = 0; a < m; ++a) {
+        const double *x = X + (size_t)a * d;
+        int best = -1; double bv = -INFINITY;
+        for (int c = 0; c < nc; ++c) {
+            const double *y = C_in + (size_t)c * d;
+            double dot = 0.0;
+            for (int t = 0; t < d; ++t) dot += x[t] * y[t];
+            double den = mag[a] * cn[c];
+            double cs = den > 0.0 ? dot / den : 0.0;
+            if (cs > theta && cs > bv) { bv = cs; best = c; }
+        }
+        ref[a] = best;
+        if (best >= 0) ++matched; else rest[nr++] = a;
+    }
+    *n_matched = matched;
+    int picks_n = 0;
+    if (nr > 0) {
+        int W = WORDS(nr);
+        double *XR = (double *)malloc(sizeof(double) * (size_t)nr * d);
+        double *mR = (double *)malloc(sizeof(double) * (size_t)nr);
+        uint32_t *G = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)nr * W + 4);
+        int32_t *deg = (int32_t *)malloc(sizeof(int32_t) * (size_t)nr);
+        int32_t *picks = (int32_t *)malloc(sizeof(int32_t) * (size_t)nr);
+        int32_t *rr = (int32_t *)malloc(sizeof(int32_t) * (size_t)nr);
+        for (int j = 0; j < nr; ++j) memcpy(XR + (size_t)j * d, X + (size_t)rest[j] * d, sizeof(double) * (size_t)d);
+        oracle_magnitudes(XR, nr, d, mR);
+        oracle_adjacency(XR, mR, nr, d, theta, G, deg);
+        picks_n = literal ? oracle_merge_literal(G, nr, picks, rr) : oracle_merge_incremental(G, nr, picks, rr);
+        int room = cap - nc; if (room < 0) room = 0;
+        for (int j = 0; j < nr; ++j) ref[rest[j]] = rr[j] < room ? nc + rr[j] : -1;
+        oracle_codebook(XR, mR, d, picks, picks_n < room ? picks_n : room, C_new);
+        free(XR); free(mR); free(G); free(deg); free(picks); free(rr);
+    }
+    free(cn); free(rest);
+    return nc + picks_n;
+}
+
 /* Eq. (14): reconstruction  x~_a = C[r_a] * m_a. */
 void oracle_reconstruct(const double *C, const int32_t *ref, const double *mag, int n, int d,
                         double *out)
