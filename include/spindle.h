@@ -177,6 +177,45 @@ spindle_status spindle_reconstruct(int32_t units, int32_t seq_len, int32_t head_
                                    const float *mag, void *out, void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Decode-time merge                                                           */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Workspace of spindle_decode_merge for desc (seq_len = new tokens per problem, at most 1024;
+ * group_size is ignored).  Errors as check of desc; UNSUPPORTED beyond 1024 new tokens.
+ */
+spindle_status spindle_decode_workspace_bytes(const spindle_kv_desc *desc, size_t *bytes);
+
+/*
+ * Sec. "Similarity Based Token Replacement", the paragraph after Eq. 14: new tokens of one
+ * tensor (K or V) are merged into the codebooks an earlier spindle_compress_shallow or
+ * spindle_decode_merge call left.  Per problem u = (batch, kv-head), with m = desc->seq_len:
+ *   1. every new token a takes the stored entry c < n_codes[u] of highest cosine (Eq. 4,
+ *      between the raw token and the stored row, the row's own norm in the denominator),
+ *      lowest c on ties, provided that cosine exceeds theta (strictly, as Eq. 9);
+ *   2. the tokens that found none run through Alg. 1 among themselves (Eq. 9-13, their input
+ *      order deciding ties); pick j becomes entry n_codes[u] + j: its unit vector is
+ *      written to row n_codes[u] + j of C and its tokens refer to it.
+ * Decisions are taken in double precision exactly as spindle_compress_shallow takes them.
+ * Entries that do not fit into max_codes rows are not stored and their tokens get ref = -1;
+ * n_found tells (n_found[u] > max_codes: rebuild or enlarge the codebook).
+ *   X_new     [batch, n_kv_heads, m, d] in desc->dtype (device)
+ *   C         [batch, n_kv_heads, max_codes, d] in desc->dtype (device), read and appended to
+ *   n_codes   [batch, n_kv_heads] int32 (device): in = stored entries, out = stored entries afterwards
+ *   n_found   [batch, n_kv_heads] int32 (device): entries needed in total
+ *   n_matched [batch, n_kv_heads] int32 (device), optional: tokens merged in step 1
+ *   ref       [batch, n_kv_heads, m] int32 (device): entry of each new token
+ *   mag       [batch, n_kv_heads, m] float32 (device): Eq. 8
+ * Only enqueues on `stream`; allocates nothing.  Errors: INVALID_ARG (null or misaligned
+ * pointers, theta outside (-1, 1), max_codes < 1), UNSUPPORTED (head_dim != 128, m > 1024),
+ * WORKSPACE, HIP.
+ */
+spindle_status spindle_decode_merge(const spindle_kv_desc *desc, const void *X_new, float theta,
+                                    int32_t max_codes, void *C, int32_t *n_codes, int32_t *n_found,
+                                    int32_t *n_matched, int32_t *ref, float *mag, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- */
 /* Host helpers (plain arithmetic on the host, no GPU work)                    */
 /* ------------------------------------------------------------------------- */
 

@@ -25,7 +25,8 @@ _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
            "spindle_compress_shallow", "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
-           "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_profile_read",
+           "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_decode_workspace_bytes", "spindle_decode_merge",
+           "spindle_profile_read",
            "spindle_last_error", "spindle_version"]
 
 
@@ -64,7 +65,9 @@ def lib():
         L.spindle_layer_budgets.argtypes = [C.c_double, i32, i32, i32, C.c_double, C.POINTER(C.c_int32),
                                             C.POINTER(C.c_double)]
         L.spindle_reserve_ratio.argtypes = [C.c_int64, C.c_int64, C.c_int64, i32, i32, i32, C.POINTER(C.c_double)]
-        for name in EXPORTS[:9]:
+        L.spindle_decode_workspace_bytes.argtypes = [C.POINTER(KvDesc), C.POINTER(sz)]
+        L.spindle_decode_merge.argtypes = [C.POINTER(KvDesc), vp, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        for name in EXPORTS[:11]:
             getattr(L, name).restype = C.c_int
         L.spindle_last_error.restype = C.c_char_p
         L.spindle_version.restype = C.c_uint32
@@ -173,6 +176,37 @@ def spindle_reserve_ratio(kept_tokens, total_tokens, codebook_entries, head_dim=
     _check(lib().spindle_reserve_ratio(int(kept_tokens), int(total_tokens), int(codebook_entries), int(head_dim),
                                        int(index_bits), int(elem_bits), out))
     return tuple(out[:])
+
+
+def spindle_decode_workspace_bytes(desc: KvDesc) -> int:
+    out = C.c_size_t(0)
+    _check(lib().spindle_decode_workspace_bytes(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def spindle_decode_merge(desc, X_new, theta, max_codes, Cb, n_codes, n_found, n_matched, ref, mag, workspace,
+                         workspace_bytes, stream=None):
+    _check(lib().spindle_decode_merge(C.byref(desc), _ptr(X_new), float(theta), int(max_codes), _ptr(Cb),
+                                      _ptr(n_codes), _ptr(n_found), _ptr(n_matched), _ptr(ref), _ptr(mag),
+                                      _ptr(workspace), int(workspace_bytes), stream or _stream()))
+
+
+def decode_merge(X_new, dtype, theta, Cb, n_codes):
+    """Merges X_new [B, H, m, d] into the codebooks Cb [B, H, cap, d] (updated in place, with n_codes
+    [B, H] int32).  Returns dict(ref, mag, n_found, n_matched)."""
+    import torch
+    B, H, m, d = X_new.shape
+    desc = KvDesc(B, H, 1, m, d, _DT[dtype])
+    nbytes = spindle_decode_workspace_bytes(desc)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X_new.device)
+    out = dict(ref=torch.empty((B, H, m), dtype=torch.int32, device=X_new.device),
+               mag=torch.empty((B, H, m), dtype=torch.float32, device=X_new.device),
+               n_found=torch.empty((B, H), dtype=torch.int32, device=X_new.device),
+               n_matched=torch.empty((B, H), dtype=torch.int32, device=X_new.device))
+    spindle_decode_merge(desc, X_new, theta, Cb.shape[2], Cb, n_codes, out["n_found"], out["n_matched"],
+                         out["ref"], out["mag"], ws, ws.numel())
+    out["workspace"] = ws
+    return out
 
 
 def spindle_profile(enable: bool) -> None:

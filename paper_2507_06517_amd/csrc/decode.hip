@@ -1,0 +1,389 @@
+// Decode-time merge (Sec. "Similarity Based Token Replacement", the paragraph after Eq. 14):
+// tokens generated after the prefill first look for a stored codebook entry within theta;
+// those that find none get entries of their own by the construction of Alg. 1, appended to
+// the codebook.
+//
+// Kernels, enqueued on the caller's stream; u indexes one (batch, kv-head) problem of m new tokens:
+//   decode_match   magnitudes (Eq. 8) and, per new token, the stored entry of highest cosine
+//                  (Eq. 4) if it exceeds theta, lowest index on ties; everything in double
+//                  precision with the dimension-order sums the adjacency decision is defined by
+//   decode_build   one workgroup per problem: the unmatched tokens' adjacency matrix (Eq. 9) in
+//                  LDS, the greedy highest-degree loop (Eq. 10-13) as stated, new entries and
+//                  references
+#include <math.h>
+
+#include "common.h"
+
+namespace spindle {
+namespace {
+
+constexpr int kDecodeMax = 1024;     // new tokens per problem and call
+constexpr int kMatchTokens = 16;     // new tokens per workgroup of decode_match
+constexpr int kMatchThreads = 256;
+constexpr int kBuildThreads = 1024;
+
+struct DecodeParams {
+  const char *X;        // [U][m][128] new tokens in `dtype`
+  char *C;              // [U][cap][128] codebook in `dtype`, rows < n_codes[u] valid, appended to
+  int32_t *n_codes;     // [U] in: stored entries, out: stored entries afterwards
+  int32_t *n_found;     // [U] entries needed (stored + new picks), may exceed cap
+  int32_t *n_matched;   // [U] optional: tokens merged with an existing entry
+  int32_t *ref;         // [U][m]
+  float *mag;           // [U][m]
+  double *m64;          // workspace [U][m]
+  int dtype, U, m, cap;
+  double theta;
+};
+
+template <int DT>
+__device__ __forceinline__ const char *token_row(const DecodeParams &p, int u, int a) {
+  return p.X + ((size_t)u * p.m + a) * (kHeadDim * sizeof(typename Elem<DT>::type));
+}
+
+// (value, index) maximum with the lower index winning ties
+__device__ __forceinline__ void take_better(double &bv, int &bi, double ov, int oi) {
+  if (oi >= 0 && (bi < 0 || ov > bv || (ov == bv && oi < bi))) {
+    bv = ov;
+    bi = oi;
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p) {
+  typedef typename Elem<DT>::type T;
+  constexpr int per = 16 / sizeof(T);              // elements per 16-byte piece
+  constexpr int pieces = kHeadDim / per;
+  __shared__ __attribute__((aligned(16))) double xs[kHeadDim][kMatchTokens];   // [dimension][token]
+  __shared__ double ms[kMatchTokens];
+  __shared__ double red_v[kMatchThreads / kWave][kMatchTokens];
+  __shared__ int red_i[kMatchThreads / kWave][kMatchTokens];
+  const int u = blockIdx.y, a0 = blockIdx.x * kMatchTokens, tid = threadIdx.x;
+  int nc = p.n_codes[u];
+  nc = nc < 0 ? 0 : (nc > p.cap ? p.cap : nc);
+
+  for (int i = tid; i < kMatchTokens * kHeadDim; i += kMatchThreads) {
+    const int tok = i / kHeadDim, dim = i % kHeadDim;
+    double v = 0.0;
+    if (a0 + tok < p.m) v = (double)Elem<DT>::to_float(reinterpret_cast<const T *>(token_row<DT>(p, u, a0 + tok))[dim]);
+    xs[dim][tok] = v;
+  }
+  __syncthreads();
+  if (tid < kMatchTokens) {
+    double ss = 0.0;
+    for (int dim = 0; dim < kHeadDim; ++dim) ss += xs[dim][tid] * xs[dim][tid];
+    const double mg = sqrt(ss);
+    ms[tid] = mg;
+    if (a0 + tid < p.m) {
+      p.m64[(size_t)u * p.m + a0 + tid] = mg;
+      p.mag[(size_t)u * p.m + a0 + tid] = (float)mg;
+    }
+  }
+  __syncthreads();
+
+  double best[kMatchTokens];
+  int bidx[kMatchTokens];
+#pragma unroll
+  for (int t = 0; t < kMatchTokens; ++t) {
+    best[t] = 0.0;
+    bidx[t] = -1;
+  }
+  const char *Cu = p.C + (size_t)u * p.cap * (kHeadDim * sizeof(T));
+  for (int c = tid; c < nc; c += kMatchThreads) {
+    const u4 *row = reinterpret_cast<const u4 *>(Cu + (size_t)c * (kHeadDim * sizeof(T)));
+    double acc[kMatchTokens];
+#pragma unroll
+    for (int t = 0; t < kMatchTokens; ++t) acc[t] = 0.0;
+    double css = 0.0;
+    for (int pc = 0; pc < pieces; ++pc) {
+      const u4 v = row[pc];
+      const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+      for (int j = 0; j < per; ++j) {
+        const double y = (double)Elem<DT>::to_float(e[j]);
+        css += y * y;
+        const double *xr = xs[pc * per + j];
+#pragma unroll
+        for (int t = 0; t < kMatchTokens; ++t) acc[t] += xr[t] * y;
+      }
+    }
+    const double cn = sqrt(css);
+#pragma unroll
+    for (int t = 0; t < kMatchTokens; ++t) {
+      const double den = ms[t] * cn;
+      const double cs = den > 0.0 ? acc[t] / den : 0.0;
+      if (cs > p.theta && (bidx[t] < 0 || cs > best[t])) {   // c ascends: the first of equal values stays
+        best[t] = cs;
+        bidx[t] = c;
+      }
+    }
+  }
+  const int lane = lane_id(), wave = tid >> 6;
+#pragma unroll
+  for (int t = 0; t < kMatchTokens; ++t) {
+    double bv = best[t];
+    int bi = bidx[t];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const double ov = __shfl_xor(bv, o);
+      const int oi = __shfl_xor(bi, o);
+      take_better(bv, bi, ov, oi);
+    }
+    if (lane == 0) {
+      red_v[wave][t] = bv;
+      red_i[wave][t] = bi;
+    }
+  }
+  __syncthreads();
+  if (tid < kMatchTokens && a0 + tid < p.m) {
+    double bv = red_v[0][tid];
+    int bi = red_i[0][tid];
+    for (int w = 1; w < kMatchThreads / kWave; ++w) take_better(bv, bi, red_v[w][tid], red_i[w][tid]);
+    p.ref[(size_t)u * p.m + a0 + tid] = bi;
+  }
+}
+
+// LDS of decode_build, in 32-bit words, for m new tokens: one token as doubles per wave, the
+// adjacency rows with an odd pitch (thread i walks row i: consecutive rows must start in
+// different banks), two bitmaps, then four 16-bit arrays (position in the input, degree, pick
+// number per token; the pick list).  160,000 bytes at m = 1024.
+__host__ __device__ inline int build_pitch(int m) { return ((m + 31) / 32) | 1; }
+__host__ __device__ inline size_t build_lds_words(int m) {
+  return 2 * kHeadDim * (kBuildThreads / kWave) + (size_t)m * build_pitch(m) + 2 * (size_t)((m + 31) / 32) +
+         2 * (size_t)((m + 1) & ~1);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kBuildThreads) void decode_build(DecodeParams p) {
+  typedef typename Elem<DT>::type T;
+  constexpr int per = 16 / sizeof(T);
+  constexpr int pieces = kHeadDim / per;
+  constexpr int kWaves = kBuildThreads / kWave;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  __shared__ int wave_sum[kWaves];
+  __shared__ uint32_t wave_key[kWaves];
+  __shared__ int sh_r;
+  const int u = blockIdx.x, m = p.m, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+  const int Wd = (m + 31) / 32, pitch = build_pitch(m);
+  double *xi = reinterpret_cast<double *>(lds) + (size_t)wave * kHeadDim;   // one token per wave
+  uint32_t *adj = lds + 2 * kHeadDim * kWaves;       // [m][pitch]
+  uint32_t *alive = adj + (size_t)m * pitch;         // [Wd]
+  uint32_t *dying = alive + Wd;                      // [Wd]
+  const int m2 = (m + 1) & ~1;
+  uint16_t *rest = reinterpret_cast<uint16_t *>(dying + Wd);   // unmatched tokens, input order
+  uint16_t *deg = rest + m2;
+  uint16_t *rref = deg + m2;                         // pick number of each unmatched token
+  uint16_t *picks = rref + m2;                       // unmatched-token index of each pick
+  int nc = p.n_codes[u];
+  nc = nc < 0 ? 0 : (nc > p.cap ? p.cap : nc);
+  int32_t *ref = p.ref + (size_t)u * m;
+  const double *m64 = p.m64 + (size_t)u * m;
+
+  // unmatched tokens in input order
+  {
+    const bool un = tid < m && ref[tid] < 0;
+    const unsigned long long mk = __ballot(un);
+    if (lane == 0) wave_sum[wave] = __popcll(mk);
+    __syncthreads();
+    int before = 0, total = 0;
+    for (int w = 0; w < kWaves; ++w) {
+      before += w < wave ? wave_sum[w] : 0;
+      total += wave_sum[w];
+    }
+    if (un) rest[before + __popcll(mk & ((1ull << lane) - 1ull))] = (uint16_t)tid;
+    if (tid == 0) sh_r = total;
+  }
+  for (int i = tid; i < m * pitch; i += kBuildThreads) adj[i] = 0u;
+  __syncthreads();
+  const int r = sh_r;
+  if (tid == 0 && p.n_matched) p.n_matched[u] = m - r;
+
+  // Eq. 9 among the unmatched tokens: each unordered pair once, both bits set
+  for (int i = wave; i < r; i += kWaves) {
+    const T *src = reinterpret_cast<const T *>(token_row<DT>(p, u, rest[i]));
+    xi[lane] = (double)Elem<DT>::to_float(src[lane]);
+    xi[lane + 64] = (double)Elem<DT>::to_float(src[lane + 64]);
+    const double mi = m64[rest[i]];
+    if (lane == 0) atomicOr(&adj[(size_t)i * pitch + (i >> 5)], 1u << (i & 31));     // G_aa = 1
+    __builtin_amdgcn_wave_barrier();
+    for (int j0 = i + 1; j0 < r; j0 += kWave) {
+      const int j = j0 + lane;
+      if (j < r) {
+        const u4 *row = reinterpret_cast<const u4 *>(token_row<DT>(p, u, rest[j]));
+        double acc = 0.0;
+        for (int pc = 0; pc < pieces; ++pc) {
+          const u4 v = row[pc];
+          const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+          for (int k = 0; k < per; ++k) acc += xi[pc * per + k] * (double)Elem<DT>::to_float(e[k]);
+        }
+        const double den = mi * m64[rest[j]];
+        const double cs = den > 0.0 ? acc / den : 0.0;
+        if (cs > p.theta) {
+          atomicOr(&adj[(size_t)i * pitch + (j >> 5)], 1u << (j & 31));
+          atomicOr(&adj[(size_t)j * pitch + (i >> 5)], 1u << (i & 31));
+        }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+  for (int w = tid; w < Wd; w += kBuildThreads) {
+    const int lo = w * 32;
+    alive[w] = r >= lo + 32 ? 0xFFFFFFFFu : (r > lo ? (1u << (r - lo)) - 1u : 0u);
+  }
+  __syncthreads();
+  if (tid < r) {                                     // Eq. 10
+    int d = 0;
+    for (int w = 0; w < Wd; ++w) d += __popc(adj[(size_t)tid * pitch + w]);
+    deg[tid] = (uint16_t)d;
+  }
+  __syncthreads();
+
+  // Alg. 1: take the remaining token of highest degree (lowest index on ties), give its
+  // remaining neighbourhood its entry, remove it, lower the degrees of the others (Eq. 11-13)
+  int npicks = 0;
+  for (;;) {
+    const bool live = tid < r && ((alive[tid >> 5] >> (tid & 31)) & 1u);
+    uint32_t key = live ? ((uint32_t)deg[tid] << 16) | (uint32_t)(0xFFFF - tid) : 0u;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const uint32_t ok = __shfl_xor(key, o);
+      key = ok > key ? ok : key;
+    }
+    if (lane == 0) wave_key[wave] = key;
+    __syncthreads();
+    uint32_t top = 0;
+    for (int w = 0; w < kWaves; ++w) top = wave_key[w] > top ? wave_key[w] : top;
+    if (top == 0u) break;                            // nobody left
+    if ((top >> 16) == 1u) {
+      // only isolated tokens are left: each is its own entry, in index order
+      if (live) {
+        int before = 0;
+        for (int w = 0; w < (tid >> 5); ++w) before += __popc(alive[w]);
+        before += __popc(alive[tid >> 5] & ((1u << (tid & 31)) - 1u));
+        rref[tid] = (uint16_t)(npicks + before);
+        picks[npicks + before] = (uint16_t)tid;
+      }
+      int total = 0;
+      for (int w = 0; w < Wd; ++w) total += __popc(alive[w]);
+      npicks += total;
+      break;
+    }
+    const int v = 0xFFFF - (int)(top & 0xFFFFu);
+    if (tid < Wd) dying[tid] = adj[(size_t)v * pitch + tid] & alive[tid];
+    if (tid == 0) picks[npicks] = (uint16_t)v;
+    __syncthreads();
+    if (live) {
+      if ((dying[tid >> 5] >> (tid & 31)) & 1u) {
+        rref[tid] = (uint16_t)npicks;                // Eq. 12
+      } else {
+        int gone = 0;
+        for (int w = 0; w < Wd; ++w) {
+          const uint32_t dw = dying[w];
+          if (dw) gone += __popc(adj[(size_t)tid * pitch + w] & dw);
+        }
+        deg[tid] = (uint16_t)(deg[tid] - gone);      // Eq. 13, as a degree update
+      }
+    }
+    __syncthreads();
+    if (tid < Wd) alive[tid] &= ~dying[tid];
+    ++npicks;
+    __syncthreads();
+  }
+  __syncthreads();
+
+  // outputs: references of the unmatched tokens, the new rows, the counts
+  const int room = p.cap - nc > 0 ? p.cap - nc : 0;
+  const int stored = npicks < room ? npicks : room;
+  if (tid < r) ref[rest[tid]] = (int)rref[tid] < room ? nc + (int)rref[tid] : -1;
+  T *Cu = reinterpret_cast<T *>(p.C) + (size_t)u * p.cap * kHeadDim;
+  for (int j = wave; j < stored; j += kWaves) {
+    const int tok = rest[picks[j]];
+    const T *src = reinterpret_cast<const T *>(token_row<DT>(p, u, tok));
+    const double mg = m64[tok];
+    for (int d = lane; d < kHeadDim; d += kWave) {
+      const double x = (double)Elem<DT>::to_float(src[d]);
+      Cu[(size_t)(nc + j) * kHeadDim + d] = Elem<DT>::from_float(mg > 0.0 ? (float)(x / mg) : 0.f);
+    }
+  }
+  if (tid == 0) {
+    p.n_found[u] = nc + npicks;
+    p.n_codes[u] = nc + stored;
+  }
+}
+
+spindle_status check_decode(const spindle_kv_desc *desc) {
+  spindle_status s = check_desc(desc);
+  if (s != SPINDLE_OK) return s;
+  if (desc->seq_len > kDecodeMax)
+    SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "at most %d new tokens per call, got %d", kDecodeMax, desc->seq_len);
+  return SPINDLE_OK;
+}
+
+size_t decode_workspace(const spindle_kv_desc *desc) {
+  return align_up((size_t)desc->batch * desc->n_kv_heads * desc->seq_len * sizeof(double), 256);
+}
+
+}  // namespace
+}  // namespace spindle
+
+using namespace spindle;
+
+extern "C" spindle_status spindle_decode_workspace_bytes(const spindle_kv_desc *desc, size_t *bytes) {
+  if (!bytes) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "bytes is NULL");
+  spindle_status s = check_decode(desc);
+  if (s != SPINDLE_OK) return s;
+  *bytes = decode_workspace(desc);
+  return SPINDLE_OK;
+}
+
+extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, const void *X_new, float theta,
+                                               int32_t max_codes, void *C, int32_t *n_codes, int32_t *n_found,
+                                               int32_t *n_matched, int32_t *ref, float *mag, void *workspace,
+                                               size_t workspace_bytes, void *stream) {
+  spindle_status s = check_decode(desc);
+  if (s != SPINDLE_OK) return s;
+  if (max_codes < 1) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "max_codes must be >= 1");
+  if (!(theta > -1.f && theta < 1.f)) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "theta must lie in (-1, 1)");
+  if (!X_new || !C || !n_codes || !n_found || !ref || !mag || !workspace)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "X_new, C, n_codes, n_found, ref, mag and workspace are required");
+  if ((reinterpret_cast<uintptr_t>(X_new) | reinterpret_cast<uintptr_t>(C) | reinterpret_cast<uintptr_t>(workspace)) & 15)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+  if (workspace_bytes < decode_workspace(desc))
+    SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, decode_workspace(desc));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DecodeParams p;
+  p.X = static_cast<const char *>(X_new);
+  p.C = static_cast<char *>(C);
+  p.n_codes = n_codes;
+  p.n_found = n_found;
+  p.n_matched = n_matched;
+  p.ref = ref;
+  p.mag = mag;
+  p.m64 = static_cast<double *>(workspace);
+  p.dtype = desc->dtype;
+  p.U = desc->batch * desc->n_kv_heads;
+  p.m = desc->seq_len;
+  p.cap = max_codes;
+  p.theta = (double)theta;
+  const dim3 mg((p.m + kMatchTokens - 1) / kMatchTokens, p.U);
+  const size_t lds = build_lds_words(p.m) * sizeof(uint32_t);
+#define SPINDLE_DECODE_LAUNCH(DT)                                                                          \
+  do {                                                                                                     \
+    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_build<DT>),                     \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                \
+    {                                                                                                      \
+      ProfScope ps("decode_match", st);                                                                    \
+      hipLaunchKernelGGL(decode_match<DT>, mg, dim3(kMatchThreads), 0, st, p);                             \
+    }                                                                                                      \
+    {                                                                                                      \
+      ProfScope ps("decode_build", st);                                                                    \
+      hipLaunchKernelGGL(decode_build<DT>, dim3(p.U), dim3(kBuildThreads), lds, st, p);                    \
+    }                                                                                                      \
+  } while (0)
+  if (p.dtype == SPINDLE_F16) SPINDLE_DECODE_LAUNCH(SPINDLE_F16);
+  else if (p.dtype == SPINDLE_BF16) SPINDLE_DECODE_LAUNCH(SPINDLE_BF16);
+  else SPINDLE_DECODE_LAUNCH(SPINDLE_F32);
+#undef SPINDLE_DECODE_LAUNCH
+  SPINDLE_HIP(hipGetLastError());
+  return SPINDLE_OK;
+}

@@ -238,3 +238,19 @@ def small_random(seed: int, dtype: str = "f16", B: int = 1, H: int = 2, l: int =
     """Small ragged-size layer for parity tests (sizes need not be tile multiples)."""
     return _clustered_layer((99, seed, l), dtype, B, H, l, hn, lw, pool, budget, cap, n_centroids,
                             noise_frac=noise_frac, drift_sigma=drift_sigma, name=f"small/{seed}/{l}")
+
+
+def decode_case(seed: int, dtype: str = "f16", B: int = 1, H: int = 2, n_prefill: int = 600, m: int = 128,
+                n_centroids: int = 24, novel_frac: float = 0.25, novel_centroids: int = 5,
+                sigma: float = 0.1, d: int = 128):
+    """Decode-time stand-in: `n_prefill` clustered tokens per head (the codebook is built from
+    them) and `m` later tokens, of which a fraction `novel_frac` comes from `novel_centroids`
+    directions the prefill never saw (they find no entry and need new ones) and the rest from
+    the prefill's own centroids.  Returns (prefill [B,H,n_prefill,d], new [B,H,m,d]) in the
+    device representation of `dtype`."""
+    rng = _rng(77, seed, n_prefill, m)
+    x, cent, _ = clustered(rng, B, H, n_prefill + m, d, n_centroids, sigma, heavy_frac=0.05)
+    fresh, _, _ = clustered(rng, B, H, m, d, max(novel_centroids, 1), sigma)
+    novel = rng.random((B, H, m)) < novel_frac
+    new = np.where(novel[..., None], fresh, x[:, :, n_prefill:])
+    return cast(x[:, :, :n_prefill], dtype), cast(new, dtype)

@@ -109,3 +109,20 @@ def test_compress_calls_reject_bad_arguments_before_any_launch(sb):
     assert shallow(wsb=1024) == 3
     assert L.spindle_reconstruct(1, 16, 64, sb.F16, 4, fake, fake, fake, fake, null) == 2
     assert L.spindle_reconstruct(1, 16, 128, sb.F16, 4, null, fake, fake, fake, null) == 1
+
+    # decode-time merge: validation happens before anything is enqueued
+    dd = sb.KvDesc(1, 2, 1, 64, 128, sb.F16)
+
+    def decode(**kw):
+        a = dict(d=dd, X=fake, th=0.98, cap=16, C=fake, nc=fake, nf=fake, ref=fake, mag=fake, ws=fake, wsb=1 << 20)
+        a.update(kw)
+        return L.spindle_decode_merge(C.byref(a["d"]), a["X"], a["th"], a["cap"], a["C"], a["nc"], a["nf"], null,
+                                      a["ref"], a["mag"], a["ws"], a["wsb"], null)
+
+    assert decode(X=null) == 1
+    assert decode(cap=0) == 1
+    assert decode(th=1.0) == 1
+    assert decode(wsb=16) == 3
+    assert decode(d=sb.KvDesc(1, 2, 1, 1025, 128, sb.F16)) == 2
+    assert decode(d=sb.KvDesc(1, 2, 1, 64, 64, sb.F16)) == 2
+    assert sb.spindle_decode_workspace_bytes(dd) >= 2 * 64 * 8

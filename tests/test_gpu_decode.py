@@ -1,0 +1,136 @@
+"""Parity of spindle_decode_merge (decode-time merge, paragraph after Eq. 14) with the oracle.
+The stored codebook both sides start from is the oracle's own prefill codebook, rounded to the
+storage type by the input generators; nothing the library computes reaches the oracle."""
+import numpy as np
+import pytest
+
+from paper_2507_06517_amd import workloads as wl
+
+import parity
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(300)]
+
+
+def stored_codebooks(oracle, pre, dtype, theta, cap, keep):
+    """Oracle prefill codebooks of every head, first `keep[b][h]` entries, as device bits."""
+    B, H, n0, d = pre.shape
+    Cb = np.zeros((B, H, cap, d), dtype=wl.cast(np.zeros(1), dtype).dtype)
+    nc = np.zeros((B, H), dtype=np.int32)
+    for b in range(B):
+        for h in range(H):
+            o = oracle.shallow_unit(wl.to_f64(pre[b, h], dtype), theta, cap)
+            k = min(o["n_codes"], keep[b][h])
+            Cb[b, h, :k] = wl.cast(o["C"][:k], dtype)
+            nc[b, h] = k
+    return Cb, nc
+
+
+def run_and_check(oracle, new, Cb, nc, dtype, theta):
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    B, H, m, d = new.shape
+    cap = Cb.shape[2]
+    th = float(np.float32(theta))
+    Cd, nd = sb.to_device(Cb, dtype), torch.from_numpy(nc.copy()).cuda()
+    out = sb.decode_merge(sb.to_device(new, dtype), dtype, th, Cd, nd)
+    torch.cuda.synchronize()
+    Cg = sb.to_host_bits(Cd, dtype)
+    g = {k: v.cpu().numpy() for k, v in out.items() if k != "workspace"}
+    n_after = nd.cpu().numpy()
+    res = []
+    for b in range(B):
+        for h in range(H):
+            k = int(nc[b, h])
+            o = oracle.decode_merge(wl.to_f64(new[b, h], dtype), wl.to_f64(Cb[b, h, :k], dtype), th, cap)
+            assert g["n_matched"][b, h] == o["n_matched"]
+            assert g["n_found"][b, h] == o["n_found"] and n_after[b, h] == o["n_codes"]
+            assert np.array_equal(g["ref"][b, h], o["ref"]), "references differ"
+            assert np.array_equal(g["mag"][b, h], o["mag"].astype(np.float32)), "magnitudes differ"
+            assert np.array_equal(Cg[b, h, :k], Cb[b, h, :k]), "stored entries must not change"
+            parity.check_codebook_vectors(Cg[b, h, k:o["n_codes"]], o["C_new"], dtype)
+            assert not Cg[b, h, o["n_codes"]:].any(), "rows past the stored entries must stay zero"
+            res.append(o)
+    return res, Cg, n_after
+
+
+@pytest.mark.parametrize("dtype,m", [("f16", 128), ("bf16", 37), ("f32", 256), ("f16", 1), ("f16", 1024), ("bf16", 700)])
+def test_decode_merge_sizes_and_types(oracle, dtype, m):
+    theta = 0.95 if dtype == "bf16" else 0.98
+    pre, new = wl.decode_case(m, dtype, B=1, H=3, n_prefill=500, m=m)
+    Cb, nc = stored_codebooks(oracle, pre, dtype, theta, 400, [[400, 400, 400]])
+    res, _, _ = run_and_check(oracle, new, Cb, nc, dtype, theta)
+    if m >= 37:
+        assert any(o["n_matched"] > 0 for o in res) and any(o["n_found"] > k for o, k in zip(res, nc.ravel()))
+
+
+def test_empty_partial_and_full_codebooks(oracle):
+    # unit 0: no stored entries (plain Alg. 1 on the new tokens); unit 1: half of the prefill's
+    # entries; units 2, 3: all of them; then tables with two free rows and with none
+    dtype, theta = "f16", 0.98
+    pre, new = wl.decode_case(3, dtype, B=2, H=2, n_prefill=400, m=200, novel_frac=0.4, novel_centroids=7)
+    Cb, nc = stored_codebooks(oracle, pre, dtype, theta, 64, [[0, 12], [64, 64]])
+    res, Cg, n_after = run_and_check(oracle, new, Cb, nc, dtype, theta)
+    assert res[0]["n_matched"] == 0
+    # a table with exactly two free rows
+    k = int(nc[1, 1])
+    small = np.ascontiguousarray(Cb[1:2, 1:2, :k + 2])
+    res2, _, _ = run_and_check(oracle, new[1:2, 1:2], small, nc[1:2, 1:2], dtype, theta)
+    assert res2[0]["n_found"] > k + 2 and (res2[0]["ref"] == -1).any()
+    # and one with none
+    none = np.ascontiguousarray(Cb[1:2, 1:2, :k])
+    res3, _, _ = run_and_check(oracle, new[1:2, 1:2], none, nc[1:2, 1:2], dtype, theta)
+    assert res3[0]["n_codes"] == k and (res3[0]["ref"] == -1).sum() == 200 - res3[0]["n_matched"]
+
+
+def test_duplicates_zero_vectors_and_equal_entries(oracle):
+    dtype, theta = "f32", 0.9
+    rng = np.random.default_rng(11)
+    d = 128
+    ent = rng.standard_normal((6, d))
+    ent /= np.linalg.norm(ent, axis=1, keepdims=True)
+    ent[4] = ent[1]                                   # two equal rows: the lower index wins
+    Cb = np.zeros((1, 1, 16, d), dtype=np.float32)
+    Cb[0, 0, :6] = ent
+    new = np.zeros((1, 1, 9, d), dtype=np.float32)
+    new[0, 0, 0] = 3 * ent[1]
+    new[0, 0, 1] = 0.0                                # zero vector: its own (zero) entry
+    new[0, 0, 2] = rng.standard_normal(d)             # new direction
+    new[0, 0, 3] = new[0, 0, 2] * 0.5                 # same direction: joins it
+    new[0, 0, 4] = ent[4] * 0.25
+    new[0, 0, 5] = 0.0
+    new[0, 0, 6] = -ent[0]                            # opposite to an entry
+    new[0, 0, 7] = ent[5] + 0.01 * rng.standard_normal(d)
+    new[0, 0, 8] = new[0, 0, 2]
+    res, _, _ = run_and_check(oracle, new, Cb, np.array([[6]], dtype=np.int32), dtype, theta)
+    r = res[0]["ref"]
+    assert r[0] == 1 and r[4] == 1 and r[7] == 5 and r[2] == r[3] == r[8] == 6 and r[6] >= 6
+    # theta below zero: a zero vector (cosine 0 by definition) merges with entry 0
+    run_and_check(oracle, new, Cb, np.array([[6]], dtype=np.int32), dtype, -0.5)
+
+
+def test_two_steps_in_a_row(oracle):
+    # the codebook grows over two calls; fp32 storage, where both sides round the new rows alike
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    dtype, theta = "f32", 0.98
+    pre, new = wl.decode_case(21, dtype, B=1, H=2, n_prefill=300, m=160, novel_frac=0.5, novel_centroids=9)
+    Cb, nc = stored_codebooks(oracle, pre, dtype, theta, 200, [[200, 200]])
+    first, second = new[:, :, :80], np.ascontiguousarray(new[:, :, 80:])
+    res, Cg, n_after = run_and_check(oracle, np.ascontiguousarray(first), Cb, nc, dtype, theta)
+    # the oracle's own table after step one, rounded to the storage type by the generator's cast
+    Cb1 = Cb.copy()
+    for h in range(2):
+        k = int(nc[0, h])
+        Cb1[0, h, k:res[h]["n_codes"]] = wl.cast(res[h]["C_new"], dtype)
+    nc1 = np.array([[res[0]["n_codes"], res[1]["n_codes"]]], dtype=np.int32)
+    assert np.array_equal(Cb1, Cg) and np.array_equal(nc1, n_after)
+    run_and_check(oracle, second, Cb1, nc1, dtype, theta)
+
+
+def test_rejects_bad_arguments():
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    d = sb.KvDesc(1, 2, 1, 2000, 128, sb.F16)
+    with pytest.raises(sb.SpindleError) as e:
+        sb.spindle_decode_workspace_bytes(d)
+    assert e.value.code == 2
