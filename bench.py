@@ -23,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F16_TFLOPS = 2500.0      # MI355X dense fp16 matrix peak
 PEAK_HBM_GBS = 8000.0
+PEAK_VALU_F64_TFLOPS = 78.6         # 256 CUs x 64 lanes x 2 flop x 2.4 GHz
 
 
 def cpu_baseline(L, wl, sample_n=12288):
@@ -75,6 +76,46 @@ def time_reconstruct(torch, sb, L, shallow, reps=20):
     gbs = nbytes / (ms * 1e-3) / 1e9
     return {"ms_k_and_v": ms, "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": gbs / PEAK_HBM_GBS, "tokens_per_s": L.batch * L.seq_len / (ms * 1e-3)}
+
+
+def time_decode(torch, sb, L, K, shallow, m=256, novel=0.25, reps=10):
+    """Decode-time merge on the step's own K codebooks, outside the timed step: m later tokens per
+    head (tokens of the layer at random positions with 1 % noise; a quarter replaced by directions
+    the layer never saw) merged into the stored entries.  Dominant kernel: the double-precision
+    search of the stored entries, 2 x 128 flop per (token, entry) on the vector ALUs."""
+    g = torch.Generator(device="cuda").manual_seed(5)
+    pos = torch.randint(0, L.seq_len, (m,), generator=g, device="cuda")
+    base = K[:, :, pos].float()
+    base = base * (1 + 0.01 * torch.randn(base.shape, generator=g, device="cuda"))
+    fresh = torch.randn(base.shape, generator=g, device="cuda")
+    pick = torch.rand((L.batch, L.n_kv_heads, m, 1), generator=g, device="cuda") < novel
+    new = torch.where(pick, fresh, base).to(K.dtype).contiguous()
+    cap = L.max_codes + m
+    stored = shallow.out["n_codes_k"].to(torch.int32)
+    Cb = torch.zeros((L.batch, L.n_kv_heads, cap, L.head_dim), dtype=K.dtype, device="cuda")
+    Cb[:, :, :L.max_codes] = shallow.out["C_k"]
+    nc = stored.clone()
+    out = sb.decode_merge(new, L.dtype, L.theta_k, Cb, nc)          # warm-up
+    torch.cuda.synchronize()
+    sb.spindle_profile(True)
+    for _ in range(reps):
+        nc.copy_(stored)
+        out = sb.decode_merge(new, L.dtype, L.theta_k, Cb, nc)
+    torch.cuda.synchronize()
+    recs = sb.spindle_profile_read()
+    sb.spindle_profile(False)
+    ms = {}
+    for name, t in recs:
+        ms[name] = ms.get(name, 0.0) + t / reps
+    total = sum(ms.values())
+    flop = 2.0 * L.head_dim * m * float(stored.sum().item())
+    tf = flop / (ms["decode_match"] * 1e-3) / 1e12
+    return {"new_tokens_per_head": m, "stored_entries": stored.cpu().numpy().ravel().tolist(),
+            "merged_with_stored": out["n_matched"].cpu().numpy().ravel().tolist(),
+            "entries_after": out["n_found"].cpu().numpy().ravel().tolist(),
+            "kernel_ms": ms, "tokens_per_s": L.batch * L.n_kv_heads * m / (total * 1e-3),
+            "roofline": {"kernel": "decode_match", "bound": "alu", "achieved": tf, "peak": PEAK_VALU_F64_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tf / PEAK_VALU_F64_TFLOPS}}
 
 
 def main():
@@ -193,6 +234,7 @@ def main():
     out["deep_roofline"] = {"bound": "hbm", "achieved": deep_bytes / (ms_deep * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": deep_bytes / (ms_deep * 1e-3) / 1e9 / PEAK_HBM_GBS}
     out["reconstruct"] = time_reconstruct(torch, sb, L, shallow)
+    out["decode_merge"] = time_decode(torch, sb, L, K, shallow)
     # Eq. 15 on this layer: eviction alone (r1) and replacement alone (r2 r3), each on the full layer
     stored = int(shallow.out["n_codes_k"].sum().item() + shallow.out["n_codes_v"].sum().item())
     bits = 8 * torch.empty(0, dtype=sb.torch_dtype(L.dtype)).element_size()

@@ -182,9 +182,10 @@ spindle_status spindle_reconstruct(int32_t units, int32_t seq_len, int32_t head_
 
 /*
  * Workspace of spindle_decode_merge for desc (seq_len = new tokens per problem, at most 1024;
- * group_size is ignored).  Errors as check of desc; UNSUPPORTED beyond 1024 new tokens.
+ * group_size is ignored) and a codebook table of max_codes rows.  Errors: INVALID_ARG for a
+ * bad desc or max_codes < 1; UNSUPPORTED beyond 1024 new tokens.
  */
-spindle_status spindle_decode_workspace_bytes(const spindle_kv_desc *desc, size_t *bytes);
+spindle_status spindle_decode_workspace_bytes(const spindle_kv_desc *desc, int32_t max_codes, size_t *bytes);
 
 /*
  * Sec. "Similarity Based Token Replacement", the paragraph after Eq. 14: new tokens of one

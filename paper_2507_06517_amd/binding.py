@@ -65,7 +65,7 @@ def lib():
         L.spindle_layer_budgets.argtypes = [C.c_double, i32, i32, i32, C.c_double, C.POINTER(C.c_int32),
                                             C.POINTER(C.c_double)]
         L.spindle_reserve_ratio.argtypes = [C.c_int64, C.c_int64, C.c_int64, i32, i32, i32, C.POINTER(C.c_double)]
-        L.spindle_decode_workspace_bytes.argtypes = [C.POINTER(KvDesc), C.POINTER(sz)]
+        L.spindle_decode_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_decode_merge.argtypes = [C.POINTER(KvDesc), vp, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         for name in EXPORTS[:11]:
             getattr(L, name).restype = C.c_int
@@ -178,9 +178,9 @@ def spindle_reserve_ratio(kept_tokens, total_tokens, codebook_entries, head_dim=
     return tuple(out[:])
 
 
-def spindle_decode_workspace_bytes(desc: KvDesc) -> int:
+def spindle_decode_workspace_bytes(desc: KvDesc, max_codes: int) -> int:
     out = C.c_size_t(0)
-    _check(lib().spindle_decode_workspace_bytes(C.byref(desc), C.byref(out)))
+    _check(lib().spindle_decode_workspace_bytes(C.byref(desc), int(max_codes), C.byref(out)))
     return out.value
 
 
@@ -197,7 +197,7 @@ def decode_merge(X_new, dtype, theta, Cb, n_codes):
     import torch
     B, H, m, d = X_new.shape
     desc = KvDesc(B, H, 1, m, d, _DT[dtype])
-    nbytes = spindle_decode_workspace_bytes(desc)
+    nbytes = spindle_decode_workspace_bytes(desc, Cb.shape[2])
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X_new.device)
     out = dict(ref=torch.empty((B, H, m), dtype=torch.int32, device=X_new.device),
                mag=torch.empty((B, H, m), dtype=torch.float32, device=X_new.device),

@@ -4,7 +4,8 @@
 // the codebook.
 //
 // Kernels, enqueued on the caller's stream; u indexes one (batch, kv-head) problem of m new tokens:
-//   decode_match   magnitudes (Eq. 8) and, per new token, the stored entry of highest cosine
+//   decode_prep    magnitudes (Eq. 8) and the new tokens as doubles
+//   decode_match   per new token and slice of 512 stored entries, the entry of highest cosine
 //                  (Eq. 4) if it exceeds theta, lowest index on ties; everything in double
 //                  precision with the dimension-order sums the adjacency decision is defined by
 //   decode_build   one workgroup per problem: the unmatched tokens' adjacency matrix (Eq. 9) in
@@ -20,6 +21,8 @@ namespace {
 constexpr int kDecodeMax = 1024;     // new tokens per problem and call
 constexpr int kMatchTokens = 16;     // new tokens per workgroup of decode_match
 constexpr int kMatchThreads = 256;
+constexpr int kLaneEntries = 2;      // stored entries per lane of decode_match
+constexpr int kSliceEntries = kMatchThreads * kLaneEntries;
 constexpr int kBuildThreads = 1024;
 
 struct DecodeParams {
@@ -31,7 +34,11 @@ struct DecodeParams {
   int32_t *ref;         // [U][m]
   float *mag;           // [U][m]
   double *m64;          // workspace [U][m]
+  double *Xd;           // workspace [U][tiles][128][16] the new tokens as doubles
+  double *part_v;       // workspace [U][tiles][slices][16] best cosine of a token within a slice of entries
+  int *part_i;          //           and its entry, -1 if none exceeds theta
   int dtype, U, m, cap;
+  int tiles, slices;    // ceil(m / 16), ceil(cap / 512)
   double theta;
 };
 
@@ -48,19 +55,13 @@ __device__ __forceinline__ void take_better(double &bv, int &bi, double ov, int 
   }
 }
 
+// Double-precision copies of the new tokens, laid out for decode_match: [u][tile of 16 tokens]
+// [dimension][token in tile], tokens past m as zeros; magnitudes (Eq. 8, dimension-order sum).
 template <int DT>
-__global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p) {
+__global__ __launch_bounds__(kMatchThreads) void decode_prep(DecodeParams p) {
   typedef typename Elem<DT>::type T;
-  constexpr int per = 16 / sizeof(T);              // elements per 16-byte piece
-  constexpr int pieces = kHeadDim / per;
-  __shared__ __attribute__((aligned(16))) double xs[kHeadDim][kMatchTokens];   // [dimension][token]
-  __shared__ double ms[kMatchTokens];
-  __shared__ double red_v[kMatchThreads / kWave][kMatchTokens];
-  __shared__ int red_i[kMatchThreads / kWave][kMatchTokens];
-  const int u = blockIdx.y, a0 = blockIdx.x * kMatchTokens, tid = threadIdx.x;
-  int nc = p.n_codes[u];
-  nc = nc < 0 ? 0 : (nc > p.cap ? p.cap : nc);
-
+  __shared__ double xs[kHeadDim][kMatchTokens + 1];
+  const int u = blockIdx.y, tile = blockIdx.x, a0 = tile * kMatchTokens, tid = threadIdx.x;
   for (int i = tid; i < kMatchTokens * kHeadDim; i += kMatchThreads) {
     const int tok = i / kHeadDim, dim = i % kHeadDim;
     double v = 0.0;
@@ -68,52 +69,83 @@ __global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p) {
     xs[dim][tok] = v;
   }
   __syncthreads();
-  if (tid < kMatchTokens) {
+  double *dst = p.Xd + ((size_t)u * p.tiles + tile) * (kHeadDim * kMatchTokens);
+  for (int i = tid; i < kMatchTokens * kHeadDim; i += kMatchThreads) dst[i] = xs[i / kMatchTokens][i % kMatchTokens];
+  if (tid < kMatchTokens && a0 + tid < p.m) {
     double ss = 0.0;
     for (int dim = 0; dim < kHeadDim; ++dim) ss += xs[dim][tid] * xs[dim][tid];
     const double mg = sqrt(ss);
-    ms[tid] = mg;
-    if (a0 + tid < p.m) {
-      p.m64[(size_t)u * p.m + a0 + tid] = mg;
-      p.mag[(size_t)u * p.m + a0 + tid] = (float)mg;
-    }
+    p.m64[(size_t)u * p.m + a0 + tid] = mg;
+    p.mag[(size_t)u * p.m + a0 + tid] = (float)mg;
   }
-  __syncthreads();
+}
+
+// One workgroup = 16 new tokens x 512 stored entries, two entries per thread.  The tokens'
+// values are the same for every lane, so they are read through uniform loads (scalar
+// registers) and each lane streams its own entry row: per dimension 16 fused multiply-adds
+// against two conversions and one load per eight dimensions.  Every (token, entry) sum runs
+// over the dimensions in order, as the decision is defined.  The best entry of each token
+// within the slice goes to the workspace; decode_build combines the slices.
+template <int DT>
+__global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p, const double *__restrict__ Xd,
+                                                             const double *__restrict__ m64) {
+  typedef typename Elem<DT>::type T;
+  constexpr int per = 16 / sizeof(T);              // elements per 16-byte piece
+  constexpr int pieces = kHeadDim / per;
+  __shared__ double red_v[kMatchThreads / kWave][kMatchTokens];
+  __shared__ int red_i[kMatchThreads / kWave][kMatchTokens];
+  const int u = blockIdx.y, tile = blockIdx.x % p.tiles, slice = blockIdx.x / p.tiles, tid = threadIdx.x;
+  int nc = p.n_codes[u];
+  nc = nc < 0 ? 0 : (nc > p.cap ? p.cap : nc);
+  if (slice * kSliceEntries >= nc) return;          // decode_build only reads the slices below nc
+  const int a0 = tile * kMatchTokens;
+  const double *xt = Xd + ((size_t)u * p.tiles + tile) * (kHeadDim * kMatchTokens);
 
   double best[kMatchTokens];
   int bidx[kMatchTokens];
+  {
+    int c[kLaneEntries];
+    const u4 *row[kLaneEntries];
+    double acc[kLaneEntries][kMatchTokens], css[kLaneEntries];
 #pragma unroll
-  for (int t = 0; t < kMatchTokens; ++t) {
-    best[t] = 0.0;
-    bidx[t] = -1;
-  }
-  const char *Cu = p.C + (size_t)u * p.cap * (kHeadDim * sizeof(T));
-  for (int c = tid; c < nc; c += kMatchThreads) {
-    const u4 *row = reinterpret_cast<const u4 *>(Cu + (size_t)c * (kHeadDim * sizeof(T)));
-    double acc[kMatchTokens];
+    for (int e = 0; e < kLaneEntries; ++e) {
+      c[e] = slice * kSliceEntries + e * kMatchThreads + tid;
+      const int cr = c[e] < nc ? c[e] : nc - 1;     // lanes past the last entry recompute it and drop the result
+      row[e] = reinterpret_cast<const u4 *>(p.C + ((size_t)u * p.cap + cr) * (kHeadDim * sizeof(T)));
+      css[e] = 0.0;
 #pragma unroll
-    for (int t = 0; t < kMatchTokens; ++t) acc[t] = 0.0;
-    double css = 0.0;
+      for (int t = 0; t < kMatchTokens; ++t) acc[e][t] = 0.0;
+    }
     for (int pc = 0; pc < pieces; ++pc) {
-      const u4 v = row[pc];
-      const T *e = reinterpret_cast<const T *>(&v);
+      u4 v[kLaneEntries];
+#pragma unroll
+      for (int e = 0; e < kLaneEntries; ++e) v[e] = row[e][pc];
 #pragma unroll
       for (int j = 0; j < per; ++j) {
-        const double y = (double)Elem<DT>::to_float(e[j]);
-        css += y * y;
-        const double *xr = xs[pc * per + j];
+        const double *xr = xt + (pc * per + j) * kMatchTokens;
 #pragma unroll
-        for (int t = 0; t < kMatchTokens; ++t) acc[t] += xr[t] * y;
+        for (int e = 0; e < kLaneEntries; ++e) {
+          const double y = (double)Elem<DT>::to_float(reinterpret_cast<const T *>(&v[e])[j]);
+          css[e] += y * y;
+#pragma unroll
+          for (int t = 0; t < kMatchTokens; ++t) acc[e][t] += xr[t] * y;
+        }
       }
     }
-    const double cn = sqrt(css);
 #pragma unroll
     for (int t = 0; t < kMatchTokens; ++t) {
-      const double den = ms[t] * cn;
-      const double cs = den > 0.0 ? acc[t] / den : 0.0;
-      if (cs > p.theta && (bidx[t] < 0 || cs > best[t])) {   // c ascends: the first of equal values stays
-        best[t] = cs;
-        bidx[t] = c;
+      best[t] = 0.0;
+      bidx[t] = -1;
+    }
+#pragma unroll
+    for (int e = 0; e < kLaneEntries; ++e) {        // ascending entry index: the first of equal values stays
+      const double cn = sqrt(css[e]);
+#pragma unroll
+      for (int t = 0; t < kMatchTokens; ++t) {
+        const double ma = a0 + t < p.m ? m64[(size_t)u * p.m + a0 + t] : 0.0;
+        const double den = ma * cn;
+        const double cs = den > 0.0 ? acc[e][t] / den : 0.0;
+        if (c[e] < nc && cs > p.theta) take_better(best[t], bidx[t], cs, c[e]);
       }
     }
   }
@@ -134,11 +166,13 @@ __global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p) {
     }
   }
   __syncthreads();
-  if (tid < kMatchTokens && a0 + tid < p.m) {
+  if (tid < kMatchTokens) {
     double bv = red_v[0][tid];
     int bi = red_i[0][tid];
     for (int w = 1; w < kMatchThreads / kWave; ++w) take_better(bv, bi, red_v[w][tid], red_i[w][tid]);
-    p.ref[(size_t)u * p.m + a0 + tid] = bi;
+    const size_t at = (((size_t)u * p.tiles + tile) * p.slices + slice) * kMatchTokens + tid;
+    p.part_v[at] = bv;
+    p.part_i[at] = bi;
   }
 }
 
@@ -178,9 +212,18 @@ __global__ __launch_bounds__(kBuildThreads) void decode_build(DecodeParams p) {
   int32_t *ref = p.ref + (size_t)u * m;
   const double *m64 = p.m64 + (size_t)u * m;
 
-  // unmatched tokens in input order
+  // best stored entry of each token over the slices (ascending, so ties stay with the lower
+  // index), then the unmatched tokens in input order
   {
-    const bool un = tid < m && ref[tid] < 0;
+    int mine = -1;
+    if (tid < m) {
+      const int used = (nc + kSliceEntries - 1) / kSliceEntries;
+      const size_t at = (((size_t)u * p.tiles + tid / kMatchTokens) * p.slices) * kMatchTokens + tid % kMatchTokens;
+      double bv = 0.0;
+      for (int sl = 0; sl < used; ++sl) take_better(bv, mine, p.part_v[at + (size_t)sl * kMatchTokens], p.part_i[at + (size_t)sl * kMatchTokens]);
+      ref[tid] = mine;
+    }
+    const bool un = tid < m && mine < 0;
     const unsigned long long mk = __ballot(un);
     if (lane == 0) wave_sum[wave] = __popcll(mk);
     __syncthreads();
@@ -319,8 +362,25 @@ spindle_status check_decode(const spindle_kv_desc *desc) {
   return SPINDLE_OK;
 }
 
-size_t decode_workspace(const spindle_kv_desc *desc) {
-  return align_up((size_t)desc->batch * desc->n_kv_heads * desc->seq_len * sizeof(double), 256);
+// Carves the workspace (or only sizes it when `ws` is null).
+size_t decode_carve(const spindle_kv_desc *desc, int cap, void *ws, DecodeParams *p) {
+  const size_t U = (size_t)desc->batch * desc->n_kv_heads;
+  const int tiles = (desc->seq_len + kMatchTokens - 1) / kMatchTokens;
+  const int slices = (cap + kSliceEntries - 1) / kSliceEntries;
+  Carver cv(ws);
+  double *m64 = cv.take<double>(U * desc->seq_len);
+  double *Xd = cv.take<double>(U * tiles * kHeadDim * kMatchTokens);
+  double *pv = cv.take<double>(U * tiles * slices * kMatchTokens);
+  int *pi = cv.take<int>(U * tiles * slices * kMatchTokens);
+  if (p) {
+    p->m64 = m64;
+    p->Xd = Xd;
+    p->part_v = pv;
+    p->part_i = pi;
+    p->tiles = tiles;
+    p->slices = slices;
+  }
+  return cv.total();
 }
 
 }  // namespace
@@ -328,11 +388,12 @@ size_t decode_workspace(const spindle_kv_desc *desc) {
 
 using namespace spindle;
 
-extern "C" spindle_status spindle_decode_workspace_bytes(const spindle_kv_desc *desc, size_t *bytes) {
+extern "C" spindle_status spindle_decode_workspace_bytes(const spindle_kv_desc *desc, int32_t max_codes, size_t *bytes) {
   if (!bytes) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "bytes is NULL");
   spindle_status s = check_decode(desc);
   if (s != SPINDLE_OK) return s;
-  *bytes = decode_workspace(desc);
+  if (max_codes < 1) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "max_codes must be >= 1");
+  *bytes = decode_carve(desc, max_codes, nullptr, nullptr);
   return SPINDLE_OK;
 }
 
@@ -348,8 +409,8 @@ extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, cons
     SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "X_new, C, n_codes, n_found, ref, mag and workspace are required");
   if ((reinterpret_cast<uintptr_t>(X_new) | reinterpret_cast<uintptr_t>(C) | reinterpret_cast<uintptr_t>(workspace)) & 15)
     SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-  if (workspace_bytes < decode_workspace(desc))
-    SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, decode_workspace(desc));
+  const size_t need = decode_carve(desc, max_codes, nullptr, nullptr);
+  if (workspace_bytes < need) SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, need);
   hipStream_t st = static_cast<hipStream_t>(stream);
   DecodeParams p;
   p.X = static_cast<const char *>(X_new);
@@ -359,21 +420,25 @@ extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, cons
   p.n_matched = n_matched;
   p.ref = ref;
   p.mag = mag;
-  p.m64 = static_cast<double *>(workspace);
+  decode_carve(desc, max_codes, workspace, &p);
   p.dtype = desc->dtype;
   p.U = desc->batch * desc->n_kv_heads;
   p.m = desc->seq_len;
   p.cap = max_codes;
   p.theta = (double)theta;
-  const dim3 mg((p.m + kMatchTokens - 1) / kMatchTokens, p.U);
+  const dim3 pg(p.tiles, p.U), mg(p.tiles * p.slices, p.U);
   const size_t lds = build_lds_words(p.m) * sizeof(uint32_t);
 #define SPINDLE_DECODE_LAUNCH(DT)                                                                          \
   do {                                                                                                     \
     SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_build<DT>),                     \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                \
     {                                                                                                      \
+      ProfScope ps("decode_prep", st);                                                                     \
+      hipLaunchKernelGGL(decode_prep<DT>, pg, dim3(kMatchThreads), 0, st, p);                              \
+    }                                                                                                      \
+    {                                                                                                      \
       ProfScope ps("decode_match", st);                                                                    \
-      hipLaunchKernelGGL(decode_match<DT>, mg, dim3(kMatchThreads), 0, st, p);                             \
+      hipLaunchKernelGGL(decode_match<DT>, mg, dim3(kMatchThreads), 0, st, p, p.Xd, p.m64);                \
     }                                                                                                      \
     {                                                                                                      \
       ProfScope ps("decode_build", st);                                                                    \

@@ -125,4 +125,4 @@ def test_compress_calls_reject_bad_arguments_before_any_launch(sb):
     assert decode(wsb=16) == 3
     assert decode(d=sb.KvDesc(1, 2, 1, 1025, 128, sb.F16)) == 2
     assert decode(d=sb.KvDesc(1, 2, 1, 64, 64, sb.F16)) == 2
-    assert sb.spindle_decode_workspace_bytes(dd) >= 2 * 64 * 8
+    assert sb.spindle_decode_workspace_bytes(dd, 16) >= 2 * 64 * 8 * 129

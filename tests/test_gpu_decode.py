@@ -132,5 +132,5 @@ def test_rejects_bad_arguments():
     from paper_2507_06517_amd import binding as sb
     d = sb.KvDesc(1, 2, 1, 2000, 128, sb.F16)
     with pytest.raises(sb.SpindleError) as e:
-        sb.spindle_decode_workspace_bytes(d)
+        sb.spindle_decode_workspace_bytes(d, 64)
     assert e.value.code == 2
