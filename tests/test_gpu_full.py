@@ -145,3 +145,37 @@ def test_eviction_then_codebook_on_the_kept_tokens(oracle):
     stored = int(g["n_codes_k"].sum() + g["n_codes_v"].sum())
     r1, r2, r3, r = sb.spindle_reserve_ratio(2 * H * L.budget, 2 * H * l, stored, d, 16, 16)
     assert r1 == L.budget / l and 0 < r2 <= 256 / L.budget and abs(r - r1 * r2 * (d + 2) / d) < 1e-15
+
+
+def test_unfolded_gqa_then_one_codebook_per_kv_head(oracle):
+    # The alternative for grouped-query models (Sec. "Attention Weight Based Token Eviction", last
+    # paragraph): K and V are repeated once per query head, every query head evicts on its own
+    # attention, and the codebook over the unfolded copies of a KV head removes the repetition
+    # again (copies have cosine 1).  Both entry points are used as they are: the eviction with a
+    # group size of one on the repeated tensors, the codebook on the concatenated kept rows.
+    L = wl.config2(0)
+    B, H, l, d = L.K.shape
+    hn, budget, cap = L.group_size, 512, 640
+    Kr, Vr = np.repeat(L.K, hn, axis=1), np.repeat(L.V, hn, axis=1)
+    un = wl.Layer(L.dtype, Kr, Vr, L.Qw, 1, L.window, L.pool, budget, cap)
+    p64, kept64 = parity.oracle_deep(oracle, un)
+    kept, Ko, Vo, sc = parity.gpu_deep(un)
+    rep = {}
+    for q in range(H * hn):
+        parity.check_deep_unit(p64[0, q], kept64[0, q], sc[0, q], kept[0, q], L.window, l, rep)
+    assert not rep, "ambiguous selections would make the two codebooks start from different rows"
+    folded = wl.Layer(L.dtype, np.ascontiguousarray(Ko[:, :, :budget]).reshape(B, H, hn * budget, d),
+                      np.ascontiguousarray(Vo[:, :, :budget]).reshape(B, H, hn * budget, d), L.Qw, hn, L.window,
+                      L.pool, budget, cap)
+    g = parity.gpu_shallow(folded, cap)
+    shared = []
+    for t, X, theta in (("k", L.K, L.theta_k), ("v", L.V, L.theta_v)):
+        for h in range(H):
+            rows = np.concatenate([kept64[0, h * hn + j] for j in range(hn)])
+            o = parity.check_shallow_unit(oracle, wl.to_f64(X[0, h][rows], L.dtype), theta, cap, L.dtype, g, t, 0, h)
+            # copies of one token kept by several query heads end up in the same entry
+            first = {}
+            for pos, r in zip(rows, o["ref"]):
+                assert first.setdefault(int(pos), int(r)) == int(r)
+            shared.append(len(rows) - len(first))
+    assert max(shared) > 0, "the query heads of a group should agree on some tokens"
