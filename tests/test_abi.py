@@ -126,3 +126,15 @@ def test_compress_calls_reject_bad_arguments_before_any_launch(sb):
     assert decode(d=sb.KvDesc(1, 2, 1, 1025, 128, sb.F16)) == 2
     assert decode(d=sb.KvDesc(1, 2, 1, 64, 64, sb.F16)) == 2
     assert sb.spindle_decode_workspace_bytes(dd, 16) >= 2 * 64 * 8 * 129
+
+
+def test_missing_library_raises_instead_of_falling_back(sb, monkeypatch, tmp_path):
+    # there is no CPU path: without the built library every product call must fail loudly
+    monkeypatch.setattr(sb, "_lib", None)
+    monkeypatch.setattr(sb, "LIB_PATH", str(tmp_path / "libspindle.so"))
+    with pytest.raises(FileNotFoundError):
+        sb.lib()
+    with pytest.raises(FileNotFoundError):
+        sb.spindle_deep_workspace_bytes(sb.KvDesc(1, 8, 4, 4096, 128, sb.F16), 32)
+    with pytest.raises(FileNotFoundError):
+        sb.spindle_layer_budgets(0.5, 4096, 32, 8)

@@ -55,3 +55,15 @@ def test_config2_shapes_and_cluster_cosines():
 def test_config3_budgets_taper():
     b = [wl.config3_budget(i) for i in range(8, 32)]
     assert b[0] == 2048 and b[-1] == 256 and all(x >= y for x, y in zip(b, b[1:]))
+
+
+def test_decode_case_mixes_known_and_new_directions():
+    pre, new = wl.decode_case(1, "f16", B=1, H=2, n_prefill=300, m=96, novel_frac=0.3)
+    assert pre.shape == (1, 2, 300, 128) and new.shape == (1, 2, 96, 128) and pre.dtype == np.float16
+    pre2, new2 = wl.decode_case(1, "f16", B=1, H=2, n_prefill=300, m=96, novel_frac=0.3)
+    assert np.array_equal(pre, pre2) and np.array_equal(new, new2)
+    P, N = wl.to_f64(pre[0, 0], "f16"), wl.to_f64(new[0, 0], "f16")
+    P /= np.linalg.norm(P, axis=1, keepdims=True)
+    N /= np.linalg.norm(N, axis=1, keepdims=True)
+    near = (N @ P.T).max(axis=1) > 0.98
+    assert 0.5 < near.mean() < 0.85          # most later tokens resemble a prefill token, the novel ones none
