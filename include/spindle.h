@@ -255,10 +255,13 @@ spindle_status spindle_reserve_ratio(int64_t kept_tokens, int64_t total_tokens, 
 /* ------------------------------------------------------------------------- */
 
 /*
- * enable != 0: every kernel the library launches from now on is bracketed by a pair of
- * HIP events recorded on the stream it is launched on; enable == 0 stops recording.
- * Either call discards the records collected so far.  Process-wide; not meant to be
- * switched while another thread is inside a compress call.
+ * enable = 1: every kernel the library launches from now on is bracketed by a pair of HIP
+ * events recorded on the stream it is launched on; enable = 2: only the similarity kernel of
+ * spindle_compress_shallow ("shallow_gram") is; enable = 0 stops recording.  An event between
+ * two kernels of a stream costs about 10 us of idle time on the GPU, so mode 1 lengthens a
+ * step by some 5 % and is meant for breakdowns, mode 2 (two events per call) for measuring the
+ * dominant kernel inside a timed run.  Every call discards the records collected so far.
+ * Process-wide; not meant to be switched while another thread is inside a compress call.
  */
 spindle_status spindle_profile(int32_t enable);
 

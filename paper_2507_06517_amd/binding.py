@@ -209,8 +209,9 @@ def decode_merge(X_new, dtype, theta, Cb, n_codes):
     return out
 
 
-def spindle_profile(enable: bool) -> None:
-    _check(lib().spindle_profile(1 if enable else 0))
+def spindle_profile(mode) -> None:
+    """0/False: off; 1/True: HIP events around every kernel; 2: around the similarity kernel only."""
+    _check(lib().spindle_profile(int(mode)))
 
 
 def spindle_profile_read(max_records: int = 4096):

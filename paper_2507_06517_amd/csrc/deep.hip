@@ -16,7 +16,7 @@ namespace spindle {
 namespace {
 
 constexpr int kStageKeys = 128;      // keys per LDS stage
-constexpr int kStagesPerBlock = 4;   // keys per block = 512
+constexpr int kStagesPerBlock = 8;   // keys per block = 1024
 constexpr int kKeysPerBlock = kStageKeys * kStagesPerBlock;
 constexpr int kDeepThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;

@@ -37,7 +37,7 @@ struct ProfRec {
 };
 static std::mutex g_prof_mu;
 static std::vector<ProfRec> g_prof;
-static bool g_prof_on = false;
+static int g_prof_mode = 0;             // 0 off, 1 every kernel, 2 only the similarity kernel
 
 static void prof_clear() {
   for (ProfRec &r : g_prof) {
@@ -48,7 +48,8 @@ static void prof_clear() {
 }
 
 ProfScope::ProfScope(const char *name, hipStream_t s) : idx(-1), st(s) {
-  if (!g_prof_on) return;
+  if (g_prof_mode == 0) return;
+  if (g_prof_mode == 2 && strcmp(name, "shallow_gram") != 0) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   ProfRec r;
   strncpy(r.name, name, sizeof(r.name) - 1);
@@ -71,7 +72,7 @@ ProfScope::~ProfScope() {
 extern "C" spindle_status spindle_profile(int32_t enable) {
   std::lock_guard<std::mutex> lk(spindle::g_prof_mu);
   spindle::prof_clear();
-  spindle::g_prof_on = enable != 0;
+  spindle::g_prof_mode = enable == 2 ? 2 : (enable != 0 ? 1 : 0);
   return SPINDLE_OK;
 }
 
