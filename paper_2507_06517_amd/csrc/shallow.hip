@@ -13,7 +13,7 @@
 //   shallow_edge_lists  degrees (Eq. 10) and neighbour lists from those records
 //   shallow_mirror  lower triangle of G by bit transposition     } only when the caller wants G,
 //   shallow_lists   degrees and neighbour lists from the rows of G } or the records do not suffice
-//   merge_onehop, merge_twohop, merge_update, merge_reset
+//   merge_onehop, merge_twohop, merge_update
 //                   the first rounds of the greedy highest-degree codebook construction
 //                   (Eq. 11-13) in its exact parallel form, one launch per phase
 //   shallow_merge   the remaining rounds, one workgroup per problem
@@ -55,8 +55,13 @@ constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad (shallow_prep)
 constexpr int kStageBytes = kStageCols * 256;   // staged tokens: unpadded rows, 16-byte pieces swizzled
 
 constexpr int kSegCap = 512;      // edges a wave may record per chunk (64 rows x 1024 columns)
-constexpr int kCounters = 16;     // ints per ut
-enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4, C_ROUNDS = 5 };
+constexpr int kCounters = 32;     // ints per ut
+// Grid round r reads the list length C_ALIVE0 + r and builds C_ALIVE0 + r + 1, and has its own
+// candidate and dying counters, so that nothing has to be cleared between the rounds; the
+// slots 6..15 hold the phase timings of the tail kernel.
+enum { C_ALIVE0 = 0, C_ALIVE1 = 1, C_CAND = 2, C_DYING = 3, C_PICKS = 4, C_ROUNDS = 5,
+       C_ALIVE2 = 16, C_CAND1 = 17, C_DYING1 = 18 };
+__host__ __device__ constexpr int alive_slot(int round) { return round < 2 ? C_ALIVE0 + round : C_ALIVE2; }
 
 struct ShallowParams {
   const char *X[2];        // input tensors [U][n][128] in `dtype` (index = tensor slot)
@@ -637,13 +642,11 @@ __device__ __forceinline__ uint32_t transpose_stage(uint32_t x, int st, uint32_t
   return r;
 }
 
-__global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p, int force) {
-  extern __shared__ __attribute__((aligned(16))) uint32_t mtile[];   // [1024][kMirrorPitch]
-  if (!force && *p.need_full == 0) return;         // sparse graph: the lists came from the edge records
+__device__ __forceinline__ void mirror_half_tile(const ShallowParams &p, uint32_t *mtile, int item) {
   const int n = p.n, Wp = p.Wp;
   const int T = (n + 1023) >> 10, npairs = T * (T - 1) / 2;
-  // blocks b and b + 8 are the two halves of one tile
-  const int q = (blockIdx.x >> 4) * 8 + (blockIdx.x & 7), ha = (blockIdx.x >> 3) & 1;
+  // items b and b + 8 are the two halves of one tile
+  const int q = (item >> 4) * 8 + (item & 7), ha = (item >> 3) & 1;
   if (q >= p.UT * npairs) return;
   const int ut = q / npairs, pair = q % npairs;
   int TI = (int)((1.f + sqrtf(1.f + 8.f * (float)pair)) * 0.5f);
@@ -721,6 +724,18 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
   }
 }
 
+// The launch is a fixed number of workgroups that walk over the half tiles (the grid is a
+// multiple of 16, so the two halves of a tile stay on one XCD): when the gate is closed, which
+// is the usual case, the launch costs a few hundred workgroups that exit at once.
+__global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p, int force, int items) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t mtile[];   // [1024][kMirrorPitch]
+  if (!force && *p.need_full == 0) return;         // sparse graph: the lists came from the edge records
+  for (int item = blockIdx.x; item < items; item += gridDim.x) {
+    mirror_half_tile(p, mtile, item);
+    __syncthreads();
+  }
+}
+
 // ---------------------------------------------------------------- exact fix-up
 __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
   const int ut = blockIdx.y;                         // all problems side by side: each list is short
@@ -752,11 +767,10 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
 // bytes per token instead of the whole bitmap row.  Denser rows keep using the bitmap.
 constexpr int kListCap = 256;
 
-__global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force) {
-  if (!force && *p.need_full == 0) return;         // sparse graph: done by shallow_edge_lists
-  const int ut = blockIdx.y, n = p.n, Wp = p.Wp;
+__device__ __forceinline__ void lists_of_rows(const ShallowParams &p, int ut, int group) {
+  const int n = p.n, Wp = p.Wp;
   const int lane = lane_id(), wave = threadIdx.x >> 6;
-  const int row0 = (blockIdx.x * 4 + wave) * 4;
+  const int row0 = (group * 4 + wave) * 4;
   constexpr int kHold = 8;                           // 16-byte pieces of a row a lane keeps: rows of up to 65536 bits
   for (int v = row0; v < row0 + 4 && v < n; ++v) {
     const u4 *row = reinterpret_cast<const u4 *>(p.G + ((size_t)ut * n + v) * Wp);
@@ -803,6 +817,13 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force)
       }
     }
   }
+}
+
+// Fixed-size launch like shallow_mirror: the workgroups walk over the groups of 16 rows.
+__global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force) {
+  if (!force && *p.need_full == 0) return;         // sparse graph: done by shallow_edge_lists
+  const int groups = (p.n + 15) / 16;
+  for (int group = blockIdx.x; group < groups; group += gridDim.x) lists_of_rows(p, blockIdx.y, group);
 }
 
 // ---------------------------------------------------------------- lists from edge records
@@ -929,6 +950,7 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
 constexpr int kMergeThreads = 1024;
 constexpr int kSegW = 8;                 // lanes that share one row
 constexpr int kGridRounds = 2;
+static_assert(kGridRounds <= 2, "alive_slot and the per-round counters cover two grid rounds");
 constexpr int kPhaseThreads = 256;
 constexpr int kKeysInLds = 36 * 1024;   // tokens whose keys fit in LDS next to the other buffers
 
@@ -1172,15 +1194,15 @@ __device__ __forceinline__ void phase_recount(const ShallowParams &p, size_t bas
   }
 }
 
-__device__ __forceinline__ MergeView global_view(const ShallowParams &p, int ut) {
+__device__ __forceinline__ MergeView global_view(const ShallowParams &p, int ut, int round) {
   MergeView w;
   const size_t base = (size_t)ut * p.n;
   int *cnt = p.counters + (size_t)ut * kCounters;
   w.key = p.key + base;
   w.dead = reinterpret_cast<uint32_t *>(p.gone8 + (size_t)ut * p.n16);
-  w.n_alive = cnt + C_ALIVE0;   // the grid kernels address the two alive counters themselves
-  w.n_cand = cnt + C_CAND;
-  w.n_dying = cnt + C_DYING;
+  w.n_alive = cnt + alive_slot(round);
+  w.n_cand = cnt + (round ? C_CAND1 : C_CAND);
+  w.n_dying = cnt + (round ? C_DYING1 : C_DYING);
   w.n_picks = cnt + C_PICKS;
   w.seg = (blockIdx.x * blockDim.x + threadIdx.x) / kSegW;
   w.nsegs = gridDim.x * blockDim.x / kSegW;
@@ -1196,9 +1218,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, i
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   const int ut = blockIdx.y;
   const size_t base = (size_t)ut * p.n;
-  MergeView w = global_view(p, ut);
-  const int *cnt = p.counters + (size_t)ut * kCounters;
-  const int nalive = cnt[round & 1];
+  MergeView w = global_view(p, ut, round);
+  const int nalive = *w.n_alive;
   if ((int)(blockIdx.x * blockDim.x / kSegW) >= nalive) return;      // block-uniform: no work for this block
   if (keys_in_lds) {
     if ((p.n & 3) == 0) {                             // rows of the key array are then 16-byte aligned
@@ -1212,10 +1233,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, i
   }
   phase_onehop(p, base, w, (round & 1 ? p.alive2 : p.alive) + base, nalive);
 }
-__global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p) {
+__global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p, int round) {
   const int ut = blockIdx.y;
-  const MergeView w = global_view(p, ut);
-  phase_twohop<true, 4>(p, (size_t)ut * p.n, w, p.counters[(size_t)ut * kCounters + C_CAND]);
+  const MergeView w = global_view(p, ut, round);
+  phase_twohop<true, 4>(p, (size_t)ut * p.n, w, *w.n_cand);
 }
 // End of a grid round.  Tokens marked dead get key 0; every other token of the list counts
 // its neighbours that are not dead (its new degree, Eq. 13: with most tokens leaving in the
@@ -1227,7 +1248,7 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
   const int ut = blockIdx.y, lane = lane_id(), n = p.n;
   const size_t base = (size_t)ut * n;
   int *cnt = p.counters + (size_t)ut * kCounters;
-  const int nalive = cnt[round & 1];
+  const int nalive = cnt[alive_slot(round)];
   const int seg = (blockIdx.x * blockDim.x + threadIdx.x) / kSegW, nsegs = gridDim.x * blockDim.x / kSegW;
   const int sl = threadIdx.x & (kSegW - 1);
   if ((int)(blockIdx.x * blockDim.x / kSegW) >= nalive) return;
@@ -1277,7 +1298,7 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
     if (threadIdx.x == 0) {
       int t = 0;
       for (int q = 0; q < kPhaseThreads / kWave; ++q) t += wave_total[q];
-      block_at = t ? atomicAdd(&cnt[(round & 1) ^ 1], t) : 0;
+      block_at = t ? atomicAdd(&cnt[alive_slot(round + 1)], t) : 0;
     }
     __syncthreads();
     int at = block_at;
@@ -1290,16 +1311,6 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
     __syncthreads();                                 // wave_total is rewritten by the next trip
   }
 }
-// between rounds: the counters of the finished round start again at zero
-__global__ void merge_reset(ShallowParams p, int round) {
-  const int ut = blockIdx.x * blockDim.x + threadIdx.x;
-  if (ut >= p.UT) return;
-  int *cnt = p.counters + (size_t)ut * kCounters;
-  cnt[round & 1] = 0;
-  cnt[C_CAND] = 0;
-  cnt[C_DYING] = 0;
-}
-
 template <int DT>
 __device__ __forceinline__ void emit_code(const ShallowParams &p, int ut, int vert, int r) {
   typedef typename Elem<DT>::type T;
@@ -1364,7 +1375,7 @@ __global__ __launch_bounds__(kMergeThreads) void shallow_merge(ShallowParams p) 
       w.dead[i] = word;
     }
   }
-  if (tid == 0) { sh_n[0] = cnt[kGridRounds & 1]; sh_n[1] = 0; sh_n[2] = 0; sh_n[3] = cnt[C_PICKS]; }
+  if (tid == 0) { sh_n[0] = cnt[alive_slot(kGridRounds)]; sh_n[1] = 0; sh_n[2] = 0; sh_n[3] = cnt[C_PICKS]; }
   __syncthreads();
   MERGE_TICK(0)
 
@@ -1926,11 +1937,13 @@ extern "C" spindle_status spindle_compress_shallow(
       SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_mirror),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMirrorLds));
       ProfScope ps("shallow_mirror", st);
-      hipLaunchKernelGGL(shallow_mirror, dim3(16 * ((p.UT * npairs + 7) / 8)), dim3(kMirrorThreads), kMirrorLds, st, p, force);
+      const int items = 16 * ((p.UT * npairs + 7) / 8);
+      hipLaunchKernelGGL(shallow_mirror, dim3(items < 512 ? items : 512), dim3(kMirrorThreads), kMirrorLds, st, p, force, items);
     }
     SPINDLE_HIP(hipGetLastError());
     { ProfScope ps("shallow_lists", st);
-    hipLaunchKernelGGL(shallow_lists, dim3((n + 15) / 16, p.UT), dim3(256), 0, st, p, force); }
+    const int groups = (n + 15) / 16;
+    hipLaunchKernelGGL(shallow_lists, dim3(groups < 128 ? groups : 128, p.UT), dim3(256), 0, st, p, force); }
   }
   {
     int gx = (n + 4 * (kPhaseThreads / kSegW) - 1) / (4 * (kPhaseThreads / kSegW));
@@ -1949,9 +1962,8 @@ extern "C" spindle_status spindle_compress_shallow(
     for (int round = 0; round < kGridRounds; ++round) {
       ProfScope ps("shallow_merge_grid", st);
       hipLaunchKernelGGL(merge_onehop, dim3(ox, p.UT), dim3(kMergeThreads), key_lds, st, p, round, keys_in_lds);
-      hipLaunchKernelGGL(merge_twohop, pg, dim3(kPhaseThreads), 0, st, p);
+      hipLaunchKernelGGL(merge_twohop, pg, dim3(kPhaseThreads), 0, st, p, round);
       hipLaunchKernelGGL(merge_update, pg, dim3(kPhaseThreads), dead_lds, st, p, round);
-      hipLaunchKernelGGL(merge_reset, dim3((p.UT + 255) / 256), dim3(256), 0, st, p, round);
     }
   }
   const size_t merge_lds = n <= kKeysInLds ? ((size_t)((n + 3) & ~3) + (n + 31) / 32) * sizeof(uint32_t) : 0;
