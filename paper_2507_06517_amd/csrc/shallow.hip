@@ -55,6 +55,7 @@ constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad (shallow_prep)
 constexpr int kStageBytes = kStageCols * 256;   // staged tokens: unpadded rows, 16-byte pieces swizzled
 
 constexpr int kSegCap = 512;      // edges a wave may record per chunk (64 rows x 1024 columns)
+constexpr int kFixBucket = 2048;  // pairs decided in double precision that one row panel can take
 constexpr int kCounters = 32;     // ints per ut
 // Grid round r reads the list length C_ALIVE0 + r and builds C_ALIVE0 + r + 1, and has its own
 // candidate and dying counters, so that nothing has to be cleared between the rounds; the
@@ -87,8 +88,9 @@ struct ShallowParams {
   // row panel, wave): segment ((ut * nJc + J) * nI + I) * 4 + w, kSegCap entries
   uint32_t *edges;
   unsigned *ecount;        // entries of each segment
-  uint32_t *fedges;        // [UT][fix_cap] pairs shallow_fixup found adjacent, row << 16 | column
-  unsigned *fecount;       // [UT]
+  uint32_t *fedges;        // [UT][panels][kFixBucket] pairs shallow_fixup found adjacent, row << 16 | column,
+                           //     filed under the 256-row panel of each end whose list they extend
+  unsigned *fecount;       // [UT][panels]
   unsigned *need_full;     // [1] an edge segment ran full or a row has more neighbours than a list holds:
                            //     degrees and lists are then taken from the complete bitmap
   unsigned fix_cap;        // per ut
@@ -749,14 +751,31 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
     const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
     const bool adj = cos64(p, ut, a, b) > theta;
     if (adj) atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
-    // ... and as a record for the neighbour lists (one counter update per wave)
-    const unsigned long long mk = __ballot(adj);
-    if (mk) {
-      const int lane = lane_id();
-      unsigned at = 0;
-      if (lane == __builtin_ctzll(mk)) at = atomicAdd(p.fecount + ut, (unsigned)__popcll(mk));
-      at = __shfl(at, __builtin_ctzll(mk));
-      if (adj) p.fedges[(size_t)ut * p.fix_cap + at + __popcll(mk & ((1ull << lane) - 1ull))] = e;
+    // ... and as a record for the neighbour lists, filed under the panel of the row; a pair of
+    // two different 1024-token tiles was only evaluated in this orientation, so it also
+    // extends the list of its column
+    // (consecutive pairs of the list mostly share their panels, and same-address atomics are
+    // served one at a time: one counter update per wave and panel)
+    const int nI = (p.n + kPanelRows - 1) / kPanelRows, lane = lane_id();
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int end = k == 0 ? b / kPanelRows : a / kPanelRows;
+      const bool want = adj && (k == 0 || (a >> 10) != (b >> 10));
+      unsigned long long todo = __ballot(want);
+      while (todo) {                                   // wave-uniform
+        const int leader = __builtin_ctzll(todo);
+        const int which = __shfl(end, leader);
+        const unsigned long long same = __ballot(want && end == which) & todo;
+        const size_t bucket = (size_t)ut * nI + which;
+        unsigned at = 0;
+        if (lane == leader) at = atomicAdd(p.fecount + bucket, (unsigned)__popcll(same));
+        at = __shfl(at, leader) + (unsigned)__popcll(same & ((1ull << lane) - 1ull));
+        if ((same >> lane) & 1ull) {
+          if (at < (unsigned)kFixBucket) p.fedges[bucket * kFixBucket + at] = e;
+          else atomicOr(p.need_full, 1u);
+        }
+        todo &= ~same;
+      }
     }
   }
 }
@@ -894,15 +913,16 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
     }
   }
   {
-    // pairs decided in double precision: (row, column) records of the whole problem
-    const unsigned fn = p.fecount[ut];
-    const int fc = (int)(fn < p.fix_cap ? fn : p.fix_cap);
-    const uint32_t *fe = p.fedges + (size_t)ut * p.fix_cap;
+    // pairs decided in double precision that have an end in this panel
+    const size_t bucket = (size_t)ut * nI + I;
+    const unsigned fn = p.fecount[bucket];
+    const int fc = (int)(fn < (unsigned)kFixBucket ? fn : (unsigned)kFixBucket);
+    const uint32_t *fe = p.fedges + bucket * kFixBucket;
     for (int i = tid; i < fc; i += kEdgeThreads) {
       const uint32_t rec = fe[i];
       const int a = (int)(rec >> 16), b = (int)(rec & 0xFFFFu);
       if (a >= row0 && a < row0 + kPanelRows) add(a, b);
-      if ((a >> 10) != (b >> 10) && b >= row0 && b < row0 + kPanelRows) add(b, a);   // other tile: recorded once
+      if ((a >> 10) != (b >> 10) && b >= row0 && b < row0 + kPanelRows) add(b, a);   // other tile: evaluated once
     }
   }
   __syncthreads();
@@ -1770,6 +1790,12 @@ struct ShallowLayout {
   size_t bytes;
 };
 
+// 32-bit words at the end of the workspace that every call clears before use.
+size_t zero_words(int UT, int n) {
+  const size_t nchunk = (size_t)((n + kChunkCols - 1) / kChunkCols), nI = (size_t)((n + kPanelRows - 1) / kPanelRows);
+  return (size_t)UT * kCounters + 4 + 2 * (size_t)UT + (size_t)UT * nchunk + (size_t)UT * nI;
+}
+
 size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   Carver cv(ws);
   const size_t N = (size_t)UT * n;
@@ -1800,7 +1826,7 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.ccand = cv.take<uint2>(N * 2 * kCandCap);
   p.fix_cap = (unsigned)(32 * (size_t)n > 4096 ? 32 * (size_t)n : 4096);
   p.fix = cv.take<uint32_t>((size_t)UT * p.fix_cap);
-  p.fedges = cv.take<uint32_t>((size_t)UT * p.fix_cap);
+  p.fedges = cv.take<uint32_t>((size_t)UT * ((n + kPanelRows - 1) / kPanelRows) * kFixBucket);
   {
     const size_t nI = (size_t)((n + kPanelRows - 1) / kPanelRows), nJc = (size_t)((n + kChunkCols - 1) / kChunkCols);
     p.edges = cv.take<uint32_t>((size_t)UT * nJc * nI * 4 * kSegCap);
@@ -1808,16 +1834,16 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   }
   // everything that must start at zero sits together at the end:
   // counters [UT][kCounters], ovf_count, fix_overflow, need_full + 1 spare, fix_count [UT], ovf_cnt [UT],
-  // fecount [UT], echunk [UT][chunks]
+  // echunk [UT][chunks], fecount [UT][panels]
   const size_t nchunk = (size_t)((n + kChunkCols - 1) / kChunkCols);
-  p.counters = cv.take<int>((size_t)UT * kCounters + 4 + 3 * (size_t)UT + (size_t)UT * nchunk);
+  p.counters = cv.take<int>(zero_words(UT, n));
   int *tail = p.counters ? p.counters + (size_t)UT * kCounters : nullptr;
   p.ovf_count = reinterpret_cast<unsigned *>(tail);
   p.fix_overflow = reinterpret_cast<unsigned *>(tail ? tail + 1 : nullptr);
   p.fix_count = reinterpret_cast<unsigned *>(tail ? tail + 4 : nullptr);
   p.ovf_cnt = reinterpret_cast<unsigned *>(tail ? tail + 4 + UT : nullptr);
-  p.fecount = reinterpret_cast<unsigned *>(tail ? tail + 4 + 2 * (size_t)UT : nullptr);
-  p.echunk = reinterpret_cast<unsigned *>(tail ? tail + 4 + 3 * (size_t)UT : nullptr);
+  p.echunk = reinterpret_cast<unsigned *>(tail ? tail + 4 + 2 * (size_t)UT : nullptr);
+  p.fecount = reinterpret_cast<unsigned *>(tail ? tail + 4 + 2 * (size_t)UT + (size_t)UT * nchunk : nullptr);
   p.need_full = reinterpret_cast<unsigned *>(tail ? tail + 2 : nullptr);
   return cv.total();
 }
@@ -1907,7 +1933,7 @@ extern "C" spindle_status spindle_compress_shallow(
     adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
   }
   // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = (size_t)p.UT * kCounters + 4 + 3 * (size_t)p.UT + (size_t)p.UT * ((n + kChunkCols - 1) / kChunkCols);
+  const size_t nzero = zero_words(p.UT, n);
   const size_t cwords = (size_t)U * max_codes * kHeadDim * dtype_bytes(p.dtype) / 4;
   hipLaunchKernelGGL(shallow_init, dim3(1024), dim3(256), 0, st, p, nzero, cwords, T);
 
