@@ -389,18 +389,27 @@ __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p, int v
       const uint32_t dmask = (1u << w) - 1u;
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
-      for (int a0 = 0; a0 < lc; a0 += kSelThreads) {
-        const int a = a0 + tid;
-        const uint32_t x = a < lc ? pooled[a] : 0u;
-        const bool in = a < lc && (bits_left == 32 || (x >> bits_left) == (prefix >> bits_left));
-        const int d = (int)((x >> shift) & dmask);
-        // the digit of the first lane that takes part is counted once for all lanes that share it
-        const unsigned long long act = __ballot(in);
-        if (act) {
-          const int d0 = __shfl(d, __builtin_ctzll(act));
-          const unsigned long long same = __ballot(in && d == d0);
-          if (lane == __builtin_ctzll(act)) atomicAdd(&hist[d0], __popcll(same));
-          if (in && d != d0) atomicAdd(&hist[d], 1);
+      constexpr int kAtOnce = 4;                        // independent keys per thread and trip
+      for (int a0 = 0; a0 < lc; a0 += kAtOnce * kSelThreads) {
+        uint32_t x[kAtOnce];
+#pragma unroll
+        for (int q = 0; q < kAtOnce; ++q) {
+          const int a = a0 + q * kSelThreads + tid;
+          x[q] = a < lc ? pooled[a] : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < kAtOnce; ++q) {
+          const int a = a0 + q * kSelThreads + tid;
+          const bool in = a < lc && (bits_left == 32 || (x[q] >> bits_left) == (prefix >> bits_left));
+          const int d = (int)((x[q] >> shift) & dmask);
+          if (in) {
+            // scores of one unit crowd into few digits: the digit of the first lane that takes
+            // part is counted once for all lanes that share it
+            const int d0 = __builtin_amdgcn_readfirstlane(d);
+            const unsigned long long same = __ballot(d == d0);
+            if (d != d0) atomicAdd(&hist[d], 1);
+            else if (lane == __builtin_ctzll(same)) atomicAdd(&hist[d0], __popcll(same));
+          }
         }
       }
       __syncthreads();
