@@ -137,6 +137,11 @@ __global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p, co
       best[t] = 0.0;
       bidx[t] = -1;
     }
+    // Few (token, entry) pairs come near theta, and a double-precision division costs as much as
+    // twenty multiply-adds: the quotient is only formed where the dot product is not already
+    // clearly below theta times the norms (for theta >= 0; a quotient that close to theta from
+    // below cannot round up past it).
+    const double low = p.theta >= 0.0 ? p.theta * (1.0 - 1e-12) : -INFINITY;
 #pragma unroll
     for (int e = 0; e < kLaneEntries; ++e) {        // ascending entry index: the first of equal values stays
       const double cn = sqrt(css[e]);
@@ -144,8 +149,10 @@ __global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p, co
       for (int t = 0; t < kMatchTokens; ++t) {
         const double ma = a0 + t < p.m ? m64[(size_t)u * p.m + a0 + t] : 0.0;
         const double den = ma * cn;
-        const double cs = den > 0.0 ? acc[e][t] / den : 0.0;
-        if (c[e] < nc && cs > p.theta) take_better(best[t], bidx[t], cs, c[e]);
+        if (c[e] < nc && (!(den > 0.0) || acc[e][t] > low * den)) {
+          const double cs = den > 0.0 ? acc[e][t] / den : 0.0;
+          if (cs > p.theta) take_better(best[t], bidx[t], cs, c[e]);
+        }
       }
     }
   }
@@ -154,11 +161,13 @@ __global__ __launch_bounds__(kMatchThreads) void decode_match(DecodeParams p, co
   for (int t = 0; t < kMatchTokens; ++t) {
     double bv = best[t];
     int bi = bidx[t];
+    if (__ballot(bi >= 0) != 0) {                    // wave-uniform: most tokens find nothing in most slices
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const double ov = __shfl_xor(bv, o);
-      const int oi = __shfl_xor(bi, o);
-      take_better(bv, bi, ov, oi);
+      for (int o = 32; o > 0; o >>= 1) {
+        const double ov = __shfl_xor(bv, o);
+        const int oi = __shfl_xor(bi, o);
+        take_better(bv, bi, ov, oi);
+      }
     }
     if (lane == 0) {
       red_v[wave][t] = bv;
