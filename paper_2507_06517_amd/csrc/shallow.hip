@@ -1003,13 +1003,18 @@ __device__ __forceinline__ Nbrs load_nbrs(const ShallowParams &p, size_t base, i
 template <typename F>
 __device__ __forceinline__ void for_nbrs(const ShallowParams &p, const Nbrs &r, int sl, F f) {
   if (r.cnt0 >= 0) {
+    // most rows are short: every fourth entry the wave checks whether any lane has more
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
+    for (int j = 0; j < 16; ++j) {
+      if (j > 0 && (j & 3) == 0 && __ballot(j < r.cnt0) == 0) break;
       if (j < r.cnt0) f((int)((r.q[j >> 3][(j >> 1) & 3] >> (16 * (j & 1))) & 0xFFFFu));
+    }
     if (r.cnt1 > 0) {
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
+      for (int j = 0; j < 16; ++j) {
+        if (j > 0 && (j & 3) == 0 && __ballot(j < r.cnt1) == 0) break;
         if (j < r.cnt1) f((int)((r.q[2 + (j >> 3)][(j >> 1) & 3] >> (16 * (j & 1))) & 0xFFFFu));
+      }
     }
   } else {
     for (int w4 = sl; w4 < p.Wp / 4; w4 += kSegW) {
@@ -1027,13 +1032,69 @@ __device__ __forceinline__ void for_nbrs(const ShallowParams &p, const Nbrs &r, 
   }
 }
 
-__device__ __forceinline__ uint32_t seg_max(uint32_t v) {   // over a segment
+// Lane exchanges inside an 8-lane segment by DPP (no LDS round trip): the two quad
+// permutations, then the mirror of the eight lanes, which pairs each lane with one of the
+// other quad.
+static_assert(kSegW == 8, "the segment reductions are written for eight lanes");
+__device__ __forceinline__ uint32_t seg_xchg(uint32_t v, int step) {
+  return step == 0 ? (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false)     // quad_perm [1,0,3,2]
+         : step == 1 ? (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false)   // quad_perm [2,3,0,1]
+                     : (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false); // row_half_mirror
+}
+__device__ __forceinline__ uint32_t seg_max(uint32_t v) {   // over a segment, result in every lane
 #pragma unroll
-  for (int o = kSegW / 2; o > 0; o >>= 1) {
-    const uint32_t x = __shfl_xor(v, o);
+  for (int step = 0; step < 3; ++step) {
+    const uint32_t x = seg_xchg(v, step);
     v = x > v ? x : v;
   }
   return v;
+}
+__device__ __forceinline__ int seg_sum(int v) {             // over a segment, result in every lane
+#pragma unroll
+  for (int step = 0; step < 3; ++step) v += (int)seg_xchg((uint32_t)v, step);
+  return v;
+}
+
+// The same walk four entries at a time: f4(b, ok) gets four neighbour slots of this lane
+// (ok[t] false: slot t is past the end of the lane's part and b[t] is not a token) and can issue
+// its look-ups together, so that a row costs a few memory round trips instead of one per
+// entry; the wave stops as soon as no lane has entries left.  f1(b) handles one neighbour of
+// a dense row (bitmap walk).
+template <typename F4, typename F1>
+__device__ __forceinline__ void for_nbrs4(const ShallowParams &p, const Nbrs &r, int sl, F4 f4, F1 f1) {
+  if (r.cnt0 >= 0) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int cnt = half ? r.cnt1 : r.cnt0;
+      if (__ballot(cnt > 0) == 0) break;               // wave-uniform
+#pragma unroll
+      for (int j0 = 0; j0 < 16; j0 += 4) {
+        if (__ballot(j0 < cnt) == 0) break;            // wave-uniform
+        int b[4];
+        bool ok[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int j = j0 + t;
+          ok[t] = j < cnt;
+          b[t] = (int)((r.q[2 * half + (j >> 3)][(j >> 1) & 3] >> (16 * (j & 1))) & 0xFFFFu);
+        }
+        f4(b, ok);
+      }
+    }
+  } else {
+    for (int w4 = sl; w4 < p.Wp / 4; w4 += kSegW) {
+      const u4 q = r.row[w4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        uint32_t bits = q[j];
+        while (bits) {
+          const int t = __builtin_ctz(bits);
+          bits &= bits - 1;
+          f1((w4 * 4 + j) * 32 + t);
+        }
+      }
+    }
+  }
 }
 
 // Where the state of one problem lives for the running kernel (LDS or global memory), and
@@ -1068,7 +1129,18 @@ __device__ __forceinline__ void phase_onehop(const ShallowParams &p, size_t base
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       uint32_t mk = on[k] ? w.key[vv[k]] : 0;          // a token is its own neighbour
-      if (on[k]) for_nbrs(p, r[k], w.sl, [&](int b) { const uint32_t kk = w.key[b]; mk = kk > mk ? kk : mk; });
+      if (on[k]) {
+        const int self = vv[k];
+        for_nbrs4(p, r[k], w.sl,
+                  [&](const int *b, const bool *ok) {
+                    uint32_t kk[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) kk[t] = w.key[ok[t] ? b[t] : self];   // own key again: harmless
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) mk = kk[t] > mk ? kk[t] : mk;
+                  },
+                  [&](int b) { const uint32_t kk = w.key[b]; mk = kk > mk ? kk : mk; });
+      }
       m[k] = seg_max(mk);
     }
 #pragma unroll
@@ -1118,9 +1190,27 @@ __device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base
       uint32_t mk = 0;
       int rk = 0;                                    // remaining neighbours in this lane's part
       // remaining = key != 0 (keys only change in the later phases of the round)
-      if (on[k]) for_nbrs(p, r[k], w.sl, [&](int b) {
-        if (w.key[b] != 0) { const uint32_t q = m1[b]; mk = q > mk ? q : mk; ++rk; }
-      });
+      if (on[k]) {
+        const int self = uv[k];
+        for_nbrs4(p, r[k], w.sl,
+                  [&](const int *b, const bool *ok) {
+                    uint32_t kk[4], q[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) kk[t] = w.key[ok[t] ? b[t] : self];
+                    bool there[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                      there[t] = ok[t] && kk[t] != 0;
+                      q[t] = m1[there[t] ? b[t] : self];
+                    }
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                      if (there[t]) { mk = q[t] > mk ? q[t] : mk; ++rk; }
+                  },
+                  [&](int b) {
+                    if (w.key[b] != 0) { const uint32_t q = m1[b]; mk = q > mk ? q : mk; ++rk; }
+                  });
+      }
       m[k] = seg_max(mk);
       rem[k] = rk;
     }
@@ -1182,7 +1272,17 @@ __device__ __forceinline__ void phase_degree(const ShallowParams &p, size_t base
     };
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-      if (on[k]) for_nbrs(p, r[k], w.sl, drop);
+      if (on[k])
+        for_nbrs4(p, r[k], w.sl,
+                  [&](const int *b, const bool *ok) {
+                    uint32_t word[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) word[t] = w.dead[(ok[t] ? b[t] : 0) >> 5];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                      if (ok[t] && !((word[t] >> (b[t] & 31)) & 1u)) atomicSub(&w.key[b[t]], 1u << 16);
+                  },
+                  drop);
   }
 }
 
@@ -1206,9 +1306,17 @@ __device__ __forceinline__ void phase_recount(const ShallowParams &p, size_t bas
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       int c = 0;
-      if (on[k]) for_nbrs(p, r[k], w.sl, [&](int b) { c += !((w.dead[b >> 5] >> (b & 31)) & 1u); });
+      if (on[k])
+        for_nbrs4(p, r[k], w.sl,
+                  [&](const int *b, const bool *ok) {
+                    uint32_t word[4];
 #pragma unroll
-      for (int o = kSegW / 2; o > 0; o >>= 1) c += __shfl_xor(c, o);
+                    for (int t = 0; t < 4; ++t) word[t] = w.dead[(ok[t] ? b[t] : 0) >> 5];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) c += ok[t] && !((word[t] >> (b[t] & 31)) & 1u);
+                  },
+                  [&](int b) { c += !((w.dead[b >> 5] >> (b & 31)) & 1u); });
+      c = seg_sum(c);
       if (on[k] && w.sl == 0) w.key[vv[k]] = ((uint32_t)c << 16) | (uint32_t)(0xFFFF - vv[k]);
     }
   }
@@ -1304,9 +1412,17 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       int c = 0;
-      if (live[k]) for_nbrs(p, r[k], sl, [&](int b) { c += !dead[b]; });
+      if (live[k])
+        for_nbrs4(p, r[k], sl,
+                  [&](const int *b, const bool *ok) {
+                    uint8_t gone[4];
 #pragma unroll
-      for (int o = kSegW / 2; o > 0; o >>= 1) c += __shfl_xor(c, o);
+                    for (int t = 0; t < 4; ++t) gone[t] = dead[ok[t] ? b[t] : 0];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) c += ok[t] && !gone[t];
+                  },
+                  [&](int b) { c += !dead[b]; });
+      c = seg_sum(c);
       const bool lead = live[k] && sl == 0;
       if (lead) key[vv[k]] = ((uint32_t)c << 16) | (uint32_t)(0xFFFF - vv[k]);
       mk[k] = __ballot(lead);
