@@ -785,6 +785,10 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
 // neighbour indices as a compact uint16 list, so that the merge rounds touch a few hundred
 // bytes per token instead of the whole bitmap row.  Denser rows keep using the bitmap.
 constexpr int kListCap = 256;
+// Where the p-th neighbour of a row is stored: lane sl of the 8-lane segment that later walks
+// the row reads the 16 entries from sl * 16 on (of each half of 128), so the neighbours are dealt
+// out to the lanes in turn and a short row occupies all eight lanes instead of the first one.
+__host__ __device__ constexpr int list_slot(int p) { return (p & ~127) | ((p & 7) << 4) | ((p & 127) >> 3); }
 
 __device__ __forceinline__ void lists_of_rows(const ShallowParams &p, int ut, int group) {
   const int n = p.n, Wp = p.Wp;
@@ -820,7 +824,8 @@ __device__ __forceinline__ void lists_of_rows(const ShallowParams &p, int ut, in
       if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = deg;
     }
     if (deg <= kListCap) {
-      uint16_t *dst = p.nbr + ((size_t)ut * n + v) * kListCap + (incl - c);
+      uint16_t *dst = p.nbr + ((size_t)ut * n + v) * kListCap;
+      int at = incl - c;                               // neighbours in the words of lower lanes
 #pragma unroll
       for (int i = 0; i < kHold; ++i) {
         const int w4 = lane + i * kWave;
@@ -830,7 +835,7 @@ __device__ __forceinline__ void lists_of_rows(const ShallowParams &p, int ut, in
           while (bits) {
             const int t = __builtin_ctz(bits);
             bits &= bits - 1;
-            *dst++ = (uint16_t)((w4 * 4 + j) * 32 + t);
+            dst[list_slot(at++)] = (uint16_t)((w4 * 4 + j) * 32 + t);
           }
         }
       }
@@ -875,8 +880,8 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
   auto add = [&](int row, int other) {
     const int r = row - row0;
     const int pos = atomicAdd(&cursor[r], 1);
-    if (pos < kEdgeLds) part[r][pos] = (uint16_t)other;
-    else if (pos < kListCap) lists[(size_t)r * kListCap + pos] = (uint16_t)other;
+    if (pos < kEdgeLds) part[r][list_slot(pos)] = (uint16_t)other;
+    else if (pos < kListCap) lists[(size_t)r * kListCap + list_slot(pos)] = (uint16_t)other;
   };
   const int nown = 4 * (nJc - Jm);                   // (chunk, wave) segments of this panel
   const int nin = 16 * Jm;                           // (panel, wave) segments of earlier tiles for this tile's chunk
@@ -930,7 +935,8 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
   for (int k = tid; k < kPanelRows * (kEdgeLds / 8); k += kEdgeThreads) {
     const int r = k / (kEdgeLds / 8), piece = k % (kEdgeLds / 8);
     const int have = cursor[r] < kEdgeLds ? cursor[r] : kEdgeLds;
-    if (row0 + r < n && piece * 8 < have)
+    // piece = half of a lane's 16 entries: entries (piece >> 1) + 8 j for j = 8 (piece & 1) ...
+    if (row0 + r < n && have > (piece >> 1) + 64 * (piece & 1))
       *reinterpret_cast<u4 *>(lists + (size_t)r * kListCap + piece * 8) = *reinterpret_cast<const u4 *>(&part[r][piece * 8]);
   }
   if (tid < kPanelRows && row0 + tid < n) {
@@ -989,9 +995,11 @@ __device__ __forceinline__ Nbrs load_nbrs(const ShallowParams &p, size_t base, i
   r.q[0] = src[0];    // unconditional: the slot exists for every row, and the loads
   r.q[1] = src[1];    // then do not wait for the degree
   r.row = reinterpret_cast<const u4 *>(p.G + (base + v) * p.Wp);
-  const int c0 = d0 - sl * 16, c1 = d0 - 128 - sl * 16;
-  r.cnt0 = d0 <= kListCap ? (c0 < 0 ? 0 : (c0 > 16 ? 16 : c0)) : -1;
-  r.cnt1 = d0 <= kListCap ? (c1 < 0 ? 0 : (c1 > 16 ? 16 : c1)) : 0;
+  // entries sl, sl + 8, ... of each half belong to this lane (list_slot)
+  const int h0 = d0 < 128 ? d0 : 128, h1 = d0 - 128;
+  const int c0 = (h0 - sl + 7) >> 3, c1 = (h1 - sl + 7) >> 3;
+  r.cnt0 = d0 <= kListCap ? (c0 < 0 ? 0 : c0) : -1;
+  r.cnt1 = d0 <= kListCap && h1 > 0 ? (c1 < 0 ? 0 : c1) : 0;
   if (r.cnt1 > 0) {
     r.q[2] = src[16];
     r.q[3] = src[17];
@@ -1242,14 +1250,25 @@ __device__ __forceinline__ void phase_twohop(const ShallowParams &p, size_t base
         int at = 0;
         if (lane == kWave - 1) at = atomicAdd(w.n_dying, incl);
         at = __shfl(at, kWave - 1) + incl - mine;
-        if (picked) for_nbrs(p, r[k], w.sl, [&](int b) {
-          if (w.key[b] != 0) {
-            slot[b] = s;
-            if (kBytes) reinterpret_cast<uint8_t *>(w.dead)[b] = 1;
-            else atomicOr(&w.dead[b >> 5], 1u << (b & 31));
-            dying[at++] = b;
-          }
-        });
+        auto take = [&](int b) {
+          slot[b] = s;
+          if (kBytes) reinterpret_cast<uint8_t *>(w.dead)[b] = 1;
+          else atomicOr(&w.dead[b >> 5], 1u << (b & 31));
+          dying[at++] = b;
+        };
+        if (picked) {
+          const int self = uv[k];
+          for_nbrs4(p, r[k], w.sl,
+                    [&](const int *b, const bool *ok) {
+                      uint32_t kk[4];
+#pragma unroll
+                      for (int t = 0; t < 4; ++t) kk[t] = w.key[ok[t] ? b[t] : self];
+#pragma unroll
+                      for (int t = 0; t < 4; ++t)
+                        if (ok[t] && kk[t] != 0) take(b[t]);
+                    },
+                    [&](int b) { if (w.key[b] != 0) take(b); });
+        }
       }
     }
   }
