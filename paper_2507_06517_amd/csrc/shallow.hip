@@ -1380,10 +1380,112 @@ __global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, i
   }
   phase_onehop(p, base, w, (round & 1 ? p.alive2 : p.alive) + base, nalive);
 }
+// Two-hop phase of a grid round: one wave per candidate.  Candidates are few (hundreds per
+// problem) and have the longest lists, and every look-up here is a trip to L2: with four
+// slots per lane the whole list of a candidate is one look-up step for its keys and one
+// for their one-hop maxima, whatever its length.
 __global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p, int round) {
-  const int ut = blockIdx.y;
-  const MergeView w = global_view(p, ut, round);
-  phase_twohop<true, 4>(p, (size_t)ut * p.n, w, *w.n_cand);
+  const int ut = blockIdx.y, lane = lane_id();
+  const size_t base = (size_t)ut * p.n;
+  int *cnt = p.counters + (size_t)ut * kCounters;
+  const int ncand = cnt[round ? C_CAND1 : C_CAND];
+  int *n_dying = cnt + (round ? C_DYING1 : C_DYING), *n_picks = cnt + C_PICKS;
+  const uint32_t *key = p.key + base, *m1 = p.m1 + base;
+  const int *cand = p.cand + base;
+  int *slot = p.slot + base, *dying = p.dying + base, *pick_vert = p.pick_vert + base;
+  uint32_t *pick_key = p.pick_key + base;
+  uint8_t *gone = p.gone8 + (size_t)ut * p.n16;
+  const int wave0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nwaves = gridDim.x * blockDim.x / kWave;
+  for (int i = wave0; i < ncand; i += nwaves) {      // wave-uniform
+    const int u = cand[i];
+    const uint32_t ku = key[u];
+    const int d0 = p.deg0[base + u];
+    int b[4];
+    bool there[4] = {false, false, false, false};
+    uint32_t mk = 0;
+    int rk = 0;                                       // remaining neighbours in this lane's slots
+    const u4 *row = reinterpret_cast<const u4 *>(p.G + (base + u) * p.Wp);
+    if (d0 <= kListCap) {
+      const uint2 raw = *reinterpret_cast<const uint2 *>(p.nbr + (base + u) * kListCap + 4 * lane);
+      uint32_t kk[4], q[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int s = 4 * lane + t;                  // slot -> position in the list (inverse of list_slot)
+        const int at = (s & ~127) | ((s & 15) << 3) | ((s & 127) >> 4);
+        b[t] = (int)(((t < 2 ? raw.x : raw.y) >> (16 * (t & 1))) & 0xFFFFu);
+        there[t] = at < d0;
+        kk[t] = key[there[t] ? b[t] : u];
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        there[t] = there[t] && kk[t] != 0;           // remaining = key != 0 (keys change later in the round)
+        q[t] = m1[there[t] ? b[t] : u];
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        if (there[t]) { mk = q[t] > mk ? q[t] : mk; ++rk; }
+    } else {
+      for (int w4 = lane; w4 < p.Wp / 4; w4 += kWave) {
+        const u4 qw = row[w4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          uint32_t bits = qw[j];
+          while (bits) {
+            const int t = __builtin_ctz(bits);
+            bits &= bits - 1;
+            const int v = (w4 * 4 + j) * 32 + t;
+            if (key[v] != 0) { const uint32_t q = m1[v]; mk = q > mk ? q : mk; ++rk; }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const uint32_t x = __shfl_xor(mk, o);
+      mk = x > mk ? x : mk;
+    }
+    if (mk != ku) continue;                           // wave-uniform: not the largest key within two hops
+    int s = 0;
+    if (lane == 0) {
+      s = atomicAdd(n_picks, 1);
+      pick_key[s] = ku;
+      pick_vert[s] = u;
+    }
+    s = __shfl(s, 0);
+    int incl = rk;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int x = __shfl_up(incl, o);
+      if (lane >= o) incl += x;
+    }
+    int at = 0;
+    if (lane == kWave - 1) at = atomicAdd(n_dying, incl);
+    at = __shfl(at, kWave - 1) + incl - rk;
+    auto take = [&](int v) {
+      slot[v] = s;
+      gone[v] = 1;
+      dying[at++] = v;
+    };
+    if (d0 <= kListCap) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        if (there[t]) take(b[t]);
+    } else {
+      for (int w4 = lane; w4 < p.Wp / 4; w4 += kWave) {
+        const u4 qw = row[w4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          uint32_t bits = qw[j];
+          while (bits) {
+            const int t = __builtin_ctz(bits);
+            bits &= bits - 1;
+            const int v = (w4 * 4 + j) * 32 + t;
+            if (key[v] != 0) take(v);
+          }
+        }
+      }
+    }
+  }
 }
 // End of a grid round.  Tokens marked dead get key 0; every other token of the list counts
 // its neighbours that are not dead (its new degree, Eq. 13: with most tokens leaving in the
