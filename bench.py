@@ -2,7 +2,7 @@
 """Throughput of the prefill-time KV reduction pass on one MI355X.
 
 One step = one pass of the whole hot path over one layer of the 32k-context
-workload (benchmark configs[3]: Mistral-7B-shaped, 8 KV heads x 4 query heads,
+workload (the benchmark configuration configs[3]: Mistral-7B-shaped, 8 KV heads x 4 query heads,
 head_dim 128, seq_len 32768, fp16, clustered keys/values with drift):
   spindle_compress_deep    (window 64, pool 7, budget 2048)  and
   spindle_compress_shallow (K and V, theta 0.98 / 0.95, codebook cap 2048).

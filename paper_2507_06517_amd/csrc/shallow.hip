@@ -1380,10 +1380,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_onehop(ShallowParams p, i
   }
   phase_onehop(p, base, w, (round & 1 ? p.alive2 : p.alive) + base, nalive);
 }
-// Two-hop phase of a grid round: one wave per candidate.  Candidates are few (hundreds per
-// problem) and have the longest lists, and every look-up here is a trip to L2: with four
-// slots per lane the whole list of a candidate is one look-up step for its keys and one
-// for their one-hop maxima, whatever its length.
+// Two-hop phase of a grid round.  When candidates are few (hundreds per problem: they then
+// have the longest lists, and every look-up here is a trip to L2) a wave takes one candidate:
+// with four slots per lane its whole list is one look-up step for the keys and one for their
+// one-hop maxima, whatever its length.
 __global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p, int round) {
   const int ut = blockIdx.y, lane = lane_id();
   const size_t base = (size_t)ut * p.n;
@@ -1396,6 +1396,12 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p, i
   uint32_t *pick_key = p.pick_key + base;
   uint8_t *gone = p.gone8 + (size_t)ut * p.n16;
   const int wave0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nwaves = gridDim.x * blockDim.x / kWave;
+  if (ncand > 2 * nwaves) {
+    // many candidates (isolated tokens are all candidates): short lists, eight lanes per row
+    const MergeView w = global_view(p, ut, round);
+    phase_twohop<true, 4>(p, base, w, ncand);
+    return;
+  }
   for (int i = wave0; i < ncand; i += nwaves) {      // wave-uniform
     const int u = cand[i];
     const uint32_t ku = key[u];
