@@ -33,6 +33,23 @@ def test_without_adjacency_export(oracle, l, n_centroids):
     parity.check_shallow_layer(oracle, L, debug=False)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_graph_sweep(oracle, seed):
+    # graphs of many shapes (sparse to nearly complete, with and without drift and isolated
+    # tokens, sizes that are not tile multiples), each compared with the oracle's loop in full
+    rng = np.random.default_rng(1000 + seed)
+    l = int(rng.integers(40, 3000))
+    dtype = ("f16", "bf16", "f32")[seed % 3]
+    L = wl.small_random(100 + seed, dtype, B=1, H=2, l=l, lw=1, cap=l,
+                        n_centroids=int(rng.integers(1, 60)), noise_frac=float(rng.uniform(0.0, 0.6)),
+                        drift_sigma=float(rng.choice([0.0, 0.002, 0.006])))
+    L.theta_k = float(rng.choice([0.5, 0.8, 0.9, 0.95, 0.98, 0.995]))
+    L.theta_v = float(rng.choice([0.3, 0.7, 0.9, 0.97, 0.99]))
+    res, g = parity.check_shallow_layer(oracle, L, debug=bool(seed & 1))
+    parity.check_shallow_layer(oracle, L, cap=max(1, l // int(rng.integers(2, 40))), debug=False)
+    print("sweep", seed, dtype, l, L.theta_k, L.theta_v, [o["n_codes_uncapped"] for o in res], flush=True)
+
+
 def test_threshold_extremes_and_single_tensor(oracle):
     L = wl.small_random(8, "f16", B=1, H=1, l=200, lw=1, cap=200)
     L.theta_k, L.theta_v = 1.0, -1.5
