@@ -22,6 +22,22 @@ def test_small_ragged(oracle, dtype, l, lw, hn, pool, budget):
     parity.check_deep_layer(oracle, L)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_shape_sweep(oracle, seed):
+    # sequence lengths around the block and stage sizes of the kernels (128-key stages, 1024 keys
+    # per block), every window x group size up to the limit of 256 rows, odd pooling widths
+    rng = np.random.default_rng(2000 + seed)
+    hn = int(rng.choice([1, 2, 4, 8]))
+    lw = int(rng.choice([w for w in (1, 3, 16, 32, 64, 128, 256) if w * hn <= 256]))
+    l = lw + int(rng.choice([0, 1, 127, 128, 129, 1023, 1024, 1025, 2047, 3000, 5000]))
+    pool = int(rng.choice([1, 3, 7, 15, 31]))
+    budget = int(rng.integers(lw, l + 2))
+    dtype = ("f16", "bf16", "f32")[seed % 3]
+    L = wl.small_random(200 + seed, dtype, B=1, H=2, l=l, hn=hn, lw=lw, pool=pool, budget=budget)
+    rep = parity.check_deep_layer(oracle, L, norm=seed & 1)
+    print("sweep", seed, dtype, l, lw, hn, pool, budget, rep, flush=True)
+
+
 def test_norm_none_and_budget_edges(oracle):
     L = wl.small_random(4, "f16", B=1, H=2, l=600, hn=4, lw=32, pool=7, budget=100)
     parity.check_deep_layer(oracle, L, norm=1)
