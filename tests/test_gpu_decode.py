@@ -63,6 +63,23 @@ def test_decode_merge_sizes_and_types(oracle, dtype, m):
         assert any(o["n_matched"] > 0 for o in res) and any(o["n_found"] > k for o, k in zip(res, nc.ravel()))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_sweep(oracle, seed):
+    # later-token counts around the tile of 16, tables around the slice of 512 entries, loose and
+    # tight thresholds, few to many new directions
+    rng = np.random.default_rng(3000 + seed)
+    dtype = ("f16", "bf16", "f32")[seed % 3]
+    m = int(rng.choice([15, 16, 17, 100, 255, 513, 1000]))
+    theta = float(rng.choice([0.7, 0.9, 0.95, 0.98]))
+    n_pre = int(rng.choice([300, 700, 1500]))
+    pre, new = wl.decode_case(40 + seed, dtype, B=1, H=2, n_prefill=n_pre, m=m, n_centroids=int(rng.integers(5, 700)),
+                              novel_frac=float(rng.uniform(0.0, 0.8)), novel_centroids=int(rng.integers(1, 40)))
+    keep = int(rng.choice([511, 512, 513, 2000]))
+    Cb, nc = stored_codebooks(oracle, pre, dtype, theta, keep + int(rng.integers(0, m + 2)), [[keep, keep // 2]])
+    res, _, _ = run_and_check(oracle, new, Cb, nc, dtype, theta)
+    print("sweep", seed, dtype, m, theta, nc.ravel().tolist(), [(o["n_matched"], o["n_found"]) for o in res], flush=True)
+
+
 def test_empty_partial_and_full_codebooks(oracle):
     # unit 0: no stored entries (plain Alg. 1 on the new tokens); unit 1: half of the prefill's
     # entries; units 2, 3: all of them; then tables with two free rows and with none
