@@ -16,8 +16,15 @@ namespace spindle {
 namespace {
 
 constexpr int kStageKeys = 128;      // keys per LDS stage
-constexpr int kStagesPerBlock = 8;   // keys per block = 1024
-constexpr int kKeysPerBlock = kStageKeys * kStagesPerBlock;
+constexpr int kMaxStagesPerBlock = 8; // at most 1024 keys per block
+// Stages a block takes: as many as leave about one block per compute unit.  The fixed cost of
+// a block (query fragments, the merge of the chunk statistics) outweighs idle units only while
+// the grid still covers the chip.
+inline int stages_per_block(int U, int l) {
+  const long total = (long)U * ((l + kStageKeys - 1) / kStageKeys);
+  const long s = total / 256;
+  return s < 1 ? 1 : (s > kMaxStagesPerBlock ? kMaxStagesPerBlock : (int)s);
+}
 constexpr int kDeepThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -27,6 +34,7 @@ struct DeepParams {
   float2 *partial;     // [U][nchunks][Rpad] (max, sum) per chunk of keys
   float *scores;       // [U][lc] group-averaged accumulated attention
   int l, lc, lw, hn, R, Rpad, nchunks;
+  int stages;          // 128-key stages per block
   float sc2;           // scale * log2(e): logits are kept in base-2 units
   float inv_hn;
   int norm;
@@ -78,7 +86,7 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int g = lane >> 5, c = lane & 31;
   const int wr = wave % WR, wk = wave / WR;
-  const int key_begin = chunk * kKeysPerBlock;
+  const int key_begin = chunk * p.stages * kStageKeys;
   const int key_limit = ACCUM ? p.lc : p.l;   // keys at or beyond this index are not needed
   const char *Kunit = p.K + (size_t)u * p.l * M::kRowBytes;
   const char *Qunit = p.Q + (size_t)u * p.R * M::kRowBytes;
@@ -142,10 +150,10 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
   S::store(regs, smem);
   __syncthreads();
 
-  for (int s = 0; s < kStagesPerBlock; ++s) {
+  for (int s = 0; s < p.stages; ++s) {
     const int k0 = key_begin + s * kStageKeys;
     if (k0 >= key_limit) break;                       // uniform over the block
-    const bool more = (s + 1 < kStagesPerBlock) && (k0 + kStageKeys < key_limit);
+    const bool more = (s + 1 < p.stages) && (k0 + kStageKeys < key_limit);
     if (more) S::fetch(regs, Kunit, k0 + kStageKeys, key_limit);
 
     if (ACCUM && s > 0 && threadIdx.x < kStageKeys) {
@@ -518,7 +526,8 @@ struct DeepLayout {
 DeepLayout deep_layout(void *ws, int U, int l, int lw, int Rpad) {
   Carver cv(ws);
   DeepLayout L;
-  const int nchunks = (l + kKeysPerBlock - 1) / kKeysPerBlock;
+  const int keys = stages_per_block(U, l) * kStageKeys;
+  const int nchunks = (l + keys - 1) / keys;
   const int lc = l - lw;
   L.partial = cv.take<float2>((size_t)U * nchunks * Rpad);
   L.scores = cv.take<float>((size_t)U * (lc > 0 ? lc : 1));
@@ -541,7 +550,7 @@ spindle_status launch_passes(const DeepParams &p, int U, hipStream_t st) {
   { ProfScope ps("deep_stats", st);
   hipLaunchKernelGGL((deep_pass<DT, WR, false>), dim3(p.nchunks, U), dim3(kDeepThreads), smem_stats, st, p); }
   if (p.lc > 0) {
-    const int nacc = (p.lc + kKeysPerBlock - 1) / kKeysPerBlock;
+    const int nacc = (p.lc + p.stages * kStageKeys - 1) / (p.stages * kStageKeys);
     ProfScope ps("deep_accumulate", st);
     hipLaunchKernelGGL((deep_pass<DT, WR, true>), dim3(nacc, U), dim3(kDeepThreads), smem_acc, st, p);
   }
@@ -611,7 +620,8 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   p.partial = L.partial;
   p.scores = L.scores;
   p.l = l; p.lc = lc; p.lw = lw; p.hn = desc->group_size; p.R = R; p.Rpad = Rpad;
-  p.nchunks = (l + kKeysPerBlock - 1) / kKeysPerBlock;
+  p.stages = stages_per_block(U, l);
+  p.nchunks = (l + p.stages * kStageKeys - 1) / (p.stages * kStageKeys);
   p.sc2 = scale * kLog2e;
   p.inv_hn = 1.0f / (float)desc->group_size;
   p.norm = norm;
