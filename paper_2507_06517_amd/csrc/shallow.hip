@@ -54,7 +54,15 @@ constexpr int kGramThreads = 256;
 constexpr int kLdsRow = 272;      // fp16 row of 128 + 16 B pad (shallow_prep)
 constexpr int kStageBytes = kStageCols * 256;   // staged tokens: unpadded rows, 16-byte pieces swizzled
 
-constexpr int kSegCap = 512;      // edges a wave may record per chunk (64 rows x 1024 columns)
+// Edges a wave may record per chunk (64 rows x 1024 columns): what 32 MiB per problem allow,
+// between 512 (n = 32768: 16384 segments) and 4096 (short sequences, where a cluster of similar
+// tokens fills a larger share of every chunk).
+inline int seg_cap_for(int n) {
+  const long segs = 4L * ((n + 255) / 256) * ((n + 1023) / 1024);
+  long cap = (32L << 20) / (segs * 4);
+  cap = cap < 512 ? 512 : (cap > 4096 ? 4096 : cap);
+  return (int)(cap & ~63L);
+}
 constexpr int kFixBucket = 2048;  // pairs decided in double precision that one row panel can take
 constexpr int kCounters = 32;     // ints per ut
 // Grid round r reads the list length C_ALIVE0 + r and builds C_ALIVE0 + r + 1, and has its own
@@ -85,7 +93,8 @@ struct ShallowParams {
   unsigned *fix_count;     // [UT]
   unsigned *fix_overflow;  // [1] some list was full
   // set bits of the computed part of G as (row << 16 | column), one segment per (problem, chunk,
-  // row panel, wave): segment ((ut * nJc + J) * nI + I) * 4 + w, kSegCap entries
+  // row panel, wave): segment ((ut * nJc + J) * nI + I) * 4 + w, seg_cap entries
+  int seg_cap;             // entries per segment
   uint32_t *edges;
   unsigned *ecount;        // entries of each segment
   uint32_t *fedges;        // [UT][panels][kFixBucket] pairs shallow_fixup found adjacent, row << 16 | column,
@@ -570,7 +579,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     // graphs get their neighbour lists from these without another pass over G
     const int nJc = (n + kChunkCols - 1) / kChunkCols;
     const size_t seg = (((size_t)ut * nJc + J) * nI + I) * 4 + wave;
-    uint32_t *eseg = p.edges + seg * kSegCap;
+    uint32_t *eseg = p.edges + seg * p.seg_cap;
     int ecnt = 0;                                    // wave-uniform
     const unsigned long long below = (1ull << lane) - 1ull;
     for (int it = 0; it < 8; ++it) {
@@ -591,14 +600,14 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
           const int t = __builtin_ctz(w);
           v[j] = w & (w - 1);
           const int at = ecnt + __popcll(mk & below);
-          if (at < kSegCap) eseg[at] = ((uint32_t)(arow0 + r) << 16) | (uint32_t)(col_begin + piece * 128 + j * 32 + t);
+          if (at < p.seg_cap) eseg[at] = ((uint32_t)(arow0 + r) << 16) | (uint32_t)(col_begin + piece * 128 + j * 32 + t);
         }
         ecnt += __popcll(mk);
       }
     }
     if (lane == 0) {
-      p.ecount[seg] = (unsigned)(ecnt < kSegCap ? ecnt : kSegCap);
-      if (ecnt > kSegCap) atomicOr(p.need_full, 1u);
+      p.ecount[seg] = (unsigned)(ecnt < p.seg_cap ? ecnt : p.seg_cap);
+      if (ecnt > p.seg_cap) atomicOr(p.need_full, 1u);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);              // loads issued for stages past the chunk
@@ -900,8 +909,8 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
       const int Ip = own[u] ? I : kk >> 2;
       const size_t seg = (((size_t)ut * nJc + J) * nI + Ip) * 4 + (kk & 3);
       const unsigned cn = k < nown + nin ? p.ecount[seg] : 0u;
-      cnt[u] = cn < (unsigned)kSegCap ? (int)cn : kSegCap;
-      e[u] = p.edges + seg * kSegCap;
+      cnt[u] = cn < (unsigned)p.seg_cap ? (int)cn : p.seg_cap;
+      e[u] = p.edges + seg * p.seg_cap;
       most = cnt[u] > most ? cnt[u] : most;
     }
     for (int i0 = 0; i0 < most; i0 += kWave) {
@@ -2072,7 +2081,8 @@ size_t carve(ShallowParams &p, void *ws, int UT, int n) {
   p.fedges = cv.take<uint32_t>((size_t)UT * ((n + kPanelRows - 1) / kPanelRows) * kFixBucket);
   {
     const size_t nI = (size_t)((n + kPanelRows - 1) / kPanelRows), nJc = (size_t)((n + kChunkCols - 1) / kChunkCols);
-    p.edges = cv.take<uint32_t>((size_t)UT * nJc * nI * 4 * kSegCap);
+    p.seg_cap = seg_cap_for(n);
+    p.edges = cv.take<uint32_t>((size_t)UT * nJc * nI * 4 * p.seg_cap);
     p.ecount = cv.take<unsigned>((size_t)UT * nJc * nI * 4);
   }
   // everything that must start at zero sits together at the end:
