@@ -108,12 +108,22 @@ def time_decode(torch, sb, L, K, shallow, m=256, novel=0.25, reps=10):
     for name, t in recs:
         ms[name] = ms.get(name, 0.0) + t / reps
     total = sum(ms.values())
+    # the usual decode step: one token per head and call, a single launch
+    one = new[:, :, :1].contiguous()
+    sb.spindle_profile(True)
+    for _ in range(reps):
+        nc.copy_(stored)
+        sb.decode_merge(one, L.dtype, L.theta_k, Cb, nc)
+    torch.cuda.synchronize()
+    single = [t for name, t in sb.spindle_profile_read() if name == "decode_small"]
+    sb.spindle_profile(False)
     flop = 2.0 * L.head_dim * m * float(stored.sum().item())
     tf = flop / (ms["decode_match"] * 1e-3) / 1e12
     return {"new_tokens_per_head": m, "stored_entries": stored.cpu().numpy().ravel().tolist(),
             "merged_with_stored": out["n_matched"].cpu().numpy().ravel().tolist(),
             "entries_after": out["n_found"].cpu().numpy().ravel().tolist(),
             "kernel_ms": ms, "tokens_per_s": L.batch * L.n_kv_heads * m / (total * 1e-3),
+            "one_token_per_head_call_us": float(np.mean(single)) * 1e3,
             "roofline": {"kernel": "decode_match", "bound": "alu", "achieved": tf, "peak": PEAK_VALU_F64_TFLOPS,
                          "unit": "TFLOP/s", "frac": tf / PEAK_VALU_F64_TFLOPS}}
 

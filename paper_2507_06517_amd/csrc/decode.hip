@@ -11,6 +11,7 @@
 //   decode_build   one workgroup per problem: the unmatched tokens' adjacency matrix (Eq. 9) in
 //                  LDS, the greedy highest-degree loop (Eq. 10-13) as stated, new entries and
 //                  references
+//   decode_small   all of it in one launch when a call brings at most four tokens per problem
 #include <math.h>
 
 #include "common.h"
@@ -363,6 +364,195 @@ __global__ __launch_bounds__(kBuildThreads) void decode_build(DecodeParams p) {
   }
 }
 
+// The usual decode step brings one token per head (a few with speculative decoding): then
+// three launches cost more than the work.  One workgroup per problem does it all: the tokens
+// as doubles in LDS, every thread a few stored entries (same sums, same decision as
+// decode_match), a reduction over the workgroup, and Alg. 1 on the at most MT unmatched
+// tokens by the first wave (adjacency in one word per token, the loop as stated).
+constexpr int kSmallThreads = 1024;
+
+template <int DT, int MT>
+__global__ __launch_bounds__(kSmallThreads) void decode_small(DecodeParams p) {
+  typedef typename Elem<DT>::type T;
+  constexpr int per = 16 / sizeof(T), pieces = kHeadDim / per, kWaves = kSmallThreads / kWave;
+  __shared__ __attribute__((aligned(16))) double xs[kHeadDim][MT];
+  __shared__ double ms[MT];
+  __shared__ double red_v[kWaves][MT];
+  __shared__ int red_i[kWaves][MT];
+  __shared__ int ref_s[MT];
+  __shared__ uint32_t adjm[MT];
+  const int u = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6, m = p.m;
+  int nc = p.n_codes[u];
+  nc = nc < 0 ? 0 : (nc > p.cap ? p.cap : nc);
+  for (int i = tid; i < MT * kHeadDim; i += kSmallThreads) {
+    const int tok = i / kHeadDim, dim = i % kHeadDim;
+    xs[dim][tok] = tok < m ? (double)Elem<DT>::to_float(reinterpret_cast<const T *>(token_row<DT>(p, u, tok))[dim]) : 0.0;
+  }
+  __syncthreads();
+  if (tid < MT) {
+    double ss = 0.0;
+    for (int dim = 0; dim < kHeadDim; ++dim) ss += xs[dim][tid] * xs[dim][tid];
+    const double mg = sqrt(ss);
+    ms[tid] = mg;
+    if (tid < m) p.mag[(size_t)u * m + tid] = (float)mg;
+  }
+  __syncthreads();
+
+  double best[MT];
+  int bidx[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    best[t] = 0.0;
+    bidx[t] = -1;
+  }
+  const double low = p.theta >= 0.0 ? p.theta * (1.0 - 1e-12) : -INFINITY;   // see decode_match
+  for (int c = tid; c < nc; c += kSmallThreads) {   // ascending: the first of equal values stays
+    const u4 *row = reinterpret_cast<const u4 *>(p.C + ((size_t)u * p.cap + c) * (kHeadDim * sizeof(T)));
+    double acc[MT], css = 0.0;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = 0.0;
+    for (int pc = 0; pc < pieces; ++pc) {
+      const u4 v = row[pc];
+#pragma unroll
+      for (int j = 0; j < per; ++j) {
+        const double y = (double)Elem<DT>::to_float(reinterpret_cast<const T *>(&v)[j]);
+        css += y * y;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[t] += xs[pc * per + j][t] * y;
+      }
+    }
+    const double cn = sqrt(css);
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const double den = ms[t] * cn;
+      if (t < m && (!(den > 0.0) || acc[t] > low * den)) {
+        const double cs = den > 0.0 ? acc[t] / den : 0.0;
+        if (cs > p.theta) take_better(best[t], bidx[t], cs, c);
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    double bv = best[t];
+    int bi = bidx[t];
+    if (__ballot(bi >= 0) != 0) {
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const double ov = __shfl_xor(bv, o);
+        const int oi = __shfl_xor(bi, o);
+        take_better(bv, bi, ov, oi);
+      }
+    }
+    if (lane == 0) {
+      red_v[wave][t] = bv;
+      red_i[wave][t] = bi;
+    }
+  }
+  __syncthreads();
+  if (tid < MT) {
+    double bv = red_v[0][tid];
+    int bi = red_i[0][tid];
+    for (int w = 1; w < kWaves; ++w) take_better(bv, bi, red_v[w][tid], red_i[w][tid]);
+    ref_s[tid] = tid < m ? bi : 0;                   // slots past m count as matched
+    adjm[tid] = 0u;
+  }
+  __syncthreads();
+  if (wave != 0) return;
+
+  // the unmatched tokens, in input order, among themselves (Eq. 9-13)
+  const bool un = lane < m && ref_s[lane < MT ? lane : 0] < 0;
+  const unsigned long long mask = __ballot(un);
+  const int r = __popcll(mask);
+  int rest[MT];                                      // token of each unmatched position (wave-uniform)
+  {
+    unsigned long long left = mask;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      rest[i] = left ? __builtin_ctzll(left) : 0;
+      left &= left - 1;
+    }
+  }
+  for (int pair = lane; pair < MT * MT; pair += kWave) {
+    const int i = pair / MT, j = pair % MT;
+    if (i < j && j < r) {
+      const int a = rest[i], b = rest[j];
+      double acc = 0.0;
+      for (int dim = 0; dim < kHeadDim; ++dim) acc += xs[dim][a] * xs[dim][b];
+      const double den = ms[a] * ms[b];
+      const double cs = den > 0.0 ? acc / den : 0.0;
+      if (cs > p.theta) {
+        atomicOr(&adjm[i], 1u << j);
+        atomicOr(&adjm[j], 1u << i);
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_wave_barrier();
+  int rref[MT], picks[MT];
+  int npicks = 0;
+  {
+    uint32_t alive = r >= 32 ? 0xFFFFFFFFu : (1u << r) - 1u;
+    uint32_t rows[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      rows[i] = adjm[i] | (1u << i);                 // G_aa = 1
+      rref[i] = 0;
+      picks[i] = 0;
+    }
+    while (alive) {                                  // every lane runs the same tiny loop
+      int pick = 0, top = 0;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int d = (alive >> i) & 1u ? __popc(rows[i] & alive) : 0;
+        if (d > top) { top = d; pick = i; }          // strict: lowest index on ties
+      }
+      uint32_t leaving = 0;
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        if (i == pick) leaving = rows[i] & alive;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        if ((leaving >> i) & 1u) rref[i] = npicks;
+        if (i == npicks) picks[i] = pick;
+      }
+      alive &= ~leaving;
+      ++npicks;
+    }
+  }
+  const int room = p.cap - nc > 0 ? p.cap - nc : 0;
+  const int stored = npicks < room ? npicks : room;
+  if (lane < m) {
+    int out = ref_s[lane < MT ? lane : 0];
+    if (out < 0) {
+      const int pos = __popcll(mask & ((1ull << lane) - 1ull));
+      int rr = 0;
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        if (i == pos) rr = rref[i];
+      out = rr < room ? nc + rr : -1;
+    }
+    p.ref[(size_t)u * m + lane] = out;
+  }
+  T *Cu = reinterpret_cast<T *>(p.C) + (size_t)u * p.cap * kHeadDim;
+#pragma unroll
+  for (int j = 0; j < MT; ++j) {
+    if (j < stored) {
+      int tok = 0;
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        if (i == picks[j]) tok = rest[i];
+      const double mg = ms[tok];
+      for (int d = lane; d < kHeadDim; d += kWave)
+        Cu[(size_t)(nc + j) * kHeadDim + d] = Elem<DT>::from_float(mg > 0.0 ? (float)(xs[d][tok] / mg) : 0.f);
+    }
+  }
+  if (lane == 0) {
+    p.n_found[u] = nc + npicks;
+    p.n_codes[u] = nc + stored;
+    if (p.n_matched) p.n_matched[u] = m - r;
+  }
+}
+
 spindle_status check_decode(const spindle_kv_desc *desc) {
   spindle_status s = check_desc(desc);
   if (s != SPINDLE_OK) return s;
@@ -435,6 +625,16 @@ extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, cons
   p.m = desc->seq_len;
   p.cap = max_codes;
   p.theta = (double)theta;
+  if (p.m <= 4) {
+    ProfScope ps("decode_small", st);
+#define SPINDLE_DECODE_SMALL(DT) hipLaunchKernelGGL((decode_small<DT, 4>), dim3(p.U), dim3(kSmallThreads), 0, st, p)
+    if (p.dtype == SPINDLE_F16) SPINDLE_DECODE_SMALL(SPINDLE_F16);
+    else if (p.dtype == SPINDLE_BF16) SPINDLE_DECODE_SMALL(SPINDLE_BF16);
+    else SPINDLE_DECODE_SMALL(SPINDLE_F32);
+#undef SPINDLE_DECODE_SMALL
+    SPINDLE_HIP(hipGetLastError());
+    return SPINDLE_OK;
+  }
   const dim3 pg(p.tiles, p.U), mg(p.tiles * p.slices, p.U);
   const size_t lds = build_lds_words(p.m) * sizeof(uint32_t);
 #define SPINDLE_DECODE_LAUNCH(DT)                                                                          \

@@ -80,6 +80,24 @@ def test_decode_sweep(oracle, seed):
     print("sweep", seed, dtype, m, theta, nc.ravel().tolist(), [(o["n_matched"], o["n_found"]) for o in res], flush=True)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("m", [1, 2, 3, 4])
+def test_few_tokens_per_call(oracle, dtype, m):
+    # the usual decode step: one to four tokens per head, handled by a single launch.  Several
+    # draws, so that matched tokens, new directions that resemble each other and new directions
+    # that do not all occur; then a table with one free row and with none.
+    theta = 0.98
+    for seed in range(6):
+        pre, new = wl.decode_case(500 + 10 * m + seed, dtype, B=1, H=4, n_prefill=300, m=m, n_centroids=20,
+                                  novel_frac=0.5, novel_centroids=1 + seed % 2)
+        Cb, nc = stored_codebooks(oracle, pre, dtype, theta, 64, [[64, 64, 0, 3]])
+        res, _, _ = run_and_check(oracle, new, Cb, nc, dtype, theta)
+        k = int(nc[0, 0])
+        for spare in (1, 0):
+            small = np.ascontiguousarray(Cb[:, :1, :k + spare])
+            run_and_check(oracle, np.ascontiguousarray(new[:, :1]), small, nc[:, :1], dtype, theta)
+
+
 def test_empty_partial_and_full_codebooks(oracle):
     # unit 0: no stored entries (plain Alg. 1 on the new tokens); unit 1: half of the prefill's
     # entries; units 2, 3: all of them; then tables with two free rows and with none
