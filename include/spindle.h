@@ -2,7 +2,7 @@
  * spindle.h - C ABI of the MI355X (gfx950) prefill-time KV-cache reduction pass
  * of SpindleKV (arXiv 2507.06517).
  *
- * Two operations, each working on `batch * n_kv_heads` independent problems
+ * The operations, each working on `batch * n_kv_heads` independent problems
  * ("units") per call; fold layers into `batch` to process a stack in one call:
  *
  *   spindle_compress_deep     attention-weight token eviction
@@ -10,6 +10,10 @@
  *   spindle_compress_shallow  similarity codebook replacement
  *                             (Sec. "Similarity Based Token Replacement", Eq. 8-13, Alg. 1)
  *   spindle_reconstruct       codebook look-up and rescale (Eq. 14)
+ *   spindle_decode_merge      tokens generated later join the stored codebook or extend it
+ *                             (same section, the paragraph after Eq. 14)
+ *   spindle_layer_budgets, spindle_reserve_ratio
+ *                             host arithmetic: layer-wise budgets (Eq. 5-6), reserve ratio (Eq. 15)
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, contiguous in
