@@ -72,6 +72,37 @@ def test_knife_edge_pairs_are_decided_exactly(oracle):
     assert (np.abs(S - L.theta_k) < 1e-3).sum() > 1000                # the band is well populated
 
 
+def test_more_close_pairs_than_the_pair_list_holds(oracle):
+    # every pair of tokens has a cosine within a few 1e-3 of theta: far more pairs fall inside the
+    # fp16 guard band than the list of deferred pairs holds (32 n), so the library has to fall back
+    # to deciding the close pairs in place, tile by tile, and to lists built from the bitmap
+    rng = np.random.default_rng(77)
+    n, d, theta = 1200, 128, 0.98
+    c = rng.standard_normal(d)
+    c /= np.linalg.norm(c)
+    u = rng.standard_normal((n, d))
+    u -= np.outer(u @ c, c)
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    x = np.sqrt(theta) * c + np.sqrt(1 - theta) * u           # cos(x_a, x_b) = theta + (1 - theta) u_a.u_b
+    x *= rng.uniform(0.5, 2.0, (n, 1))
+    K = wl.cast(x[None, None], "f16")
+    S = wl.to_f64(K[0, 0], "f16")
+    S /= np.linalg.norm(S, axis=1, keepdims=True)
+    close = (np.abs(S @ S.T - theta) < 2e-4).sum() // 2
+    assert close > 32 * n, "the input must overflow the pair list"
+    L = wl.Layer("f16", K, K.copy(), np.zeros((1, 1, 1, d), np.float16), 1, 1, 1, n, n, theta_k=theta, theta_v=theta)
+    parity.check_shallow_layer(oracle, L, tensors=("k",))
+    parity.check_shallow_layer(oracle, L, tensors=("k",), cap=100, debug=False)
+    # the library's own count of deferred pairs confirms that the list ran full
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    Kd = sb.to_device(L.K, "f16")
+    plan = sb.plan_shallow(Kd, "f16", theta, theta, n, tensors=("k",))
+    plan.run(Kd, None)
+    torch.cuda.synchronize()
+    assert plan.stats()[0, 2] > 32 * n
+
+
 def test_duplicates_and_zero_vectors(oracle):
     L = wl.small_random(10, "f16", B=1, H=1, l=400, lw=1, cap=400)
     L.K[0, 0, 100:150] = L.K[0, 0, 7]            # exact duplicates
