@@ -117,6 +117,22 @@ def test_empty_partial_and_full_codebooks(oracle):
     assert res3[0]["n_codes"] == k and (res3[0]["ref"] == -1).sum() == 200 - res3[0]["n_matched"]
 
 
+def test_largest_call_clique_and_isolated_tokens(oracle):
+    # 1024 new tokens and an empty table: all of them around one direction (one entry, every
+    # degree 1024), all of them unrelated (1024 entries, more than the table holds), and a mix
+    rng = np.random.default_rng(4)
+    d, m = 128, 1024
+    c = rng.standard_normal(d)
+    clique = c + 0.02 * rng.standard_normal((m, d))
+    lone = rng.standard_normal((m, d))
+    mix = np.where((np.arange(m) % 3 == 0)[:, None], clique, lone)
+    new = wl.cast(np.stack([clique, lone, mix])[None], "f16")             # [1, 3, m, d]
+    for cap in (1500, 700):
+        Cb = np.zeros((1, 3, cap, d), dtype=np.float16)
+        res, _, _ = run_and_check(oracle, new, Cb, np.zeros((1, 3), dtype=np.int32), "f16", 0.98)
+        assert [o["n_found"] for o in res] == [1, 1024, 1 + 1024 - 342]
+
+
 def test_duplicates_zero_vectors_and_equal_entries(oracle):
     dtype, theta = "f32", 0.9
     rng = np.random.default_rng(11)
