@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 PEAK_VALU_F64_TFLOPS = 78.6         # 256 CUs x 64 lanes x 2 flop x 2.4 GHz
 
 
-def cpu_baseline(L, wl, sample_n=12288):
+def cpu_baseline(L, wl, sample_n=24576):
     """The oracle as it stands, timed on this host: the eviction path on one full unit and
     the codebook path on the first `sample_n` tokens of one K unit; scaled to a whole layer
     (eviction linear in units, codebook quadratic in tokens and linear in units)."""
