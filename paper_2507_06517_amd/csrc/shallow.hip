@@ -1517,7 +1517,7 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_twohop(ShallowParams p, i
 // its neighbours that are not dead (its new degree, Eq. 13: with most tokens leaving in the
 // first rounds, recounting the few that stay is cheaper than subtracting at every
 // neighbour of every leaving token), gets its new key and moves to the other list.
-__global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, int round) {
+__global__ __launch_bounds__(kMergeThreads) void merge_update(ShallowParams p, int round) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];     // dead flags of the problem, one byte per token
   constexpr int kPer = kWave / kSegW;
   const int ut = blockIdx.y, lane = lane_id(), n = p.n;
@@ -1536,7 +1536,7 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
   const int *src = (round & 1 ? p.alive2 : p.alive) + base;
   int *dst = (round & 1 ? p.alive : p.alive2) + base;
   uint32_t *key = p.key + base;
-  __shared__ int wave_total[kPhaseThreads / kWave], block_at;
+  __shared__ int wave_total[kMergeThreads / kWave], block_at;
   const int wave = threadIdx.x / kWave;
   // block-uniform trip count (the appends below synchronise the block): waves past the end
   // of the list run with all lanes idle
@@ -1580,7 +1580,7 @@ __global__ __launch_bounds__(kPhaseThreads) void merge_update(ShallowParams p, i
     __syncthreads();
     if (threadIdx.x == 0) {
       int t = 0;
-      for (int q = 0; q < kPhaseThreads / kWave; ++q) t += wave_total[q];
+      for (int q = 0; q < kMergeThreads / kWave; ++q) t += wave_total[q];
       block_at = t ? atomicAdd(&cnt[alive_slot(round + 1)], t) : 0;
     }
     __syncthreads();
@@ -2240,7 +2240,9 @@ extern "C" spindle_status spindle_compress_shallow(
   {
     int gx = (n + 4 * (kPhaseThreads / kSegW) - 1) / (4 * (kPhaseThreads / kSegW));
     if (gx > 256) gx = 256;
-    const dim3 pg(gx, p.UT);
+    // candidates are a small part of the tokens: an eighth of the blocks that would give every
+    // 8-lane segment four rows (a grid of mostly idle blocks costs more than a second trip)
+    const dim3 tg(gx / 8 > 0 ? gx / 8 : 1, p.UT);
     // one-hop phase: 1024-thread blocks with the keys of the problem in LDS when they fit
     const int keys_in_lds = n <= kKeysInLds;
     const size_t key_lds = keys_in_lds ? (size_t)((n + 3) & ~3) * sizeof(uint32_t) : 0;
@@ -2254,8 +2256,9 @@ extern "C" spindle_status spindle_compress_shallow(
     for (int round = 0; round < kGridRounds; ++round) {
       ProfScope ps("shallow_merge_grid", st);
       hipLaunchKernelGGL(merge_onehop, dim3(ox, p.UT), dim3(kMergeThreads), key_lds, st, p, round, keys_in_lds);
-      hipLaunchKernelGGL(merge_twohop, pg, dim3(kPhaseThreads), 0, st, p, round);
-      hipLaunchKernelGGL(merge_update, pg, dim3(kPhaseThreads), dead_lds, st, p, round);
+      hipLaunchKernelGGL(merge_twohop, tg, dim3(kPhaseThreads), 0, st, p, round);
+      hipLaunchKernelGGL(merge_update, dim3(ox, p.UT), dim3(kMergeThreads), dead_lds, st, p, round);   // 1024 threads: fewer copies of the flags
+
     }
   }
   const size_t merge_lds = n <= kKeysInLds ? ((size_t)((n + 3) & ~3) + (n + 31) / 32) * sizeof(uint32_t) : 0;
