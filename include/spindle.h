@@ -56,7 +56,15 @@ typedef enum {
   SPINDLE_NORM_NONE = 1   /* plain window sum                                      */
 } spindle_norm;
 
-/* Shape of the KV cache of one call: K, V are [batch, n_kv_heads, seq_len, head_dim]. */
+/*
+ * Shape of the KV cache of one call: K, V are [batch, n_kv_heads, seq_len, head_dim].
+ * stride_b, stride_h, stride_t give the distance, in elements, between consecutive batches,
+ * heads and tokens of the INPUT tensors K and V (the head dimension is always contiguous), so
+ * that a cache stored as [batch, seq_len, n_kv_heads, head_dim] needs no copy: stride_t =
+ * n_kv_heads * head_dim, stride_h = head_dim.  All three zero = contiguous in the stated shape.
+ * Each must be a multiple of 8 elements (16-byte rows) and stride_t >= head_dim.  Qw and every
+ * output are always contiguous.  spindle_decode_merge takes contiguous new tokens (strides 0).
+ */
 typedef struct {
   int32_t batch;      /* B   >= 1                                                  */
   int32_t n_kv_heads; /* h_g >= 1                                                  */
@@ -64,6 +72,9 @@ typedef struct {
   int32_t seq_len;    /* l   >= 1                                                  */
   int32_t head_dim;   /* d_h, must be 128                                          */
   int32_t dtype;      /* spindle_dtype                                             */
+  int64_t stride_b;   /* elements between batches of K and V, 0 = contiguous       */
+  int64_t stride_h;   /* elements between heads,   0 = contiguous                  */
+  int64_t stride_t;   /* elements between tokens,  0 = contiguous                  */
 } spindle_kv_desc;
 
 /* ------------------------------------------------------------------------- */

@@ -32,7 +32,8 @@ EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_sha
 
 class KvDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_kv_heads", C.c_int32), ("group_size", C.c_int32),
-                ("seq_len", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+                ("seq_len", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_t", C.c_int64)]
 
 
 class SpindleError(RuntimeError):
@@ -110,8 +111,14 @@ def to_host_bits(t, dtype: str) -> np.ndarray:
 
 
 def desc_of(K, group_size: int, dtype: str) -> KvDesc:
+    """Descriptor of a [B, H, l, d] tensor; a view with another memory order (say a cache stored as
+    [B, l, H, d]) is described by its strides, the head dimension has to be contiguous."""
     B, H, l, d = K.shape
-    return KvDesc(B, H, group_size, l, d, _DT[dtype])
+    if K.is_contiguous():
+        return KvDesc(B, H, group_size, l, d, _DT[dtype])
+    if K.stride(3) != 1:
+        raise ValueError("the head dimension of K and V must be contiguous")
+    return KvDesc(B, H, group_size, l, d, _DT[dtype], K.stride(0), K.stride(1), K.stride(2))
 
 
 # ------------------------------------------------------------------ raw calls (same names as the C ABI)

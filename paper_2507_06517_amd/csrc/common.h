@@ -21,6 +21,16 @@ typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 void set_error(const char *fmt, ...);
 spindle_status check_desc(const spindle_kv_desc *d);
 
+// Where the rows of the input tensors K and V are: byte strides between batches, heads and tokens.
+struct KvLayout {
+  long long sb, sh, st;
+  int H;
+};
+spindle_status kv_layout(const spindle_kv_desc *d, KvLayout *out);   // validates the strides of d
+__host__ __device__ inline size_t kv_unit_offset(const KvLayout &L, int unit) {
+  return (size_t)(unit / L.H) * (size_t)L.sb + (size_t)(unit % L.H) * (size_t)L.sh;
+}
+
 #define SPINDLE_FAIL(code, ...)        \
   do {                                 \
     ::spindle::set_error(__VA_ARGS__); \

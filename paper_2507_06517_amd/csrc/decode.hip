@@ -556,6 +556,8 @@ __global__ __launch_bounds__(kSmallThreads) void decode_small(DecodeParams p) {
 spindle_status check_decode(const spindle_kv_desc *desc) {
   spindle_status s = check_desc(desc);
   if (s != SPINDLE_OK) return s;
+  if (desc->stride_b || desc->stride_h || desc->stride_t)
+    SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "the new tokens of a decode step are contiguous: strides must be 0");
   if (desc->seq_len > kDecodeMax)
     SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "at most %d new tokens per call, got %d", kDecodeMax, desc->seq_len);
   return SPINDLE_OK;

@@ -35,6 +35,7 @@ struct DeepParams {
   float *scores;       // [U][lc] group-averaged accumulated attention
   int l, lc, lw, hn, R, Rpad, nchunks;
   int stages;          // 128-key stages per block
+  KvLayout lay;        // rows of K
   float sc2;           // scale * log2(e): logits are kept in base-2 units
   float inv_hn;
   int norm;
@@ -50,13 +51,13 @@ struct Stage {
   static constexpr int kBytes = kStageKeys * M::kLdsRow;
 
   // global -> registers; keys at or beyond `l` read as zero
-  static __device__ __forceinline__ void fetch(u4 (&r)[kPasses], const char *Kunit, int k0, int l) {
+  static __device__ __forceinline__ void fetch(u4 (&r)[kPasses], const char *Kunit, size_t pitch, int k0, int l) {
     const int tr = threadIdx.x / kThreadsPerRow, tc = threadIdx.x % kThreadsPerRow;
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
       const int key = k0 + p * kRowsPerPass + tr;
       u4 v = {0, 0, 0, 0};
-      if (key < l) v = *reinterpret_cast<const u4 *>(Kunit + (size_t)key * M::kRowBytes + tc * 16);
+      if (key < l) v = *reinterpret_cast<const u4 *>(Kunit + (size_t)key * pitch + tc * 16);
       r[p] = v;
     }
   }
@@ -88,7 +89,8 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
   const int wr = wave % WR, wk = wave / WR;
   const int key_begin = chunk * p.stages * kStageKeys;
   const int key_limit = ACCUM ? p.lc : p.l;   // keys at or beyond this index are not needed
-  const char *Kunit = p.K + (size_t)u * p.l * M::kRowBytes;
+  const char *Kunit = p.K + kv_unit_offset(p.lay, u);
+  const size_t kpitch = (size_t)p.lay.st;
   const char *Qunit = p.Q + (size_t)u * p.R * M::kRowBytes;
 
   // query fragments stay in registers for the whole block
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
     }
 
   u4 regs[S::kPasses];
-  S::fetch(regs, Kunit, key_begin, key_limit);
+  S::fetch(regs, Kunit, kpitch, key_begin, key_limit);
   S::store(regs, smem);
   __syncthreads();
 
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
     const int k0 = key_begin + s * kStageKeys;
     if (k0 >= key_limit) break;                       // uniform over the block
     const bool more = (s + 1 < p.stages) && (k0 + kStageKeys < key_limit);
-    if (more) S::fetch(regs, Kunit, k0 + kStageKeys, key_limit);
+    if (more) S::fetch(regs, Kunit, kpitch, k0 + kStageKeys, key_limit);
 
     if (ACCUM && s > 0 && threadIdx.x < kStageKeys) {
       // finish the previous stage: fixed-order sum of the partial column sums
@@ -495,6 +497,7 @@ struct GatherParams {
   char *Ko, *Vo;
   const int32_t *kept;
   int l, out_stride, row_bytes;
+  KvLayout lay;        // rows of K and V
 };
 
 __global__ __launch_bounds__(256) void deep_gather(GatherParams p) {
@@ -506,7 +509,7 @@ __global__ __launch_bounds__(256) void deep_gather(GatherParams p) {
   if (j >= p.out_stride) return;
   const int idx = p.kept[(size_t)u * p.out_stride + j];
   const size_t dst = ((size_t)u * p.out_stride + j) * p.row_bytes + t * 16;
-  const size_t src = ((size_t)u * p.l + (idx < 0 ? 0 : idx)) * p.row_bytes + t * 16;
+  const size_t src = kv_unit_offset(p.lay, u) + (size_t)(idx < 0 ? 0 : idx) * (size_t)p.lay.st + t * 16;
   u4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
   if (idx >= 0) {
     kv = *reinterpret_cast<const u4 *>(p.K + src);
@@ -615,7 +618,11 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   DeepLayout L = deep_layout(workspace, U, l, lw, Rpad);
 
   DeepParams p;
+  KvLayout lay;
+  s = kv_layout(desc, &lay);
+  if (s != SPINDLE_OK) return s;
   p.K = static_cast<const char *>(K);
+  p.lay = lay;
   p.Q = static_cast<const char *>(Qw);
   p.partial = L.partial;
   p.scores = L.scores;
@@ -648,6 +655,7 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   gp.Ko = static_cast<char *>(K_out); gp.Vo = static_cast<char *>(V_out);
   gp.kept = kept_idx; gp.l = l; gp.out_stride = out_stride;
   gp.row_bytes = kHeadDim * dtype_bytes(desc->dtype);
+  gp.lay = lay;
   const int rows_per_block = 256 / (gp.row_bytes / 16);
   { ProfScope ps("deep_gather", st);
   hipLaunchKernelGGL(deep_gather, dim3((out_stride + rows_per_block - 1) / rows_per_block, U), dim3(256), 0, st, gp); }

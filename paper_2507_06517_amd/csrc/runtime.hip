@@ -31,6 +31,21 @@ spindle_status check_desc(const spindle_kv_desc *d) {
   return SPINDLE_OK;
 }
 
+spindle_status kv_layout(const spindle_kv_desc *d, KvLayout *out) {
+  const long long elt = dtype_bytes(d->dtype);
+  const long long st = d->stride_t ? d->stride_t : d->head_dim;
+  const long long sh = d->stride_h ? d->stride_h : (long long)d->seq_len * d->head_dim;
+  const long long sb = d->stride_b ? d->stride_b : (long long)d->n_kv_heads * d->seq_len * d->head_dim;
+  if (d->stride_b < 0 || d->stride_h < 0 || d->stride_t < 0 || st < d->head_dim)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "strides must be >= 0 and stride_t >= head_dim");
+  if ((st | sh | sb) & 7) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "strides must be multiples of 8 elements");
+  out->sb = sb * elt;
+  out->sh = sh * elt;
+  out->st = st * elt;
+  out->H = d->n_kv_heads;
+  return SPINDLE_OK;
+}
+
 struct ProfRec {
   char name[32];
   hipEvent_t a, b;

@@ -76,6 +76,7 @@ struct ShallowParams {
   const char *X[2];        // input tensors [U][n][128] in `dtype` (index = tensor slot)
   float theta[2];
   int dtype, U, UT, n, Wp;  // Wp = words per adjacency row (multiple of 4)
+  KvLayout lay;            // rows of the input tensors
   int cap;
   // workspace
   _Float16 *Xh;            // [UT][n][128] unit vectors
@@ -118,7 +119,7 @@ struct ShallowParams {
 
 __device__ __forceinline__ const char *x_row(const ShallowParams &p, int ut, int a) {
   const int t = ut / p.U, u = ut % p.U;
-  return p.X[t] + ((size_t)u * p.n + a) * (size_t)(kHeadDim * (p.dtype == SPINDLE_F32 ? 4 : 2));
+  return p.X[t] + kv_unit_offset(p.lay, u) + (size_t)a * (size_t)p.lay.st;
 }
 
 // x_a . x_b in double precision, summed in dimension order (products are exact).
@@ -2182,6 +2183,8 @@ extern "C" spindle_status spindle_compress_shallow(
   ShallowParams p;
   memset(&p, 0, sizeof(p));
   p.dtype = desc->dtype; p.U = U; p.UT = U * T; p.n = n;
+  s = kv_layout(desc, &p.lay);
+  if (s != SPINDLE_OK) return s;
   p.cap = max_codes;
   carve(p, workspace, p.UT, n);
   int t = 0;

@@ -77,7 +77,7 @@ def test_compress_calls_reject_bad_arguments_before_any_launch(sb):
         a = dict(K=fake, V=fake, Qw=fake, window=32, pool=7, scale=0.088, norm=0, budget=128, budgets=null,
                  out_stride=128, kept=fake, Ko=fake, Vo=fake, sc=null, ws=fake, wsb=1 << 30)
         a.update(kw)
-        return L.spindle_compress_deep(C.byref(d), a["K"], a["V"], a["Qw"], a["window"], a["pool"], a["scale"],
+        return L.spindle_compress_deep(C.byref(a.get("desc", d)), a["K"], a["V"], a["Qw"], a["window"], a["pool"], a["scale"],
                                        a["norm"], a["budget"], a["budgets"], a["out_stride"], a["kept"],
                                        a["Ko"], a["Vo"], a["sc"], a["ws"], a["wsb"], null)
 
@@ -94,6 +94,10 @@ def test_compress_calls_reject_bad_arguments_before_any_launch(sb):
     assert deep(ws=C.c_void_p(0x1010)) == 3
     assert deep(K=C.c_void_p(0x1004)) == 1
     assert b"aligned" in L.spindle_last_error()
+    # strides of K and V: token stride below head_dim, not a multiple of 8 elements, negative
+    assert deep(desc=sb.KvDesc(1, 2, 4, 512, 128, sb.F16, 0, 0, 64)) == 1
+    assert deep(desc=sb.KvDesc(1, 2, 4, 512, 128, sb.F16, 0, 132, 0)) == 1
+    assert deep(desc=sb.KvDesc(1, 2, 4, 512, 128, sb.F16, -256, 0, 0)) == 1
 
     def shallow(**kw):
         a = dict(K=fake, V=null, cap=64, C=fake, nc=fake, ref=fake, mag=fake, ws=fake, wsb=1 << 40, tk=0.98)

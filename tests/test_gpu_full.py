@@ -179,3 +179,37 @@ def test_unfolded_gqa_then_one_codebook_per_kv_head(oracle):
                 assert first.setdefault(int(pos), int(r)) == int(r)
             shared.append(len(rows) - len(first))
     assert max(shared) > 0, "the query heads of a group should agree on some tokens"
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_cache_stored_token_major(oracle, dtype):
+    # K and V kept as [batch, seq_len, heads, head_dim], the order many inference engines use:
+    # the calls take the strides and read the rows in place.  Same results as the head-major copy.
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    L = wl.small_random(31, dtype, B=2, H=3, l=1300, hn=2, lw=16, pool=7, budget=200, cap=150, n_centroids=20)
+    Kc, Vc, Q = (sb.to_device(x, L.dtype) for x in (L.K, L.V, L.Qw))
+    Kt = Kc.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)          # [B, H, l, d] view of [B, l, H, d] memory
+    Vt = Vc.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert not Kt.is_contiguous() and torch.equal(Kt, Kc)
+    kept, Ko, Vo, sc = sb.compress_deep(Kt, Vt, Q, L.group_size, L.dtype, L.window, L.pool, L.budget,
+                                        scale=parity.scale_of(L.head_dim))
+    torch.cuda.synchronize()
+    p64, kept64 = parity.oracle_deep(oracle, L)
+    rep = {}
+    for b in range(2):
+        for h in range(3):
+            parity.check_deep_unit(p64[b, h], kept64[b, h], sc[b, h].cpu().numpy().astype(np.float64),
+                                   kept[b, h].cpu().numpy(), L.window, 1300, rep)
+            g = kept64[b, h]
+            assert np.array_equal(sb.to_host_bits(Ko, dtype)[b, h, :len(g)], L.K[b, h][g])
+            assert np.array_equal(sb.to_host_bits(Vo, dtype)[b, h, :len(g)], L.V[b, h][g])
+    out = sb.compress_shallow(Kt, Vt, L.dtype, L.theta_k, L.theta_v, L.max_codes, debug=True)
+    torch.cuda.synchronize()
+    g = {}
+    for k, v in out.items():
+        g[k] = sb.to_host_bits(v, dtype) if k.startswith("C_") else (v.cpu().numpy().view(np.uint32) if k.startswith("adj_") else v.cpu().numpy())
+    for t, X, theta in (("k", L.K, L.theta_k), ("v", L.V, L.theta_v)):
+        for b in range(2):
+            for h in range(3):
+                parity.check_shallow_unit(oracle, wl.to_f64(X[b, h], dtype), theta, L.max_codes, dtype, g, t, b, h)
