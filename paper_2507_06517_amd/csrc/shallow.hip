@@ -261,6 +261,7 @@ __global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
 // double-precision decision (shallow_fixup sets the bit if it is adjacent).
 
 constexpr int kPairBuf = 256;   // queued pairs per wave before a flush
+constexpr int kWordList = 384;  // listed pieces per wave before they are turned into records
 
 // Moves a wave's queued pairs to the global list of its ut.  When that list is full the
 // pairs are dropped and a flag is raised: shallow_gram<true> then decides every close
@@ -314,6 +315,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   // written out as whole lines, because partially written lines cost several times their
   // size in HBM write traffic.  Row pitch 36 words keeps 16-byte alignment.
   __shared__ __attribute__((aligned(16))) uint32_t wstage[kGramThreads / 64][64][36];
+  __shared__ uint32_t wordlist[kGramThreads / 64][kWordList];   // the 16-byte pieces of a chunk that have a set bit
   const int n = p.n;
   const int nI = (n + kPanelRows - 1) / kPanelRows;
   const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
@@ -584,29 +586,51 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     uint32_t *eseg = p.edges + seg * p.seg_cap;
     int ecnt = 0;                                    // wave-uniform
     const unsigned long long below = (1ull << lane) - 1ull;
+    // Few of the 512 16-byte pieces of a chunk (64 rows x 8) have a bit set.  First the pieces
+    // that have one are listed (one ballot per eight rows), then every lane takes a listed piece
+    // and the wave peels off one bit of each per pass: far fewer passes than over all pieces.
+    uint32_t *wl = wordlist[wave];
+    int nw = 0;                                      // wave-uniform
+    auto expand = [&]() {
+      for (int e0 = 0; e0 < nw; e0 += kWave) {
+        const int e = e0 + lane;
+        const uint32_t key = e < nw ? wl[e] : 0u;    // row in the wave << 3 | piece
+        u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][key >> 3][(key & 7u) * 4]);
+        if (e >= nw) v = u4{0, 0, 0, 0};
+        const uint32_t rec0 = ((uint32_t)(arow0 + (int)(key >> 3)) << 16) | (uint32_t)(col_begin + (int)(key & 7u) * 128);
+        for (;;) {
+          const bool has = (v[0] | v[1] | v[2] | v[3]) != 0;
+          const unsigned long long mk = __ballot(has);
+          if (mk == 0) break;
+          if (has) {
+            const int j = v[0] ? 0 : v[1] ? 1 : v[2] ? 2 : 3;
+            const uint32_t w = v[j];
+            const int t = __builtin_ctz(w);
+            v[j] = w & (w - 1);
+            const int at = ecnt + __popcll(mk & below);
+            if (at < p.seg_cap) eseg[at] = rec0 + (uint32_t)(j * 32 + t);
+          }
+          ecnt += __popcll(mk);
+        }
+      }
+      nw = 0;
+    };
     for (int it = 0; it < 8; ++it) {
       const int r = it * 8 + (lane >> 3);
-      u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][r][piece * 4]);
+      const u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][r][piece * 4]);
       const bool live = arow0 + r < n && piece < npieces;
       if (live)
         *reinterpret_cast<u4 *>(p.G + ((size_t)ut * n + arow0 + r) * p.Wp + (col_begin >> 5) + piece * 4) = v;
-      if (!live) v = u4{0, 0, 0, 0};
-      // every pass takes one bit of each lane that still has some
-      for (;;) {
-        const bool has = (v[0] | v[1] | v[2] | v[3]) != 0;
-        const unsigned long long mk = __ballot(has);
-        if (mk == 0) break;
-        if (has) {
-          const int j = v[0] ? 0 : v[1] ? 1 : v[2] ? 2 : 3;
-          const uint32_t w = v[j];
-          const int t = __builtin_ctz(w);
-          v[j] = w & (w - 1);
-          const int at = ecnt + __popcll(mk & below);
-          if (at < p.seg_cap) eseg[at] = ((uint32_t)(arow0 + r) << 16) | (uint32_t)(col_begin + piece * 128 + j * 32 + t);
-        }
-        ecnt += __popcll(mk);
+      const bool nz = live && (v[0] | v[1] | v[2] | v[3]) != 0;
+      const unsigned long long mk = __ballot(nz);
+      if (mk) {                                      // wave-uniform
+        const int add = __popcll(mk);
+        if (nw + add > kWordList) expand();
+        if (nz) wl[nw + __popcll(mk & below)] = (uint32_t)(r << 3 | piece);
+        nw += add;
       }
     }
+    expand();
     if (lane == 0) {
       p.ecount[seg] = (unsigned)(ecnt < p.seg_cap ? ecnt : p.seg_cap);
       if (ecnt > p.seg_cap) atomicOr(p.need_full, 1u);
