@@ -9,10 +9,11 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libspindle.so")
-SOURCES = ["runtime.hip", "deep.hip", "shallow.hip", "reconstruct.hip", "decode.hip"]
+SOURCES = ["runtime.hip", "deep.hip", "shallow.hip", "shallow_graph.hip", "shallow_merge.hip",
+           "shallow_codebook.hip", "reconstruct.hip", "decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-inline-asm",      # shallow.hip's LDS load writes M0 and says so in its clobber list
+         "-Wno-inline-asm",      # the LDS loads of the codebook kernels write M0 and say so in their clobber lists
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 

@@ -1,0 +1,871 @@
+// Similarity graph of the codebook path: magnitudes and unit vectors, thresholded cosine
+// similarities on the matrix cores, exact decisions near the threshold, degrees and neighbour
+// lists (Eq. 4, 8-10).
+#include "mma.h"
+#include "shallow.h"
+
+namespace spindle {
+namespace {
+
+// ---------------------------------------------------------------- prep
+template <int DT>
+__global__ __launch_bounds__(256) void shallow_prep(ShallowParams p) {
+  typedef typename Elem<DT>::type T;
+  constexpr int kRows = 64;
+  constexpr int row_bytes = kHeadDim * sizeof(T);
+  constexpr int lds_row = row_bytes + 16;
+  constexpr int tpr = row_bytes / 16;
+  __shared__ __attribute__((aligned(16))) char tile_in[kRows * lds_row];
+  __shared__ __attribute__((aligned(16))) char tile_out[kRows * kLdsRow];
+  __shared__ float row_err[kRows];
+  __shared__ double row_inv[kRows];
+  const int ut = blockIdx.y, t = ut / p.U;
+  const int row0 = blockIdx.x * kRows;
+  for (int i = threadIdx.x; i < kRows * tpr; i += 256) {
+    const int r = i / tpr, ch = i % tpr;
+    u4 v = {0, 0, 0, 0};
+    if (row0 + r < p.n) v = *reinterpret_cast<const u4 *>(x_row(p, ut, row0 + r) + ch * 16);
+    *reinterpret_cast<u4 *>(tile_in + r * lds_row + ch * 16) = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < kRows && row0 + threadIdx.x < p.n) {
+    const int r = threadIdx.x;
+    constexpr int per = 16 / sizeof(T);
+    double ss = 0.0;
+    for (int ch = 0; ch < tpr; ++ch) {
+      const u4 v = *reinterpret_cast<const u4 *>(tile_in + r * lds_row + ch * 16);
+      const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+      for (int i = 0; i < per; ++i) {
+        const double x = (double)Elem<DT>::to_float(e[i]);
+        ss += x * x;
+      }
+    }
+    const double m = sqrt(ss);
+    const size_t idx = (size_t)ut * p.n + row0 + r;
+    p.m64[idx] = m;
+    p.mag[t][(size_t)(ut % p.U) * p.n + row0 + r] = (float)m;
+    row_inv[r] = m > 0.0 ? (double)kUnitScale / m : 0.0;
+  } else if (threadIdx.x < kRows) {
+    row_inv[threadIdx.x] = 0.0;                      // rows past the end of the sequence
+  }
+  __syncthreads();
+  {
+    // four threads per row: fp16 unit vector (x 2^10) and its distance from the exact one
+    const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
+    constexpr int per = 16 / sizeof(T);
+    const double inv64 = row_inv[r];
+    const float inv = (float)inv64;
+    double e2 = 0.0;                                   // squared distance stored - exact, scaled units
+    for (int ch = part * (tpr / 4); ch < (part + 1) * (tpr / 4); ++ch) {
+      const u4 v = *reinterpret_cast<const u4 *>(tile_in + r * lds_row + ch * 16);
+      const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+      for (int i = 0; i < per; ++i) {
+        const _Float16 hv = (_Float16)(Elem<DT>::to_float(e[i]) * inv);
+        reinterpret_cast<_Float16 *>(tile_out + r * kLdsRow)[ch * per + i] = hv;
+        const double d = (double)(float)hv - (double)Elem<DT>::to_float(e[i]) * inv64;
+        e2 += d * d;
+      }
+    }
+    e2 += __shfl_xor(e2, 1);
+    e2 += __shfl_xor(e2, 2);
+    if (part == 0 && row0 + r < p.n) {
+      // rounded up: the double-precision evaluation above is good to 1e-15, the cast to 6e-8
+      const float ev = (float)(sqrt(e2) / (double)kUnitScale) * (1.f + 1e-6f) + 1e-12f;
+      p.err[(size_t)ut * p.n + row0 + r] = ev;
+      row_err[r] = ev;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kRows) {                         // one update of the chunk's maximum per block
+    float mx = row0 + (int)threadIdx.x < p.n ? row_err[threadIdx.x] : 0.f;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (threadIdx.x == 0)
+      atomicMax(p.echunk + (size_t)ut * ((p.n + kChunkCols - 1) / kChunkCols) + row0 / kChunkCols, __float_as_uint(mx));
+  }
+  for (int i = threadIdx.x; i < kRows * 16; i += 256) {
+    const int r = i / 16, ch = i % 16;
+    if (row0 + r < p.n)
+      *reinterpret_cast<u4 *>(reinterpret_cast<char *>(p.Xh) + ((size_t)ut * p.n + row0 + r) * 256 + ch * 16) =
+          *reinterpret_cast<const u4 *>(tile_out + r * kLdsRow + ch * 16);
+  }
+}
+
+// ---------------------------------------------------------------- gram
+// Block = 4 waves; wave w keeps the unit vectors of tokens a in [I*256 + 64w, +64) as
+// MFMA A-fragments and streams tokens b of the column chunk through LDS.  Lane (g, c)
+// of a 32-column tile holds, for token b = col + c, the similarities with 16 of the 32
+// tokens a of each row block; their signs relative to theta are packed by alignbit
+// into the bits of word (a / 32) of row b of G.
+//
+// The accumulators start at -theta (in the 2^20-scaled units of the stored vectors), so
+// the sign of the result is the fp16 decision.  Results closer to zero than the guard
+// band are not trusted: their bits are cleared and the pair is queued for the exact
+// double-precision decision (shallow_fixup sets the bit if it is adjacent).
+
+constexpr int kPairBuf = 256;   // queued pairs per wave before a flush
+constexpr int kWordList = 384;  // listed pieces per wave before they are turned into records
+
+// Moves a wave's queued pairs to the global list of its ut.  When that list is full the
+// pairs are dropped and a flag is raised: shallow_gram<true> then decides every close
+// pair of every tile in place (slow, but only for inputs with an extreme number of
+// similarities within the guard band of theta).
+__device__ __forceinline__ void flush_pairs(const ShallowParams &p, int ut, const uint32_t *buf, int count) {
+  const int lane = lane_id();
+  unsigned base = 0;
+  if (lane == 0) base = atomicAdd(p.fix_count + ut, (unsigned)count);
+  base = __shfl(base, 0);
+  uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
+  if (base + (unsigned)count > p.fix_cap && lane == 0) atomicExch(p.fix_overflow, 1u);
+  for (int i = lane; i < count; i += kWave)
+    if (base + i < p.fix_cap) list[base + i] = buf[i];
+}
+
+// min(m, |a|, |b|) in one instruction.  `after_a`, `after_b` must be results of ordinary VALU
+// instructions that read the MFMA results a and b come from: the compiler places the wait states a
+// matrix-core result needs in front of instructions it knows, not in front of inline
+// assembly, so this one is tied behind such an instruction by a data dependency.
+__device__ __forceinline__ float min3_abs(float m, float a, float b, uint32_t after_a, uint32_t after_b) {
+  float r;
+  asm("v_min3_f32 %0, %1, |%2|, |%3|" : "=v"(r) : "v"(m), "v"(a), "v"(b), "v"(after_a), "v"(after_b));
+  return r;
+}
+
+// kExact = false: the fast pass described above, one block per (row panel, column chunk).
+// kExact = true: fallback pass over the same tiles, run by a fixed grid that exits at once
+// unless a pair list overflowed; it stores no words and decides the close pairs in place.
+template <bool kExact>
+__global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p) {
+  typedef Mma<SPINDLE_F16> M;
+  // two stages of 64 tokens, filled by direct global->LDS loads.  Row r keeps its 16-byte piece
+  // k at position k ^ swz(r), swz(r) = (r & 7) | ((r & 16) >> 1), so that sixteen consecutive lanes
+  // of a 128-bit LDS read (sixteen different rows, same k) hit sixteen different bank groups.
+  __shared__ __attribute__((aligned(1024))) char stage[2 * kStageBytes];
+  __shared__ uint32_t pairbuf[kGramThreads / 64][kPairBuf];
+  // the 32 words (one 128-byte line) of each of a wave's 64 rows for the current chunk;
+  // written out as whole lines, because partially written lines cost several times their
+  // size in HBM write traffic.  Row pitch 36 words keeps 16-byte alignment.
+  __shared__ __attribute__((aligned(16))) uint32_t wstage[kGramThreads / 64][64][36];
+  __shared__ uint32_t wordlist[kGramThreads / 64][kWordList];   // the 16-byte pieces of a chunk that have a set bit
+  const int n = p.n;
+  const int nI = (n + kPanelRows - 1) / kPanelRows;
+  const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
+  // blocks are dealt round-robin to the 8 XCDs: give each XCD one (ut, chunk) at a time
+  // and let it sweep the row panels, so the chunk is re-read from that XCD's L2
+  if (kExact) {
+    if (*p.fix_overflow == 0) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(p.need_full, 1u);   // bits set here leave no edge records
+  }
+  const int nitems = 8 * nI * ((p.UT * nJ + 7) / 8);
+  for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
+  const int xcd = item & 7, s_ = item >> 3;
+  const int I = s_ % nI;
+  const int pj = (s_ / nI) * 8 + xcd;
+  if (pj >= p.UT * nJ) continue;
+  // (the chunk group is rotated by ut: groups to the right hold more work, and every XCD
+  // should see all of them)
+  const int ut = pj / nJ, Jg = (pj % nJ + ut) % nJ;
+  // G is symmetric: a row panel only computes the chunks from the one holding its own
+  // tokens onwards; shallow_mirror fills the columns to the left from the transposed blocks
+  const int Jfirst = (I * kPanelRows) / kChunkCols;
+  if ((Jg + 1) * kItemChunks <= Jfirst) continue;
+  const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
+  const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
+  const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
+  const int arow0 = I * kPanelRows + 64 * wave;   // first of this wave's 64 rows of G
+  uint32_t *buf = pairbuf[wave];
+  int nbuf = 0;                                    // wave-uniform
+
+  // unit vectors of the wave's rows: MFMA B operand (matrix columns = lanes)
+  M::frag af[2][M::kSteps];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    const int a = arow0 + 32 * cb + c;
+#pragma unroll
+    for (int ks = 0; ks < M::kSteps; ++ks)
+      af[cb][ks] = a < n ? M::load(Xh + (size_t)a * 256, ks, g) : M::zero();
+  }
+  float erow[2];                                   // rounding error of the stored vectors of this lane's two rows
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    const int a = arow0 + 32 * cb + c;
+    erow[cb] = a < n ? p.err[(size_t)ut * n + a] : 0.f;
+  }
+  f16v cinit;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) cinit[v] = -theta_s;
+  // Staged token 16*g + v of a tile is fed to matrix row 8*(v/4) + 4*g + v%4, so that result
+  // register v of lane group g belongs to token 16*g + v and the packed sign bits come out
+  // in token order.
+  const int prow = 16 * ((c >> 2) & 1) + 4 * (c >> 3) + (c & 3);
+  int soff[M::kSteps];                             // byte offset of this lane's fragment ks in tile 0 of a stage
+#pragma unroll
+  for (int ks = 0; ks < M::kSteps; ++ks)
+    soff[ks] = prow * 256 + (((2 * ks + g) ^ ((prow & 7) | ((prow & 16) >> 1))) << 4);
+  uint32_t voff[4];                                // this lane's source offset within a stage, per load
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = (wave * 4 + q) * 4 + (lane >> 4);
+    voff[q] = (uint32_t)(r * 256 + (((lane & 15) ^ ((r & 7) | ((r & 16) >> 1))) << 4));
+  }
+  const uint32_t wsel = g ? 0x07060302u : 0x05040100u;
+  M::frag pf0, pf1;                                // fragments 0, 1 of the tile the next step multiplies
+  const uint32_t stage_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)stage;
+
+  bool carried = false;                            // pipeline state of the chunk to come already in place
+  f16v cur0, cur1, nxt0, nxt1;
+  for (int J = Jg * kItemChunks > Jfirst ? Jg * kItemChunks : Jfirst; J < (Jg + 1) * kItemChunks && J * kChunkCols < n; ++J) {
+  const int col_begin = J * kChunkCols;
+  const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
+  const int ntiles = (col_end - col_begin + 31) / 32;
+  // guard band of this lane's two rows against the tokens of the chunk (scaled units)
+  const float ech = __uint_as_float(p.echunk[(size_t)ut * ((n + kChunkCols - 1) / kChunkCols) + J]);
+  const float band0 = (erow[0] * (1.f + ech) + ech + kGuardSlack) * (kUnitScale * kUnitScale);
+  const float band1 = (erow[1] * (1.f + ech) + ech + kGuardSlack) * (kUnitScale * kUnitScale);
+  const float band = fmaxf(band0, band1);
+  // Stage s of the chunk = tokens col_begin + 64 s .. + 63, in buffer s & 1; tile x = half x & 1
+  // of stage x >> 1.  Each wave fills 16 rows of a stage with four 1-KiB loads (4 rows x 16
+  // pieces, lane = slot).  Rows past the end of the sequence exist (the array is padded) and
+  // are never used: their bits are masked and their pairs rejected.
+  auto dma = [&](int b0, int bufsel) {
+    const char *sbase = Xh + (size_t)b0 * 256;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lds_dma16(sbase + voff[q], stage_lds + bufsel * kStageBytes + (wave * 4 + q) * 1024);
+  };
+  auto frag_at = [&](int bufsel, int ct, int ks) -> M::frag {
+    return *reinterpret_cast<const M::frag *>(stage + bufsel * kStageBytes + ct * 32 * 256 + soff[ks]);
+  };
+  // One pipeline step: the matrix cores compute the similarities of the NEXT tile x (32
+  // staged tokens x this wave's 64 rows, minus theta) while the vector units turn the
+  // signs of the CURRENT tile (results a0, a1, first token bcol0) into the word of this
+  // lane's row of G.  The two instruction streams are independent; sched_barrier pins the
+  // issue order (two matrix instructions, then a slice of vector work).  The step starts
+  // with matrix instructions on fragments fetched during the previous step (pf0, pf1), so
+  // the matrix cores do not wait for the vector work on their previous results.
+  // (bufx, ctx) = place of tile x, (bufn, ctn) = place of tile x + 1.  With sync_fetch (x is
+  // the second half of its stage) the step also holds the block barrier after its last read
+  // of the stage, which hands the buffer to the loads of the stage after next (tokens
+  // fetch_b0 ..) and makes the next stage, loaded one barrier earlier, visible.
+  auto step = [&](int bufx, int ctx, int bufn, int ctn, bool sync_fetch, int fetch_b0, int bcol0, const f16v &a0,
+                  const f16v &a1, f16v &r0, f16v &r1) -> uint32_t {
+    M::frag f2 = frag_at(bufx, ctx, 2), f3 = frag_at(bufx, ctx, 3);
+    r0 = M::mma(pf0, af[0][0], cinit);
+    r1 = M::mma(pf0, af[1][0], cinit);
+    __builtin_amdgcn_sched_barrier(0);               // matrix instructions first: the vector work below waits for the previous tile
+    uint32_t sg0 = 0, sg1 = 0;
+    float mn = INFINITY;
+#pragma unroll
+    for (int v = 15; v >= 12; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(pf1, af[0][1], r0);
+    r1 = M::mma(pf1, af[1][1], r1);
+    M::frag f4 = frag_at(bufx, ctx, 4), f5 = frag_at(bufx, ctx, 5);
+#pragma unroll
+    for (int v = 11; v >= 9; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f2, af[0][2], r0);
+    r1 = M::mma(f2, af[1][2], r1);
+    M::frag f6 = frag_at(bufx, ctx, 6), f7 = frag_at(bufx, ctx, 7);
+#pragma unroll
+    for (int v = 8; v >= 6; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f3, af[0][3], r0);
+    r1 = M::mma(f3, af[1][3], r1);
+#pragma unroll
+    for (int v = 5; v >= 3; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (sync_fetch) {
+      __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): own loads landed, own reads done
+      __builtin_amdgcn_s_barrier();
+      dma(fetch_b0, bufx);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f4, af[0][4], r0);
+    r1 = M::mma(f4, af[1][4], r1);
+    pf0 = frag_at(bufn, ctn, 0);
+    pf1 = frag_at(bufn, ctn, 1);
+#pragma unroll
+    for (int v = 2; v >= 0; --v) {
+      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
+      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
+      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
+    }
+    uint32_t q0 = ~sg0 & 0xFFFFu, q1 = ~sg1 & 0xFFFFu;   // bit v: staged token 16*g + v
+    // pairs too close to theta for fp16: clear their bits now, queue them for the exact
+    // decision.  Bit 16*cb + v of `rest` = close.
+    uint32_t rest = 0;
+    const bool any_close = __any(mn < band);
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f5, af[0][5], r0);
+    r1 = M::mma(f5, af[1][5], r1);
+    if (any_close) {
+      uint32_t cm0 = 0, cm1 = 0;
+#pragma unroll
+      for (int v = 15; v >= 0; --v) {
+        cm0 = __builtin_amdgcn_alignbit(cm0, __float_as_uint(fabsf(a0[v]) - band0), 31);
+        cm1 = __builtin_amdgcn_alignbit(cm1, __float_as_uint(fabsf(a1[v]) - band1), 31);
+      }
+      q0 &= ~cm0;
+      q1 &= ~cm1;
+      rest = (cm0 & 0xFFFFu) | (cm1 << 16);
+    }
+    if (bcol0 < arow0 + 64 && bcol0 + 32 > arow0) {   // tile touches the diagonal: G_aa = 1
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const int i = arow0 + 32 * cb + c - bcol0;    // staged index of this lane's own token
+        if (i >= 0 && i < 32 && (i >> 4) == g) {
+          if (cb == 0) q0 |= 1u << (i & 15); else q1 |= 1u << (i & 15);
+        }
+      }
+    }
+    if (bcol0 + 32 > n) {                             // staged tokens beyond the sequence
+      const int nv = n - bcol0 - 16 * g;
+      const uint32_t keep = nv >= 16 ? 0xFFFFu : (nv <= 0 ? 0u : (1u << nv) - 1u);
+      q0 &= keep;
+      q1 &= keep;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f6, af[0][6], r0);
+    r1 = M::mma(f6, af[1][6], r1);
+    // halves[0] = the value of the lane with g = 0 of this column, halves[1] = that of g = 1
+    const uint32_t own = q0 | (q1 << 16);
+    const auto halves = __builtin_amdgcn_permlane32_swap(own, own, false, false);
+    __builtin_amdgcn_sched_barrier(0);
+    r0 = M::mma(f7, af[0][7], r0);
+    r1 = M::mma(f7, af[1][7], r1);
+    // lane group 0 keeps the word of row block 0 (low halves), group 1 that of block 1
+    const uint32_t word = __builtin_amdgcn_perm(halves[1], halves[0], wsel);
+    if (any_close) {
+      while (__any(rest != 0)) {
+        const bool has = rest != 0;
+        const int i = has ? __builtin_ctz(rest) : 0;
+        rest &= rest - 1;
+        const int row = arow0 + 32 * (i >> 4) + c;          // row of G
+        const int bit = bcol0 + 16 * g + (i & 15);           // staged token
+        const bool valid = has && row < n && bit < n && row != bit;
+        if (kExact) {
+          if (valid && cos64(p, ut, row, bit) > (double)p.theta[ut / p.U])
+            atomicOr(p.G + ((size_t)ut * n + row) * p.Wp + (bit >> 5), 1u << (bit & 31));
+          continue;
+        }
+        const unsigned long long m = __ballot(valid);
+        if (m) {                                    // wave-uniform
+          if (nbuf > kPairBuf - 64) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
+          if ((m >> lane) & 1ull) buf[nbuf + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)row << 16) | (uint32_t)bit;
+          nbuf += __popcll(m);
+        }
+      }
+    }
+    return word;
+  };
+
+  if (!carried) {
+    dma(col_begin, 0);
+    dma(col_begin + kStageCols, 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's loads have landed in LDS
+    __syncthreads();
+    // first tile of the chunk: nothing to pack yet
+    cur0 = cinit;
+    cur1 = cinit;
+#pragma unroll
+    for (int ks = 0; ks < M::kSteps; ++ks) {
+      const M::frag f = frag_at(0, 0, ks);
+      cur0 = M::mma(f, af[0][ks], cur0);
+      cur1 = M::mma(f, af[1][ks], cur1);
+    }
+    pf0 = frag_at(0, 1, 0);
+    pf1 = frag_at(0, 1, 1);
+  }
+  u4 words = {0, 0, 0, 0};
+  // four tiles (two stages) per trip: their words are one aligned 16-byte piece of the row.
+  // The trip is branch-free: tiles past the end of the chunk only occur at the end of the
+  // sequence and give zero words.  Step j packs tile t0 + j and multiplies tile x = t0 + j + 1.
+  for (int t0 = 0; t0 < ntiles; t0 += 4) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int bcol0 = col_begin + (t0 + j) * 32;
+      const int x = j + 1;                           // tile x of the trip (mod 4: t0 is a multiple of 4)
+      words[j] = step((x >> 1) & 1, x & 1, ((x + 1) >> 1) & 1, (x + 1) & 1, (x & 1) != 0,
+                      col_begin + (t0 + x + 3) * 32, bcol0, cur0, cur1, nxt0, nxt1);
+      cur0 = nxt0;
+      cur1 = nxt1;
+    }
+    if (!kExact) *reinterpret_cast<u4 *>(&wstage[wave][lane][t0]) = words;
+  }
+  if (!kExact) {
+    const int npieces = (ntiles + 3) / 4, piece = lane & 7;
+    // the set bits also go out as (row, column) records, a segment per wave and chunk: sparse
+    // graphs get their neighbour lists from these without another pass over G
+    const int nJc = (n + kChunkCols - 1) / kChunkCols;
+    const size_t seg = (((size_t)ut * nJc + J) * nI + I) * 4 + wave;
+    uint32_t *eseg = p.edges + seg * p.seg_cap;
+    int ecnt = 0;                                    // wave-uniform
+    const unsigned long long below = (1ull << lane) - 1ull;
+    // Few of the 512 16-byte pieces of a chunk (64 rows x 8) have a bit set.  First the pieces
+    // that have one are listed (one ballot per eight rows), then every lane takes a listed piece
+    // and the wave peels off one bit of each per pass: far fewer passes than over all pieces.
+    uint32_t *wl = wordlist[wave];
+    int nw = 0;                                      // wave-uniform
+    auto expand = [&]() {
+      for (int e0 = 0; e0 < nw; e0 += kWave) {
+        const int e = e0 + lane;
+        const uint32_t key = e < nw ? wl[e] : 0u;    // row in the wave << 3 | piece
+        u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][key >> 3][(key & 7u) * 4]);
+        if (e >= nw) v = u4{0, 0, 0, 0};
+        const uint32_t rec0 = ((uint32_t)(arow0 + (int)(key >> 3)) << 16) | (uint32_t)(col_begin + (int)(key & 7u) * 128);
+        for (;;) {
+          const bool has = (v[0] | v[1] | v[2] | v[3]) != 0;
+          const unsigned long long mk = __ballot(has);
+          if (mk == 0) break;
+          if (has) {
+            const int j = v[0] ? 0 : v[1] ? 1 : v[2] ? 2 : 3;
+            const uint32_t w = v[j];
+            const int t = __builtin_ctz(w);
+            v[j] = w & (w - 1);
+            const int at = ecnt + __popcll(mk & below);
+            if (at < p.seg_cap) eseg[at] = rec0 + (uint32_t)(j * 32 + t);
+          }
+          ecnt += __popcll(mk);
+        }
+      }
+      nw = 0;
+    };
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 8 + (lane >> 3);
+      const u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][r][piece * 4]);
+      const bool live = arow0 + r < n && piece < npieces;
+      if (live)
+        *reinterpret_cast<u4 *>(p.G + ((size_t)ut * n + arow0 + r) * p.Wp + (col_begin >> 5) + piece * 4) = v;
+      const bool nz = live && (v[0] | v[1] | v[2] | v[3]) != 0;
+      const unsigned long long mk = __ballot(nz);
+      if (mk) {                                      // wave-uniform
+        const int add = __popcll(mk);
+        if (nw + add > kWordList) expand();
+        if (nz) wl[nw + __popcll(mk & below)] = (uint32_t)(r << 3 | piece);
+        nw += add;
+      }
+    }
+    expand();
+    if (lane == 0) {
+      p.ecount[seg] = (unsigned)(ecnt < p.seg_cap ? ecnt : p.seg_cap);
+      if (ecnt > p.seg_cap) atomicOr(p.need_full, 1u);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // loads issued for stages past the chunk
+  __syncthreads();                                 // the stage buffers are reused by the next chunk
+  // The last steps of a full chunk have staged the 128 tokens that follow it and multiplied the
+  // first 32 of them (the pipeline always runs one tile and two stages ahead): when the next
+  // chunk of the item follows, its first tile, the fragments of its second and both stage
+  // buffers are already in place.
+  carried = col_end - col_begin == kChunkCols;
+  }
+  if (nbuf) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
+  }
+}
+
+// ---------------------------------------------------------------- mirror
+// G_ab = G_ba for the part shallow_gram leaves out: rows of the 1024-token tile TI, columns
+// of every tile TJ < TI.  One block moves half such a tile: the 64-byte pieces that hold 512
+// tokens a of the 1024 rows b of tile TJ go to LDS as two 512 x 512-bit squares, each is
+// transposed in place (32 x 32-bit blocks in registers, swapped pairwise), and row a of the
+// two squares side by side is one whole 128-byte line of G.  The two halves of a tile run on
+// the same XCD one after the other, so the second finds its half of the lines in that L2.
+constexpr int kMirrorThreads = 512;
+constexpr int kMirrorPitch = 17;                   // words per staged row: column reads hit 32 different banks
+constexpr size_t kMirrorLds = (size_t)1024 * kMirrorPitch * sizeof(uint32_t);
+
+// One stage of the 32 x 32 bit transpose held one row per lane (lane i of a 32-lane half =
+// row i): exchange with lane i ^ k, k = 16 >> st.  Lanes with bit k clear keep their bits
+// at positions with bit k clear and take the partner's bits of those positions, moved up by
+// k; the others the mirror image.  rot = right-rotation that moves the partner's bits into
+// place (32 - k or k), keep = mask of the bits the lane keeps.
+__device__ __forceinline__ uint32_t transpose_stage(uint32_t x, int st, uint32_t rot, uint32_t keep) {
+  uint32_t y;
+  if (st == 0) {
+    y = (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x401F);                        // lane ^ 16
+  } else if (st == 1) {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x128, 0xF, 0xF, false);  // row_ror:8 = lane ^ 8
+  } else if (st == 2) {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x104, 0xF, 0x5, false);  // row_shl:4 -> lanes with bit 2 clear
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)y, (int)x, 0x114, 0xF, 0xA, false);  // row_shr:4 -> lanes with bit 2 set
+  } else if (st == 3) {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+  } else {
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+  }
+  const uint32_t moved = __builtin_amdgcn_alignbit(y, y, rot);
+  uint32_t r;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(keep), "v"(x), "v"(moved));   // (x & keep) | (moved & ~keep)
+  return r;
+}
+
+__device__ __forceinline__ void mirror_half_tile(const ShallowParams &p, uint32_t *mtile, int item) {
+  const int n = p.n, Wp = p.Wp;
+  const int T = (n + 1023) >> 10, npairs = T * (T - 1) / 2;
+  // items b and b + 8 are the two halves of one tile
+  const int q = (item >> 4) * 8 + (item & 7), ha = (item >> 3) & 1;
+  if (q >= p.UT * npairs) return;
+  const int ut = q / npairs, pair = q % npairs;
+  int TI = (int)((1.f + sqrtf(1.f + 8.f * (float)pair)) * 0.5f);
+  while (TI * (TI - 1) / 2 > pair) --TI;
+  while ((TI + 1) * TI / 2 <= pair) ++TI;
+  const int TJ = pair - TI * (TI - 1) / 2;          // 0 <= TJ < TI < T
+  uint32_t *Gu = p.G + (size_t)ut * n * Wp;
+  const int w0 = 32 * TI + 16 * ha;                 // first source word
+  // rows of tile TJ all exist (TJ < T - 1); words past the row pitch read as zero
+  {
+    u4 v[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int k = it * kMirrorThreads + threadIdx.x, r = k >> 2, c4 = k & 3;
+      v[it] = u4{0, 0, 0, 0};
+      if (w0 + 4 * c4 < Wp) v[it] = *reinterpret_cast<const u4 *>(Gu + (size_t)(1024 * TJ + r) * Wp + w0 + 4 * c4);
+    }
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int k = it * kMirrorThreads + threadIdx.x, r = k >> 2, c4 = k & 3;
+      uint32_t *d = mtile + r * kMirrorPitch + 4 * c4;
+      d[0] = v[it][0]; d[1] = v[it][1]; d[2] = v[it][2]; d[3] = v[it][3];
+    }
+  }
+  __syncthreads();
+  // square s = rows 512 s ..; its block (R, C) = rows 32 R .., word C.  The transpose of the
+  // block belongs at (C, R): a wave takes the two blocks of an unordered pair, one per
+  // 32-lane half, and writes each where the other was.  272 pairs (136 per square), 34 per
+  // wave, handled two at a time so that the lane exchanges of one hide those of the other.
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), h = lane >> 5, i = lane & 31;
+  uint32_t rot[5], keep[5];
+#pragma unroll
+  for (int st = 0; st < 5; ++st) {
+    const int k = 16 >> st;
+    const uint32_t m = k == 16 ? 0x0000FFFFu : k == 8 ? 0x00FF00FFu : k == 4 ? 0x0F0F0F0Fu : k == 2 ? 0x33333333u : 0x55555555u;
+    rot[st] = (i & k) ? k : 32 - k;
+    keep[st] = (i & k) ? ~m : m;
+  }
+  const int lane_off = i * kMirrorPitch;             // word offset of this lane's row within a block
+  for (int it = 0; it < 34; it += 2) {
+    uint32_t *src[2], *dst[2];
+    bool wr[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      // everything up to the choice between the two blocks of the pair is wave-uniform
+      const int idx = (it + u) * (kMirrorThreads / 64) + wave;       // < 272
+      const int sq = idx >= 136, t = idx - 136 * sq;
+      // t -> the t-th pair wa <= wb < 16: rows r and 15 - r of the triangle hold 17 pairs together
+      const int r = t / 17, c = t - 17 * r;
+      const int wa = c < 16 - r ? r : 15 - r, wb = c < 16 - r ? r + c : c - 1;
+      const int base = sq * 512 * kMirrorPitch;
+      const int at_ab = base + 32 * wa * kMirrorPitch + wb;             // block (wa, wb)
+      const int at_ba = base + 32 * wb * kMirrorPitch + wa;             // block (wb, wa)
+      src[u] = mtile + (h ? at_ba : at_ab) + lane_off;
+      dst[u] = mtile + (h ? at_ab : at_ba) + lane_off;
+      wr[u] = h == 0 || wa != wb;
+    }
+    uint32_t x0 = *src[0], x1 = *src[1];
+#pragma unroll
+    for (int st = 0; st < 5; ++st) {
+      x0 = transpose_stage(x0, st, rot[st], keep[st]);
+      x1 = transpose_stage(x1, st, rot[st], keep[st]);
+    }
+    if (wr[0]) *dst[0] = x0;
+    if (wr[1]) *dst[1] = x1;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int k = it * kMirrorThreads + threadIdx.x, r = k >> 3, c4 = k & 7;   // row a, 16-byte piece of its line
+    const int a = 1024 * TI + 512 * ha + r;
+    const uint32_t *sp = mtile + ((c4 >> 2) * 512 + r) * kMirrorPitch + 4 * (c4 & 3);
+    const u4 v = {sp[0], sp[1], sp[2], sp[3]};
+    if (a < n) *reinterpret_cast<u4 *>(Gu + (size_t)a * Wp + 32 * TJ + 4 * c4) = v;
+  }
+}
+
+// The launch is a fixed number of workgroups that walk over the half tiles (the grid is a
+// multiple of 16, so the two halves of a tile stay on one XCD): when the gate is closed, which
+// is the usual case, the launch costs a few hundred workgroups that exit at once.
+__global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParams p, int force, int items) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t mtile[];   // [1024][kMirrorPitch]
+  if (!force && *p.need_full == 0) return;         // sparse graph: the lists came from the edge records
+  for (int item = blockIdx.x; item < items; item += gridDim.x) {
+    mirror_half_tile(p, mtile, item);
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------- exact fix-up
+__global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
+  const int ut = blockIdx.y;                         // all problems side by side: each list is short
+  const unsigned stride = gridDim.x * blockDim.x;
+  unsigned count = p.fix_count[ut];
+  if (count > p.fix_cap) count = p.fix_cap;
+  const uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
+  const double theta = (double)p.theta[ut / p.U];
+  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const uint32_t e = list[i];
+    const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
+    const bool adj = cos64(p, ut, a, b) > theta;
+    if (adj) atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+    // ... and as a record for the neighbour lists, filed under the panel of the row; a pair of
+    // two different 1024-token tiles was only evaluated in this orientation, so it also
+    // extends the list of its column
+    // (consecutive pairs of the list mostly share their panels, and same-address atomics are
+    // served one at a time: one counter update per wave and panel)
+    const int nI = (p.n + kPanelRows - 1) / kPanelRows, lane = lane_id();
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int end = k == 0 ? b / kPanelRows : a / kPanelRows;
+      const bool want = adj && (k == 0 || (a >> 10) != (b >> 10));
+      unsigned long long todo = __ballot(want);
+      while (todo) {                                   // wave-uniform
+        const int leader = __builtin_ctzll(todo);
+        const int which = __shfl(end, leader);
+        const unsigned long long same = __ballot(want && end == which) & todo;
+        const size_t bucket = (size_t)ut * nI + which;
+        unsigned at = 0;
+        if (lane == leader) at = atomicAdd(p.fecount + bucket, (unsigned)__popcll(same));
+        at = __shfl(at, leader) + (unsigned)__popcll(same & ((1ull << lane) - 1ull));
+        if ((same >> lane) & 1ull) {
+          if (at < (unsigned)kFixBucket) p.fedges[bucket * kFixBucket + at] = e;
+          else atomicOr(p.need_full, 1u);
+        }
+        todo &= ~same;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- degrees and neighbour lists
+// One wave per row of G: degree (Eq. 10) and, for rows of at most kListCap neighbours, the
+// neighbour indices as a compact uint16 list, so that the merge rounds touch a few hundred
+// bytes per token instead of the whole bitmap row.  Denser rows keep using the bitmap.
+__device__ __forceinline__ void lists_of_rows(const ShallowParams &p, int ut, int group) {
+  const int n = p.n, Wp = p.Wp;
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int row0 = (group * 4 + wave) * 4;
+  constexpr int kHold = 8;                           // 16-byte pieces of a row a lane keeps: rows of up to 65536 bits
+  for (int v = row0; v < row0 + 4 && v < n; ++v) {
+    const u4 *row = reinterpret_cast<const u4 *>(p.G + ((size_t)ut * n + v) * Wp);
+    u4 q[kHold];                                     // the row is read once
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < kHold; ++i) {
+      const int w4 = lane + i * kWave;
+      q[i] = w4 < Wp / 4 ? row[w4] : u4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int i = 0; i < kHold; ++i) c += __popc(q[i][0]) + __popc(q[i][1]) + __popc(q[i][2]) + __popc(q[i][3]);
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int x = __shfl_up(incl, o);
+      if (lane >= o) incl += x;
+    }
+    const int deg = __shfl(incl, 63);
+    if (lane == 0) {
+      const size_t i = (size_t)ut * n + v;
+      p.deg0[i] = deg;
+      p.key[i] = ((uint32_t)deg << 16) | (uint32_t)(0xFFFF - v);
+      p.alive[i] = v;
+      p.slot[i] = -1;
+      p.gone8[(size_t)ut * p.n16 + v] = 0;
+      if (v == 0) p.counters[(size_t)ut * kCounters + C_ALIVE0] = n;
+      if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = deg;
+    }
+    if (deg <= kListCap) {
+      uint16_t *dst = p.nbr + ((size_t)ut * n + v) * kListCap;
+      int at = incl - c;                               // neighbours in the words of lower lanes
+#pragma unroll
+      for (int i = 0; i < kHold; ++i) {
+        const int w4 = lane + i * kWave;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          uint32_t bits = q[i][j];
+          while (bits) {
+            const int t = __builtin_ctz(bits);
+            bits &= bits - 1;
+            dst[list_slot(at++)] = (uint16_t)((w4 * 4 + j) * 32 + t);
+          }
+        }
+      }
+    }
+  }
+}
+
+// Fixed-size launch like shallow_mirror: the workgroups walk over the groups of 16 rows.
+__global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force) {
+  if (!force && *p.need_full == 0) return;         // sparse graph: done by shallow_edge_lists
+  const int groups = (p.n + 15) / 16;
+  for (int group = blockIdx.x; group < groups; group += gridDim.x) lists_of_rows(p, blockIdx.y, group);
+}
+
+// ---------------------------------------------------------------- lists from edge records
+// Sparse graphs: degrees (Eq. 10) and neighbour lists straight from the records of set bits
+// shallow_gram and shallow_fixup left, without reading G.  One block per panel of 256 rows;
+// the first 128 entries of every list are collected in LDS and written out in whole pieces.
+// A record (a, b) of the panel's own segments puts b on the list of a.  G is symmetric and
+// only computed from each row's own 1024-token tile on, so a record (a', b) of an earlier
+// panel with b in a later tile also puts a' on the list of b: the block scans the segments
+// of all earlier tiles' panels for its own chunk and keeps the records that end in its rows
+// (inside a tile both orientations were computed and recorded).  Fill counts live in LDS;
+// the order of a list is whatever the LDS atomics make it, which no consumer depends on.
+// A row with more than kListCap neighbours, or a segment that ran full, raises need_full:
+// shallow_mirror and shallow_lists then redo everything from the bitmap.
+constexpr int kEdgeThreads = 1024;
+constexpr int kEdgeLds = 128;                      // list entries per row collected in LDS; later ones go straight to memory
+
+// kCap: the segment capacity when it is the smallest one (long sequences), else 0 = read it from
+// the parameters; with the constant the compiler unrolls the record loop and batches its loads
+// (0.14 ms against 0.21 ms on a 32k-token layer).
+template <int kCap>
+__global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams p, int force) {
+  __shared__ int cursor[kPanelRows];
+  __shared__ __attribute__((aligned(16))) uint16_t part[kPanelRows][kEdgeLds];
+  if (force || *p.need_full != 0) return;
+  const int n = p.n, ut = blockIdx.y;
+  const int nI = (n + kPanelRows - 1) / kPanelRows, nJc = (n + kChunkCols - 1) / kChunkCols;
+  const int I = nI - 1 - (int)blockIdx.x;            // panels with more segments to scan first
+  const int row0 = I * kPanelRows, Jm = row0 / kChunkCols;
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+  uint16_t *lists = p.nbr + ((size_t)ut * n + row0) * kListCap;
+  if (tid < kPanelRows) cursor[tid] = 0;
+  __syncthreads();
+  auto add = [&](int row, int other) {
+    const int r = row - row0;
+    const int pos = atomicAdd(&cursor[r], 1);
+    if (pos < kEdgeLds) part[r][list_slot(pos)] = (uint16_t)other;
+    else if (pos < kListCap) lists[(size_t)r * kListCap + list_slot(pos)] = (uint16_t)other;
+  };
+  const int nown = 4 * (nJc - Jm);                   // (chunk, wave) segments of this panel
+  const int nin = 16 * Jm;                           // (panel, wave) segments of earlier tiles for this tile's chunk
+  constexpr int kBatch = 4;                          // segments a wave has in flight
+  for (int k0 = wave * kBatch; k0 < nown + nin; k0 += (kEdgeThreads / 64) * kBatch) {
+    const uint32_t *e[kBatch];
+    int cnt[kBatch];
+    bool own[kBatch];
+    int most = 0;
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int k = k0 + u;
+      own[u] = k < nown;
+      const int kk = own[u] ? k : k - nown;
+      const int J = own[u] ? Jm + (kk >> 2) : Jm;
+      const int Ip = own[u] ? I : kk >> 2;
+      const size_t seg = (((size_t)ut * nJc + J) * nI + Ip) * 4 + (kk & 3);
+      const unsigned cn = k < nown + nin ? p.ecount[seg] : 0u;
+      const int cap = kCap ? kCap : p.seg_cap;
+      cnt[u] = cn < (unsigned)cap ? (int)cn : cap;
+      e[u] = p.edges + seg * cap;
+      most = cnt[u] > most ? cnt[u] : most;
+    }
+    for (int i0 = 0; i0 < most; i0 += kWave) {
+      uint32_t rec[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) rec[u] = i0 + lane < cnt[u] ? e[u][i0 + lane] : 0xFFFFFFFFu;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        if (i0 + lane < cnt[u]) {
+          const int a = (int)(rec[u] >> 16), b = (int)(rec[u] & 0xFFFFu);
+          if (own[u]) add(a, b);
+          else if (b >= row0 && b < row0 + kPanelRows) add(b, a);
+        }
+    }
+  }
+  {
+    // pairs decided in double precision that have an end in this panel
+    const size_t bucket = (size_t)ut * nI + I;
+    const unsigned fn = p.fecount[bucket];
+    const int fc = (int)(fn < (unsigned)kFixBucket ? fn : (unsigned)kFixBucket);
+    const uint32_t *fe = p.fedges + bucket * kFixBucket;
+    for (int i = tid; i < fc; i += kEdgeThreads) {
+      const uint32_t rec = fe[i];
+      const int a = (int)(rec >> 16), b = (int)(rec & 0xFFFFu);
+      if (a >= row0 && a < row0 + kPanelRows) add(a, b);
+      if ((a >> 10) != (b >> 10) && b >= row0 && b < row0 + kPanelRows) add(b, a);   // other tile: evaluated once
+    }
+  }
+  __syncthreads();
+  // the collected part of each list goes out in 16-byte pieces
+  for (int k = tid; k < kPanelRows * (kEdgeLds / 8); k += kEdgeThreads) {
+    const int r = k / (kEdgeLds / 8), piece = k % (kEdgeLds / 8);
+    const int have = cursor[r] < kEdgeLds ? cursor[r] : kEdgeLds;
+    // piece = half of a lane's 16 entries: entries (piece >> 1) + 8 j for j = 8 (piece & 1) ...
+    if (row0 + r < n && have > (piece >> 1) + 64 * (piece & 1))
+      *reinterpret_cast<u4 *>(lists + (size_t)r * kListCap + piece * 8) = *reinterpret_cast<const u4 *>(&part[r][piece * 8]);
+  }
+  if (tid < kPanelRows && row0 + tid < n) {
+    const int v = row0 + tid, deg = cursor[tid];
+    const size_t i = (size_t)ut * n + v;
+    p.deg0[i] = deg;
+    p.key[i] = ((uint32_t)deg << 16) | (uint32_t)(0xFFFF - v);
+    p.alive[i] = v;
+    p.slot[i] = -1;
+    p.gone8[(size_t)ut * p.n16 + v] = 0;
+    if (v == 0) p.counters[(size_t)ut * kCounters + C_ALIVE0] = n;
+    if (p.deg_out[ut / p.U]) p.deg_out[ut / p.U][(size_t)(ut % p.U) * n + v] = deg;
+    if (deg > kListCap) atomicOr(p.need_full, 1u);
+  }
+}
+
+
+}  // namespace
+
+spindle_status launch_graph(const ShallowParams &p, hipStream_t st, int force) {
+  const int n = p.n;
+  const dim3 pgrid((n + 63) / 64, p.UT);
+  { ProfScope ps("shallow_prep", st);
+  if (p.dtype == SPINDLE_F16) hipLaunchKernelGGL(shallow_prep<SPINDLE_F16>, pgrid, dim3(256), 0, st, p);
+  else if (p.dtype == SPINDLE_BF16) hipLaunchKernelGGL(shallow_prep<SPINDLE_BF16>, pgrid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(shallow_prep<SPINDLE_F32>, pgrid, dim3(256), 0, st, p); }
+
+  const int nI = (n + kPanelRows - 1) / kPanelRows;
+  const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
+  const int pairs8 = (p.UT * nJ + 7) / 8;
+  { ProfScope ps("shallow_gram", st);
+  hipLaunchKernelGGL(shallow_gram<false>, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p); }
+  { ProfScope ps("shallow_gram_exact", st);
+  hipLaunchKernelGGL(shallow_gram<true>, dim3(1024), dim3(kGramThreads), 0, st, p); }
+  { ProfScope ps("shallow_fixup", st);
+  hipLaunchKernelGGL(shallow_fixup, dim3(128, p.UT), dim3(256), 0, st, p); }
+
+  // sparse graphs: lists from the edge records; otherwise (or when the caller wants the
+  // adjacency matrix) the lower triangle is written and the lists come from the bitmap
+  { ProfScope ps("shallow_edge_lists", st);
+  const dim3 eg(nI, p.UT);
+  if (p.seg_cap == 512) hipLaunchKernelGGL(shallow_edge_lists<512>, eg, dim3(kEdgeThreads), 0, st, p, force);
+  else hipLaunchKernelGGL(shallow_edge_lists<0>, eg, dim3(kEdgeThreads), 0, st, p, force); }
+  const int T1k = (n + 1023) / 1024, npairs = T1k * (T1k - 1) / 2;
+  if (npairs > 0) {
+    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_mirror),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMirrorLds));
+    ProfScope ps("shallow_mirror", st);
+    const int items = 16 * ((p.UT * npairs + 7) / 8);
+    hipLaunchKernelGGL(shallow_mirror, dim3(items < 512 ? items : 512), dim3(kMirrorThreads), kMirrorLds, st, p, force, items);
+  }
+  SPINDLE_HIP(hipGetLastError());
+  { ProfScope ps("shallow_lists", st);
+  const int groups = (n + 15) / 16;
+  hipLaunchKernelGGL(shallow_lists, dim3(groups < 128 ? groups : 128, p.UT), dim3(256), 0, st, p, force); }
+  SPINDLE_HIP(hipGetLastError());
+  return SPINDLE_OK;
+}
+
+}  // namespace spindle
