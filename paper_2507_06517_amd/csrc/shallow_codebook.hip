@@ -219,14 +219,23 @@ __global__ __launch_bounds__(kAssignThreads, 2) void shallow_assign(ShallowParam
     if (nm > runmax[cb] + band2) cnt[cb] = 0;         // everything collected so far is out of reach
     runmax[cb] = nm;
     const float thr = nm - band2;
-    if (valid[cb]) {
-      uint2 *list = cand + ((size_t)slot[cb] * 2 + g) * kCandCap;
+    // bit v of `hits`: a[v] >= thr, from the sign of a[v] - thr (sixteen tests and branches, one per
+    // value, cost several times the matrix instructions of the tile; hits are rare)
+    uint32_t miss = 0;
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        if (a[v] >= thr) {
-          if (cnt[cb] < kCandCap) list[cnt[cb]] = make_uint2((uint32_t)(j0 + 16 * g + v), __float_as_uint(a[v]));
-          ++cnt[cb];
-        }
+    for (int v = 15; v >= 0; --v) miss = __builtin_amdgcn_alignbit(miss, __float_as_uint(a[v] - thr), 31);
+    uint32_t hits = valid[cb] ? ~miss & 0xFFFFu : 0u;
+    if (hits) {
+      uint2 *list = cand + ((size_t)slot[cb] * 2 + g) * kCandCap;
+      do {
+        const int v = __builtin_ctz(hits);
+        hits &= hits - 1;
+        float val = a[0];
+#pragma unroll
+        for (int u = 1; u < 16; ++u) val = v == u ? a[u] : val;
+        if (cnt[cb] < kCandCap) list[cnt[cb]] = make_uint2((uint32_t)(j0 + 16 * g + v), __float_as_uint(val));
+        ++cnt[cb];
+      } while (hits);
     }
   };
 
