@@ -16,7 +16,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "spindle_oracle.c")
-_LIB = os.path.join(_HERE, "libspindle_oracle.so")
+# SPINDLE_ORACLE_LIB: load this library instead (the mutation check of the pins compiles deliberately
+# broken copies of the C file and runs the pin tests against them).
+_OVERRIDE = os.environ.get("SPINDLE_ORACLE_LIB")
+_LIB = _OVERRIDE or os.path.join(_HERE, "libspindle_oracle.so")
 _lib = None
 
 _f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
@@ -26,6 +29,8 @@ _u32p = np.ctypeslib.ndpointer(dtype=np.uint32, flags="C_CONTIGUOUS")
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc -O2 (no fast-math: summation order is part of its definition)."""
+    if _OVERRIDE:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
                                "-o", _LIB, _SRC, "-lm"])

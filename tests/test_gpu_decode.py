@@ -159,6 +159,27 @@ def test_duplicates_zero_vectors_and_equal_entries(oracle):
     run_and_check(oracle, new, Cb, np.array([[6]], dtype=np.int32), dtype, -0.5)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_cosine_exactly_at_the_threshold(oracle, dtype):
+    # cos((1, 1, 1, 1), e_0) = 1 / 2 with every intermediate exact: the comparison of Eq. 9 is
+    # strict, so at theta = 1/2 the token founds an entry, just below it merges.  Tokens 1 and 2
+    # meet each other at exactly 1/2 as well ((1, 1, 0, 0) and (1, 0, 1, 0)): not adjacent at 1/2.
+    d = 128
+    Cb = np.zeros((1, 2, 8, d), dtype=np.float32)
+    Cb[:, :, 0, 0] = 1.0
+    new = np.zeros((1, 2, 3, d), dtype=np.float32)
+    new[:, :, 0, :4] = 1.0
+    new[:, :, 1, [4, 5]] = 1.0
+    new[:, :, 2, [4, 6]] = 1.0
+    Cb, new = wl.cast(Cb, dtype), wl.cast(new, dtype)
+    nc = np.array([[1, 1]], dtype=np.int32)
+    res, _, _ = run_and_check(oracle, new, Cb, nc, dtype, 0.5)
+    assert res[0]["n_matched"] == 0 and res[0]["ref"].tolist() == [1, 2, 3]
+    below = float(np.nextafter(np.float32(0.5), np.float32(0)))
+    res, _, _ = run_and_check(oracle, new, Cb, nc, dtype, below)
+    assert res[0]["n_matched"] == 1 and res[0]["ref"].tolist() == [0, 1, 1]
+
+
 def test_two_steps_in_a_row(oracle):
     # the codebook grows over two calls; fp32 storage, where both sides round the new rows alike
     import torch

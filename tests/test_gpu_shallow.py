@@ -112,6 +112,30 @@ def test_duplicates_and_zero_vectors(oracle):
     assert len(set(g["ref_k"][0, 0, 100:150].tolist() + [g["ref_k"][0, 0, 7]])) == 1
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_cosine_exactly_at_the_threshold(oracle, dtype):
+    # cos(e_0 + e_1 + e_2 + e_3, e_0) = 1 / 2 and cos(e_4 + e_5, e_4 + e_6) = 1 / 2 with every
+    # intermediate exact in any precision: Eq. 9 is strict, so at theta = 1/2 these pairs are not
+    # adjacent, and one float below they are (the approximate cosine sits inside the guard band,
+    # the double-precision decision has to get the equality right)
+    L = wl.small_random(14, dtype, B=1, H=1, l=300, lw=1, cap=300)
+    rows = np.zeros((8, L.K.shape[-1]))
+    rows[0, 0] = 1
+    rows[1, :4] = 1
+    rows[2, [4, 5]] = 1
+    rows[3, [4, 6]] = 1
+    rows[4:] = 4 * rows[:4]                            # the same again, scaled: magnitudes drop out
+    L.K[0, 0, 40:48] = wl.cast(rows, dtype)
+    L.V[0, 0, 40:48] = wl.cast(rows, dtype)
+    L.theta_k = L.theta_v = 0.5
+    res, g = parity.check_shallow_layer(oracle, L)
+    adj = lambda a, b: (g["adj_k"][0, 0, a, b >> 5] >> (b & 31)) & 1
+    assert adj(40, 41) == 0 and adj(42, 43) == 0 and adj(40, 45) == 0 and adj(40, 44) == 1 and adj(41, 45) == 1
+    L.theta_k = L.theta_v = float(np.nextafter(np.float32(0.5), np.float32(0)))
+    res, g = parity.check_shallow_layer(oracle, L)
+    assert adj(40, 41) == 1 and adj(42, 43) == 1 and adj(40, 45) == 1
+
+
 def test_cut_tokens_with_many_equidistant_entries(oracle):
     # zero vectors have cosine 0 with every entry: when their own entry is cut, every stored entry
     # ties, the candidate lists of the matrix-core search run full and the exhaustive search must

@@ -104,3 +104,16 @@ def test_zero_vectors_and_no_new_tokens_of_note(oracle):
     # a zero vector has cosine 0 with everything: unmatched, and each is its own (zero) entry
     assert o["ref"].tolist() == [4, 1, 5] and o["n_found"] == 6
     assert not o["C_new"].any() and o["mag"].tolist() == [0.0, 2.0, 0.0]
+
+
+def test_threshold_is_strict(oracle):
+    # a 3-4-5 triangle: cos((4, 3), (1, 0)) = 4 / 5, the same double as the literal 0.8.  Eq. 9 is a
+    # strict comparison, so at theta = 0.8 the token does not merge and founds an entry of its own
+    Cb = np.array([[1.0, 0.0, 0.0, 0.0]])
+    X = np.array([[4.0, 3.0, 0.0, 0.0]])
+    assert 4.0 / (5.0 * 1.0) == 0.8
+    o = oracle.decode_merge(X, Cb, 0.8, 8)
+    assert o["n_matched"] == 0 and o["ref"].tolist() == [1] and o["n_found"] == 2
+    np.testing.assert_allclose(o["C_new"], [[0.8, 0.6, 0.0, 0.0]], rtol=1e-15)
+    o = oracle.decode_merge(X, Cb, np.nextafter(0.8, 0.0), 8)
+    assert o["n_matched"] == 1 and o["ref"].tolist() == [0] and o["n_found"] == 1
