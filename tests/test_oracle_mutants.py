@@ -25,6 +25,9 @@ MUTANTS = [
     ("group_sum_instead_of_mean", "out[a] /= (double)hn;", "out[a] /= 1.0;", 0, DEEP),
     ("window_sum_skips_first_query", "for (int b = 0; b < lw; ++b) {\n            const double *q",
      "for (int b = 1; b < lw; ++b) {\n            const double *q", 0, DEEP),
+    ("weights_not_divided_by_the_row_sum", "acc[a] += exp(s[a] - M) / Z;", "acc[a] += exp(s[a] - M);", 0, DEEP),
+    ("query_position_off_by_one", "int p = lc + b;                       /* position of this query */",
+     "int p = lc + b - 1;", 0, DEEP),
     ("pool_radius_one_too_wide", "int r = (P - 1) / 2;", "int r = (P + 1) / 2;", 0, DEEP),
     ("topk_ties_take_the_higher_index", "return (a > b) - (a < b);", "return (a < b) - (a > b);", 0, DEEP),
     ("window_positions_shifted", "kept[k + b] = lc + b;", "kept[k + b] = lc + b - 1;", 0, DEEP),
@@ -33,6 +36,10 @@ MUTANTS = [
     ("threshold_not_strict", "if (oracle_cos(X, m, d, a, b) > theta) {", "if (oracle_cos(X, m, d, a, b) >= theta) {", 0, SHALLOW),
     ("no_diagonal", "        SETBIT(G + (size_t)a * W, a);\n", "", 0, SHALLOW),
     ("adjacency_not_mirrored", "                SETBIT(G + (size_t)b * W, a);\n", "", 0, SHALLOW),
+    ("row_spot_check_without_diagonal", "if (b == a || oracle_cos(X, m, d, a, b) > theta) SETBIT(row, b);",
+     "if (oracle_cos(X, m, d, a, b) > theta) SETBIT(row, b);", 0, SHALLOW),
+    ("references_numbered_from_one", "for (int b = 0; b < n; ++b) if (GETBIT(row, b)) ref[b] = nc;",
+     "for (int b = 0; b < n; ++b) if (GETBIT(row, b)) ref[b] = nc + 1;", 0, SHALLOW),
     ("literal_loop_keeps_removed_columns", "ga[w] &= ~row[w];", "ga[w] &= ~0u;", 0, SHALLOW),
     ("incremental_loop_ties_take_the_higher_index",
      "if (alive[a] && deg[a] > bestdeg)", "if (alive[a] && deg[a] >= bestdeg)", 0, SHALLOW),
@@ -47,6 +54,8 @@ MUTANTS = [
     ("decode_new_entries_not_appended", "ref[rest[j]] = rr[j] < room ? nc + rr[j] : -1;",
      "ref[rest[j]] = rr[j] < room ? rr[j] : -1;", 0, DECODE),
     ("budget_second_case_as_printed", "r1 = 2.0 * rc - 1.0;", "r1 = 1.0 - 2.0 * rc;", 0, HELPERS),
+    ("budget_first_case_without_beta", "r0 = 2.0 * rc - beta; r1 = beta;", "r0 = 2.0 * rc; r1 = beta;", 0, HELPERS),
+    ("r1_inverted", "out[0] = kept / total;", "out[0] = total / kept;", 0, HELPERS),
     ("alpha_without_the_half", "double alpha = 0.5 * (1.0 + beta);", "double alpha = 1.0 + beta;", 0, HELPERS),
     ("r3_without_the_magnitude", "out[2] = (dh + (double)int_bit / key_bit + 1.0) / dh;",
      "out[2] = (dh + (double)int_bit / key_bit) / dh;", 0, HELPERS),

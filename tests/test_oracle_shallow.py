@@ -83,6 +83,13 @@ def test_adjacency_bruteforce(oracle):
         assert np.array_equal(pack(Gb), G)
         for a in [0, n // 2, n - 1]:
             assert np.array_equal(oracle.adjacency_row(X, theta, a), G[a])
+    # a zero vector has cosine 0 with everything, itself included, and is still its own neighbour:
+    # in the full matrix and in the single-row form used for spot checks at full size
+    X, _ = clustered(rng, 40, 128, 3, 0.1)
+    X[7] = 0.0
+    G, deg = oracle.adjacency(X, 0.9)
+    assert deg[7] == 1 and unpack(G, 40)[7].nonzero()[0].tolist() == [7]
+    assert np.array_equal(oracle.adjacency_row(X, 0.9, 7), G[7])
 
 
 def test_strict_threshold(oracle):
