@@ -63,6 +63,23 @@ def test_decode_merge_sizes_and_types(oracle, dtype, m):
         assert any(o["n_matched"] > 0 for o in res) and any(o["n_found"] > k for o, k in zip(res, nc.ravel()))
 
 
+@pytest.mark.parametrize("dtype,m", [("f16", 64), ("f32", 3), ("bf16", 200)])
+def test_stored_rows_need_not_be_unit_length(oracle, dtype, m):
+    # Eq. 4 divides by the stored row's own norm: rows stretched by 0.25 .. 3 match the same tokens
+    theta = 0.95 if dtype == "bf16" else 0.98
+    pre, new = wl.decode_case(100 + m, dtype, B=1, H=2, n_prefill=400, m=m)
+    Cb, nc = stored_codebooks(oracle, pre, dtype, theta, 300, [[300, 300]])
+    rng = np.random.default_rng(m)
+    stretched = wl.cast(wl.to_f64(Cb, dtype) * rng.uniform(0.25, 3.0, Cb.shape[:3])[..., None], dtype)
+    res, _, _ = run_and_check(oracle, new, stretched, nc, dtype, theta)
+    unit, _, _ = run_and_check(oracle, new, Cb, nc, dtype, theta)
+    if m >= 64:
+        assert any(o["n_matched"] > 0 for o in res)
+        # (rounding of the stretched rows can move a knife-edge pair, so only the bulk is compared)
+        same = sum(int((a["ref"] == b["ref"]).sum()) for a, b in zip(res, unit))
+        assert same >= 0.95 * 2 * m
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_decode_sweep(oracle, seed):
     # later-token counts around the tile of 16, tables around the slice of 512 entries, loose and

@@ -64,6 +64,11 @@ def test_scaled_copies_of_entries_all_merge(oracle):
     assert o["n_matched"] == 40 and o["n_found"] == 12 and o["C_new"].shape[0] == 0
     assert np.array_equal(o["ref"], which)
     np.testing.assert_allclose(o["mag"], scale, rtol=1e-14)
+    # the cosine of Eq. 4 divides by the stored row's own norm: rows that are not of unit length
+    # (as after rounding to the storage type, here grossly) give the same matches
+    stretch = rng.uniform(0.25, 3.0, 12)
+    o2 = oracle.decode_merge(Cb[which] * scale[:, None], Cb * stretch[:, None], 0.98, 12)
+    assert o2["n_matched"] == 40 and np.array_equal(o2["ref"], which)
 
 
 def test_against_dense_numpy(oracle):

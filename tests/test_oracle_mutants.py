@@ -28,11 +28,13 @@ MUTANTS = [
     ("weights_not_divided_by_the_row_sum", "acc[a] += exp(s[a] - M) / Z;", "acc[a] += exp(s[a] - M);", 0, DEEP),
     ("query_position_off_by_one", "int p = lc + b;                       /* position of this query */",
      "int p = lc + b - 1;", 0, DEEP),
+    ("pool_ignores_the_first_position", "if (j >= 0 && j < n && x[j] > m) m = x[j];", "if (j >= 1 && j < n && x[j] > m) m = x[j];", 0, DEEP),
     ("pool_radius_one_too_wide", "int r = (P - 1) / 2;", "int r = (P + 1) / 2;", 0, DEEP),
     ("topk_ties_take_the_higher_index", "return (a > b) - (a < b);", "return (a < b) - (a > b);", 0, DEEP),
     ("window_positions_shifted", "kept[k + b] = lc + b;", "kept[k + b] = lc + b - 1;", 0, DEEP),
     ("magnitude_without_root", "m[a] = sqrt(ss);", "m[a] = ss;", 0, SHALLOW),
     ("cosine_of_zero_vector_is_one", "return den > 0.0 ? dot / den : 0.0;", "return den > 0.0 ? dot / den : 1.0;", 0, SHALLOW),
+    ("cosine_denominator_uses_one_norm_twice", "double den = m[a] * m[b];", "double den = m[a] * m[a];", 0, SHALLOW),
     ("threshold_not_strict", "if (oracle_cos(X, m, d, a, b) > theta) {", "if (oracle_cos(X, m, d, a, b) >= theta) {", 0, SHALLOW),
     ("no_diagonal", "        SETBIT(G + (size_t)a * W, a);\n", "", 0, SHALLOW),
     ("adjacency_not_mirrored", "                SETBIT(G + (size_t)b * W, a);\n", "", 0, SHALLOW),
@@ -40,6 +42,10 @@ MUTANTS = [
      "if (oracle_cos(X, m, d, a, b) > theta) SETBIT(row, b);", 0, SHALLOW),
     ("references_numbered_from_one", "for (int b = 0; b < n; ++b) if (GETBIT(row, b)) ref[b] = nc;",
      "for (int b = 0; b < n; ++b) if (GETBIT(row, b)) ref[b] = nc + 1;", 0, SHALLOW),
+    ("literal_loop_keeps_rows_of_removed_tokens", "if (GETBIT(row, a)) { for (int w = 0; w < W; ++w) ga[w] = 0; }",
+     "if (0) { for (int w = 0; w < W; ++w) ga[w] = 0; }", 0, SHALLOW),
+    ("incremental_loop_rereferences_removed_tokens", "if (alive[b] && GETBIT(row, b)) { ref[b] = nc; dying[nd++] = b; }",
+     "if (GETBIT(row, b)) { ref[b] = nc; if (alive[b]) dying[nd++] = b; }", 0, SHALLOW),
     ("literal_loop_keeps_removed_columns", "ga[w] &= ~row[w];", "ga[w] &= ~0u;", 0, SHALLOW),
     ("incremental_loop_ties_take_the_higher_index",
      "if (alive[a] && deg[a] > bestdeg)", "if (alive[a] && deg[a] >= bestdeg)", 0, SHALLOW),
@@ -50,6 +56,7 @@ MUTANTS = [
     ("reconstruction_without_magnitude", "C[(size_t)ref[a] * d + t] * mag[a];", "C[(size_t)ref[a] * d + t];", 0, SHALLOW),
     ("decode_takes_the_last_suitable_entry", "if (cs > theta && cs > bv) { bv = cs; best = c; }",
      "if (cs > theta) { bv = cs; best = c; }", 0, DECODE),
+    ("decode_ignores_the_entry_norm", "double den = mag[a] * cn[c];", "double den = mag[a];", 0, DECODE),
     ("decode_threshold_not_strict", "if (cs > theta && cs > bv)", "if (cs >= theta && cs > bv)", 0, DECODE),
     ("decode_new_entries_not_appended", "ref[rest[j]] = rr[j] < room ? nc + rr[j] : -1;",
      "ref[rest[j]] = rr[j] < room ? rr[j] : -1;", 0, DECODE),
