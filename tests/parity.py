@@ -77,10 +77,11 @@ def check_deep_unit(p64, kept64, p_gpu, kept_gpu, lw, l, report):
     assert band[diff[diff < lc]].all() if len(diff) else True
 
 
-def check_deep_layer(orc, L: wl.Layer, budget=None, norm=0):
+def check_deep_layer(orc, L: wl.Layer, budget=None, norm=0, got=None):
+    """got: (kept, K_out bits, V_out bits, scores) of an earlier gpu_deep call instead of a new one."""
     budget = budget or L.budget
     p64, kept64 = oracle_deep(orc, L, budget, norm)
-    kept, Ko, Vo, sc = gpu_deep(L, budget, norm)
+    kept, Ko, Vo, sc = got if got is not None else gpu_deep(L, budget, norm)
     report = {}
     B, H, l, d = L.K.shape
     for b in range(B):
