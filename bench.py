@@ -135,6 +135,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--seq-len", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="time the eviction call and the codebook call one after the other on one stream "
+                         "(default: the eviction call runs on a side stream beside the second half of the codebook call)")
     ap.add_argument("--workload", choices=["config4", "config5"], default="config4",
                     help="config4 = the benchmark configuration; config5 = one layer of the batch-4 bf16 stack "
                          "(half of the tokens isolated noise, codebook cut to --cap): a secondary figure")
@@ -157,10 +160,14 @@ def main():
     deep = sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, want_scores=False)
     shallow = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)
     stream = torch.cuda.current_stream()
+    layer = sb.OverlappedLayer(deep, shallow)
 
     def step():
-        deep.run(K, V, Q)
-        shallow.run(K, V)
+        if args.one_stream:
+            deep.run(K, V, Q)
+            shallow.run(K, V)
+        else:
+            layer.run(K, V, Q)                       # eviction on a side stream beside the codebook loop
 
     for _ in range(args.warmup):
         step()
@@ -178,8 +185,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        deep.run(K, V, Q)
-        shallow.run(K, V)
+        step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     gram_recs = [ms for name, ms in sb.spindle_profile_read() if name == "shallow_gram"]
@@ -242,8 +248,12 @@ def main():
                    (f"configs[4], one layer: batch 4, 8 KV heads x 4 Q heads, head_dim 128, seq_len {L.seq_len}, "
                     f"bf16, half clustered / half noise; deep: window 64, pool 15, budget {L.budget}; "
                     f"shallow: K and V, theta 0.98/0.95, cap {L.max_codes}")},
-        "breakdown_pass": "deep_ms, shallow_ms and kernel_ms come from a second pass of the same steps with HIP events "
-                          "around every kernel, which lengthens the step; roofline uses the timed steps' own events",
+        "streams": ("one" if args.one_stream else
+                    "two: the eviction call runs on a side stream beside the second half of the codebook call "
+                    "(spindle_shallow_graph, event, spindle_shallow_codebook)"),
+        "breakdown_pass": "deep_ms, shallow_ms and kernel_ms come from a second pass with the two calls one after the "
+                          "other on one stream and HIP events around every kernel, which lengthens the step; "
+                          "roofline uses the timed steps' own events",
         "ms_per_step_with_all_events": ms_step_all_events,
         "deep_ms": ms_deep, "shallow_ms": ms_shallow,
         "deep_tokens_per_s": tokens / (ms_deep * 1e-3), "shallow_tokens_per_s": tokens / (ms_shallow * 1e-3),

@@ -8,7 +8,8 @@
  *   spindle_compress_deep     attention-weight token eviction
  *                             (Sec. "Attention Weight Based Token Eviction", Eq. 1-3, 7)
  *   spindle_compress_shallow  similarity codebook replacement
- *                             (Sec. "Similarity Based Token Replacement", Eq. 8-13, Alg. 1)
+ *                             (Sec. "Similarity Based Token Replacement", Eq. 8-13, Alg. 1);
+ *                             spindle_shallow_graph + spindle_shallow_codebook = its two halves
  *   spindle_reconstruct       codebook look-up and rescale (Eq. 14)
  *   spindle_decode_merge      tokens generated later join the stored codebook or extend it
  *                             (same section, the paragraph after Eq. 14)
@@ -160,6 +161,38 @@ spindle_status spindle_shallow_workspace_bytes(const spindle_kv_desc *desc, int3
  * seq_len <= 65535.
  */
 spindle_status spindle_compress_shallow(const spindle_kv_desc *desc, const void *K, const void *V,
+                                        float theta_k, float theta_v, int32_t max_codes,
+                                        void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v,
+                                        int32_t *n_found_k, int32_t *n_found_v,
+                                        int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v,
+                                        uint32_t *adj_k, uint32_t *adj_v,
+                                        int32_t *deg_k, int32_t *deg_v,
+                                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * spindle_compress_shallow in two halves, for a caller that overlaps other work with the
+ * second one (e.g. the eviction call of another layer on a second stream that waits for an
+ * event recorded between the two):
+ *   spindle_shallow_graph     magnitudes, similarities, G, degrees and neighbour lists
+ *                             (Eq. 4, 8-10): the phase that fills the chip.  Writes mag_*,
+ *                             adj_* and deg_* if given, clears C* and sets n_codes_* to -1;
+ *                             everything else goes to the workspace
+ *   spindle_shallow_codebook  the loop of Alg. 1 (Eq. 11-13), the cap and the outputs C*,
+ *                             n_codes_*, n_found_*, ref_*: mostly one workgroup per unit,
+ *                             most of the chip is idle meanwhile
+ * Both take exactly the arguments of spindle_compress_shallow, validated the same way, and
+ * must be given the same values and the same workspace, untouched in between; calling the
+ * first and then the second on one stream is the same as the single call.
+ */
+spindle_status spindle_shallow_graph(const spindle_kv_desc *desc, const void *K, const void *V,
+                                     float theta_k, float theta_v, int32_t max_codes,
+                                     void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v,
+                                     int32_t *n_found_k, int32_t *n_found_v,
+                                     int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v,
+                                     uint32_t *adj_k, uint32_t *adj_v,
+                                     int32_t *deg_k, int32_t *deg_v,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+spindle_status spindle_shallow_codebook(const spindle_kv_desc *desc, const void *K, const void *V,
                                         float theta_k, float theta_v, int32_t max_codes,
                                         void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v,
                                         int32_t *n_found_k, int32_t *n_found_v,

@@ -23,11 +23,14 @@ F32, F16, BF16 = 0, 1, 2
 NORM_PAPER, NORM_NONE = 0, 1
 _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 
+# the first N_STATUS return a status code
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
-           "spindle_compress_shallow", "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
+           "spindle_compress_shallow", "spindle_shallow_graph", "spindle_shallow_codebook",
+           "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
            "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_decode_workspace_bytes", "spindle_decode_merge",
            "spindle_profile_read",
            "spindle_last_error", "spindle_version"]
+N_STATUS = 13
 
 
 class KvDesc(C.Structure):
@@ -57,7 +60,8 @@ def lib():
         L.spindle_compress_deep.argtypes = [C.POINTER(KvDesc), vp, vp, vp, i32, i32, f32, i32, i32, vp, i32,
                                             vp, vp, vp, vp, vp, sz, vp]
         L.spindle_shallow_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
-        L.spindle_compress_shallow.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 14 + [vp, sz, vp]
+        for fn in (L.spindle_compress_shallow, L.spindle_shallow_graph, L.spindle_shallow_codebook):
+            fn.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 14 + [vp, sz, vp]
         L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.spindle_profile.argtypes = [i32]
         L.spindle_profile_read.argtypes = [C.c_char_p, C.POINTER(C.c_float), i32]
@@ -68,7 +72,7 @@ def lib():
         L.spindle_reserve_ratio.argtypes = [C.c_int64, C.c_int64, C.c_int64, i32, i32, i32, C.POINTER(C.c_double)]
         L.spindle_decode_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_decode_merge.argtypes = [C.POINTER(KvDesc), vp, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-        for name in EXPORTS[:11]:
+        for name in EXPORTS[:N_STATUS]:
             getattr(L, name).restype = C.c_int
         L.spindle_last_error.restype = C.c_char_p
         L.spindle_version.restype = C.c_uint32
@@ -143,15 +147,29 @@ def spindle_compress_deep(desc, K, V, Qw, window, pool_kernel, scale, norm, budg
                                        workspace_bytes, stream if stream is not None else _stream()))
 
 
-def spindle_compress_shallow(desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_codes_k, n_codes_v,
-                             n_found_k, n_found_v, ref_k, ref_v, mag_k, mag_v, adj_k, adj_v, deg_k, deg_v,
-                             workspace, workspace_bytes, stream=None):
-    _check(lib().spindle_compress_shallow(C.byref(desc), _ptr(K), _ptr(V), float(theta_k), float(theta_v),
-                                          max_codes, _ptr(Ck), _ptr(Cv), _ptr(n_codes_k), _ptr(n_codes_v),
-                                          _ptr(n_found_k), _ptr(n_found_v), _ptr(ref_k), _ptr(ref_v),
-                                          _ptr(mag_k), _ptr(mag_v), _ptr(adj_k), _ptr(adj_v), _ptr(deg_k),
-                                          _ptr(deg_v), _ptr(workspace), workspace_bytes,
-                                          stream if stream is not None else _stream()))
+def _shallow_call(fn, desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_codes_k, n_codes_v,
+                  n_found_k, n_found_v, ref_k, ref_v, mag_k, mag_v, adj_k, adj_v, deg_k, deg_v,
+                  workspace, workspace_bytes, stream=None):
+    _check(fn(C.byref(desc), _ptr(K), _ptr(V), float(theta_k), float(theta_v),
+              max_codes, _ptr(Ck), _ptr(Cv), _ptr(n_codes_k), _ptr(n_codes_v),
+              _ptr(n_found_k), _ptr(n_found_v), _ptr(ref_k), _ptr(ref_v),
+              _ptr(mag_k), _ptr(mag_v), _ptr(adj_k), _ptr(adj_v), _ptr(deg_k),
+              _ptr(deg_v), _ptr(workspace), workspace_bytes,
+              stream if stream is not None else _stream()))
+
+
+def spindle_compress_shallow(*args, **kw):
+    _shallow_call(lib().spindle_compress_shallow, *args, **kw)
+
+
+def spindle_shallow_graph(*args, **kw):
+    """First half of spindle_compress_shallow (same arguments): up to the neighbour lists."""
+    _shallow_call(lib().spindle_shallow_graph, *args, **kw)
+
+
+def spindle_shallow_codebook(*args, **kw):
+    """Second half of spindle_compress_shallow (same arguments, same workspace)."""
+    _shallow_call(lib().spindle_shallow_codebook, *args, **kw)
 
 
 def spindle_shallow_stats(desc, n_tensors, workspace, stream=None):
@@ -292,14 +310,23 @@ class ShallowPlan:
     ws: object
     ws_bytes: int
 
+    def _args(self, K, V):
+        g = self.out.get
+        return (self.desc, K, V, self.theta_k, self.theta_v, self.max_codes,
+                g("C_k"), g("C_v"), g("n_codes_k"), g("n_codes_v"), g("n_found_k"), g("n_found_v"),
+                g("ref_k"), g("ref_v"), g("mag_k"), g("mag_v"), g("adj_k"), g("adj_v"),
+                g("deg_k"), g("deg_v"), self.ws, self.ws_bytes)
+
     def run(self, K, V):
-        o = self.out
-        g = lambda k: o.get(k)
-        spindle_compress_shallow(self.desc, K, V, self.theta_k, self.theta_v, self.max_codes,
-                                 g("C_k"), g("C_v"), g("n_codes_k"), g("n_codes_v"), g("n_found_k"), g("n_found_v"),
-                                 g("ref_k"), g("ref_v"), g("mag_k"), g("mag_v"), g("adj_k"), g("adj_v"),
-                                 g("deg_k"), g("deg_v"), self.ws, self.ws_bytes)
-        return o
+        spindle_compress_shallow(*self._args(K, V))
+        return self.out
+
+    def run_graph(self, K, V):
+        spindle_shallow_graph(*self._args(K, V))
+
+    def run_codebook(self, K, V):
+        spindle_shallow_codebook(*self._args(K, V))
+        return self.out
 
     def stats(self):
         n_t = sum(1 for k in self.out if k.startswith("ref_"))
@@ -324,6 +351,35 @@ def plan_shallow(K, dtype, theta_k, theta_v, max_codes, tensors=("k", "v"), debu
             out[f"deg_{t}"] = torch.empty((B, H, l), dtype=torch.int32, device=dev)
     return ShallowPlan(desc, theta_k, theta_v, max_codes, out,
                        torch.empty(nbytes, dtype=torch.uint8, device=dev), nbytes)
+
+
+class OverlappedLayer:
+    """Eviction and codebook calls of one layer on two streams.  The first half of the codebook call
+    (similarity graph) fills the chip; during the second half (the loop of Alg. 1, one workgroup per
+    problem for most of it) most compute units are idle, so the eviction call runs beside it on a
+    side stream that waits for an event recorded between the halves.  Streams and events only:
+    the calls and their arguments are those of the one-stream sequence."""
+
+    def __init__(self, deep: "DeepPlan", shallow: "ShallowPlan"):
+        import torch
+        self.deep, self.shallow = deep, shallow
+        self.side = torch.cuda.Stream()              # default priority
+        self.fork, self.join = torch.cuda.Event(), torch.cuda.Event()
+
+    def run(self, K, V, Qw):
+        import torch
+        main = torch.cuda.current_stream()
+        self.shallow.run_graph(K, V)
+        self.fork.record(main)
+        # the second half is enqueued first: its chain of short dependent kernels is the longer of
+        # the two and should not queue behind an eviction kernel
+        out = self.shallow.run_codebook(K, V)
+        self.side.wait_event(self.fork)
+        with torch.cuda.stream(self.side):
+            kept = self.deep.run(K, V, Qw)
+            self.join.record(self.side)
+        main.wait_event(self.join)                   # later work on the main stream sees both results
+        return kept, out
 
 
 def compress_shallow(K, V, dtype, theta_k, theta_v, max_codes, debug=False):

@@ -130,7 +130,11 @@ extern "C" spindle_status spindle_shallow_stats(const spindle_kv_desc *desc, int
   return SPINDLE_OK;
 }
 
-extern "C" spindle_status spindle_compress_shallow(
+namespace {
+enum { kPhaseGraph = 1, kPhaseCodebook = 2 };
+
+// The whole call or one of its halves; the arguments are those of spindle_compress_shallow.
+spindle_status run_shallow(int phases,
     const spindle_kv_desc *desc, const void *K, const void *V, float theta_k, float theta_v,
     int32_t max_codes, void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v, int32_t *n_found_k,
     int32_t *n_found_v, int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v, uint32_t *adj_k,
@@ -172,21 +176,55 @@ extern "C" spindle_status spindle_compress_shallow(
     p.n_codes[t] = n_codes_v; p.n_found[t] = n_found_v; p.ref[t] = ref_v; p.mag[t] = mag_v;
     adj[t] = adj_v; p.deg_out[t] = deg_v; ++t;
   }
-  // zero: counters, list counts, error flag, barriers; codebooks
-  const size_t nzero = zero_words(p.UT, n);
-  const size_t cwords = (size_t)U * max_codes * kHeadDim * dtype_bytes(p.dtype) / 4;
-  hipLaunchKernelGGL(shallow_init, dim3(1024), dim3(256), 0, st, p, nzero, cwords, T);
-
-  if ((s = launch_graph(p, st, adj[0] || adj[1])) != SPINDLE_OK) return s;
-  if ((s = launch_merge(p, st)) != SPINDLE_OK) return s;
-  if ((s = launch_codebook(p, st)) != SPINDLE_OK) return s;
-
-  const int W = (n + 31) / 32;
-  for (int i = 0; i < T; ++i) {
-    if (adj[i])
-      hipLaunchKernelGGL(export_adj, dim3(1024), dim3(256), 0, st, p.G + (size_t)i * U * n * p.Wp, adj[i],
-                         (size_t)U * n, p.Wp, W);
+  if (phases & kPhaseGraph) {
+    // zero: counters, list counts, error flag, barriers; codebooks
+    const size_t nzero = zero_words(p.UT, n);
+    const size_t cwords = (size_t)U * max_codes * kHeadDim * dtype_bytes(p.dtype) / 4;
+    hipLaunchKernelGGL(shallow_init, dim3(1024), dim3(256), 0, st, p, nzero, cwords, T);
+    if ((s = launch_graph(p, st, adj[0] || adj[1])) != SPINDLE_OK) return s;
+    const int W = (n + 31) / 32;                      // nothing after this point changes G
+    for (int i = 0; i < T; ++i) {
+      if (adj[i])
+        hipLaunchKernelGGL(export_adj, dim3(1024), dim3(256), 0, st, p.G + (size_t)i * U * n * p.Wp, adj[i],
+                           (size_t)U * n, p.Wp, W);
+    }
+  }
+  if (phases & kPhaseCodebook) {
+    if ((s = launch_merge(p, st)) != SPINDLE_OK) return s;
+    if ((s = launch_codebook(p, st)) != SPINDLE_OK) return s;
   }
   SPINDLE_HIP(hipGetLastError());
   return SPINDLE_OK;
+}
+}  // namespace
+
+#define SHALLOW_ARGS                                                                                    \
+  desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_codes_k, n_codes_v, n_found_k, n_found_v, ref_k,   \
+  ref_v, mag_k, mag_v, adj_k, adj_v, deg_k, deg_v, workspace, workspace_bytes, stream
+
+extern "C" spindle_status spindle_compress_shallow(
+    const spindle_kv_desc *desc, const void *K, const void *V, float theta_k, float theta_v,
+    int32_t max_codes, void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v, int32_t *n_found_k,
+    int32_t *n_found_v, int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v, uint32_t *adj_k,
+    uint32_t *adj_v, int32_t *deg_k, int32_t *deg_v, void *workspace, size_t workspace_bytes,
+    void *stream) {
+  return run_shallow(kPhaseGraph | kPhaseCodebook, SHALLOW_ARGS);
+}
+
+extern "C" spindle_status spindle_shallow_graph(
+    const spindle_kv_desc *desc, const void *K, const void *V, float theta_k, float theta_v,
+    int32_t max_codes, void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v, int32_t *n_found_k,
+    int32_t *n_found_v, int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v, uint32_t *adj_k,
+    uint32_t *adj_v, int32_t *deg_k, int32_t *deg_v, void *workspace, size_t workspace_bytes,
+    void *stream) {
+  return run_shallow(kPhaseGraph, SHALLOW_ARGS);
+}
+
+extern "C" spindle_status spindle_shallow_codebook(
+    const spindle_kv_desc *desc, const void *K, const void *V, float theta_k, float theta_v,
+    int32_t max_codes, void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v, int32_t *n_found_k,
+    int32_t *n_found_v, int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v, uint32_t *adj_k,
+    uint32_t *adj_v, int32_t *deg_k, int32_t *deg_v, void *workspace, size_t workspace_bytes,
+    void *stream) {
+  return run_shallow(kPhaseCodebook, SHALLOW_ARGS);
 }

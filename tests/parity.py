@@ -155,3 +155,25 @@ def check_shallow_layer(orc, L: wl.Layer, cap=None, units=None, tensors=("k", "v
 
     with ThreadPoolExecutor(max_workers=16) as ex:
         return list(ex.map(run, jobs)), g
+
+
+# ------------------------------------------------------------------ both paths on two streams
+
+def gpu_layer_two_streams(L: wl.Layer, cap=None, reps=2):
+    """One layer the way bench.py launches it: the eviction call on a side stream beside the second
+    half of the codebook call.  Run `reps` times into the same buffers (later runs start while nothing
+    of the earlier one is pending).  Returns (gpu_deep-style tuple, gpu_shallow-style dict)."""
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    K, V, Q = (sb.to_device(x, L.dtype) for x in (L.K, L.V, L.Qw))
+    deep = sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, scale=scale_of(L.head_dim))
+    sh = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, cap or L.max_codes)
+    layer = sb.OverlappedLayer(deep, sh)
+    for _ in range(reps):
+        (kept, Ko, Vo, sc), out = layer.run(K, V, Q)
+    torch.cuda.synchronize()
+    res = {}
+    for k, v in out.items():
+        res[k] = sb.to_host_bits(v, L.dtype) if k.startswith("C_") else v.cpu().numpy()
+    return (kept.cpu().numpy(), sb.to_host_bits(Ko, L.dtype), sb.to_host_bits(Vo, L.dtype),
+            sc.cpu().numpy().astype(np.float64)), res

@@ -108,6 +108,12 @@ def test_compress_calls_reject_bad_arguments_before_any_launch(sb):
 
     assert shallow(K=null) == 1
     assert shallow(cap=0) == 1
+    # the two halves of the call validate the same way
+    for half in (L.spindle_shallow_graph, L.spindle_shallow_codebook):
+        assert half(C.byref(d), null, null, 0.98, 0.95, 64, fake, null, fake, null, null, null, fake, null, fake,
+                    null, null, null, null, null, fake, 1 << 40, null) == 1
+        assert half(C.byref(d), fake, null, 0.98, 0.95, 64, fake, null, fake, null, null, null, fake, null, fake,
+                    null, null, null, null, null, fake, 1024, null) == 3
     assert shallow(ref=null) == 1
     assert shallow(tk=float("nan")) == 1
     assert shallow(wsb=1024) == 3

@@ -52,6 +52,16 @@ def test_config4_shallow(oracle):
     print("config4 codes", [o["n_codes_uncapped"] for o in res], flush=True)
 
 
+def test_config4_two_streams(oracle):
+    # the launch configuration bench.py times: the eviction call on a side stream beside the second
+    # half of the codebook call, run twice into the same buffers
+    L = wl.config4(0)
+    got, g = parity.gpu_layer_two_streams(L)
+    rep = parity.check_deep_layer(oracle, L, got=got)
+    res, _ = parity.check_shallow_layer(oracle, L, g=g)
+    print("config4 on two streams", rep, [o["n_codes_uncapped"] for o in res][:4], flush=True)
+
+
 def test_config4_adjacency_rows(oracle):
     # sampled rows of G and their degrees at l = 32768, every unit of K
     L = wl.config4(0)

@@ -136,6 +136,16 @@ def test_cosine_exactly_at_the_threshold(oracle, dtype):
     assert adj(40, 41) == 1 and adj(42, 43) == 1 and adj(40, 45) == 1
 
 
+@pytest.mark.parametrize("dtype,l,cap", [("f16", 1500, 80), ("bf16", 2100, 2100), ("f32", 700, 30)])
+def test_two_halves_with_the_eviction_call_beside_the_second(oracle, dtype, l, cap):
+    # spindle_shallow_graph, an event, spindle_shallow_codebook, and spindle_compress_deep on a side
+    # stream that waits for the event (what bench.py times): both results against the oracle
+    L = wl.small_random(31, dtype, B=1, H=3, l=l, lw=16, budget=l // 5, cap=cap, n_centroids=60, noise_frac=0.2)
+    got, g = parity.gpu_layer_two_streams(L)
+    parity.check_deep_layer(oracle, L, got=got)
+    parity.check_shallow_layer(oracle, L, g=g)
+
+
 def test_cut_tokens_with_many_equidistant_entries(oracle):
     # zero vectors have cosine 0 with every entry: when their own entry is cut, every stored entry
     # ties, the candidate lists of the matrix-core search run full and the exhaustive search must
