@@ -131,8 +131,10 @@ def time_decode(torch, sb, L, K, shallow, m=256, novel=0.25, reps=10):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    # the part needs about 0.1 s of load before its clocks settle: a step measured in the first
+    # few iterations is 1.5-4 % slower than the steady state
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--seq-len", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--one-stream", action="store_true",
