@@ -137,6 +137,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--seq-len", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="one step at a time (two streams within the step); default: consecutive steps are "
+                         "pipelined over two sets of buffers, the similarity phase of a step beside the codebook "
+                         "phase and the eviction call of the step before")
     ap.add_argument("--one-stream", action="store_true",
                     help="time the eviction call and the codebook call one after the other on one stream "
                          "(default: the eviction call runs on a side stream beside the second half of the codebook call)")
@@ -162,18 +166,30 @@ def main():
     deep = sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, want_scores=False)
     shallow = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)
     stream = torch.cuda.current_stream()
+    mode = "one-stream" if args.one_stream else ("two-streams" if args.no_pipeline else "pipelined")
     layer = sb.OverlappedLayer(deep, shallow)
+    first = [(deep, shallow)]
+    pipe = sb.PipelinedLayers(lambda: first.pop() if first else (
+        sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, want_scores=False),
+        sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes))) if mode == "pipelined" else None
 
     def step():
-        if args.one_stream:
+        if mode == "one-stream":
             deep.run(K, V, Q)
             shallow.run(K, V)
-        else:
+        elif mode == "two-streams":
             layer.run(K, V, Q)                       # eviction on a side stream beside the codebook loop
+        else:
+            pipe.run(K, V, Q)                        # ... and the next step's similarity phase beside both
+
+    def drain():
+        if pipe is not None:
+            pipe.finish()
+        torch.cuda.synchronize()
 
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
+    drain()
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -188,12 +204,23 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         step()
-    torch.cuda.synchronize()
+    drain()
     wall = time.perf_counter() - t0
     gram_recs = [ms for name, ms in sb.spindle_profile_read() if name == "shallow_gram"]
     assert len(gram_recs) == args.steps
     gram_ms = float(np.mean(gram_recs))
     ms_step = wall * 1e3 / args.steps
+
+    # for reference (not the reported throughput): the same steps one at a time, two streams within a step
+    ms_step_unpipelined = None
+    if mode == "pipelined":
+        sb.spindle_profile(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            layer.run(K, V, Q)
+        torch.cuda.synchronize()
+        ms_step_unpipelined = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # breakdown pass (not the reported throughput): the same steps with events around every kernel
     sb.spindle_profile(1)
@@ -250,12 +277,17 @@ def main():
                    (f"configs[4], one layer: batch 4, 8 KV heads x 4 Q heads, head_dim 128, seq_len {L.seq_len}, "
                     f"bf16, half clustered / half noise; deep: window 64, pool 15, budget {L.budget}; "
                     f"shallow: K and V, theta 0.98/0.95, cap {L.max_codes}")},
-        "streams": ("one" if args.one_stream else
-                    "two: the eviction call runs on a side stream beside the second half of the codebook call "
-                    "(spindle_shallow_graph, event, spindle_shallow_codebook)"),
+        "streams": {"one-stream": "one: the eviction call, then the codebook call",
+                    "two-streams": "two: the eviction call runs on a side stream beside the second half of the "
+                                   "codebook call (spindle_shallow_graph, event, spindle_shallow_codebook)",
+                    "pipelined": "consecutive steps pipelined over two sets of buffers: the similarity phase of a "
+                                 "step (spindle_shallow_graph) runs beside the codebook phase "
+                                 "(spindle_shallow_codebook) and the eviction call of the step before; two "
+                                 "similarity phases never overlap"}[mode],
         "breakdown_pass": "deep_ms, shallow_ms and kernel_ms come from a second pass with the two calls one after the "
                           "other on one stream and HIP events around every kernel, which lengthens the step; "
                           "roofline uses the timed steps' own events",
+        "ms_per_step_one_at_a_time": ms_step_unpipelined,
         "ms_per_step_with_all_events": ms_step_all_events,
         "deep_ms": ms_deep, "shallow_ms": ms_shallow,
         "deep_tokens_per_s": tokens / (ms_deep * 1e-3), "shallow_tokens_per_s": tokens / (ms_shallow * 1e-3),

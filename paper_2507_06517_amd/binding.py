@@ -382,6 +382,55 @@ class OverlappedLayer:
         return kept, out
 
 
+class PipelinedLayers:
+    """Consecutive layers (independent calls) in a software pipeline over `depth` sets of buffers, each
+    with a main and a side stream.  Layer k+1's similarity phase starts when layer k's has ended, so it
+    runs beside layer k's codebook phase and eviction call, which leave most of the chip idle; two
+    similarity phases never share the chip.  Streams and events only: every layer is the same sequence
+    of calls as in OverlappedLayer, and a set's buffers are reused only after all of its work is done."""
+
+    def __init__(self, make_plans, depth=2):
+        import torch
+        self.sets = []
+        for _ in range(depth):
+            deep, shallow = make_plans()
+            self.sets.append(dict(deep=deep, shallow=shallow, main=torch.cuda.Stream(), side=torch.cuda.Stream(),
+                                  graph=torch.cuda.Event(), join=torch.cuda.Event(), done=torch.cuda.Event()))
+        self.k = 0
+        self.prev_graph = None
+        self.ready = torch.cuda.Event()
+
+    def run(self, K, V, Qw):
+        """Enqueue one layer; returns its set (outputs in set['deep'] / set['shallow'].out, valid after finish())."""
+        import torch
+        s = self.sets[self.k % len(self.sets)]
+        self.k += 1
+        main, side = s["main"], s["side"]
+        self.ready.record(torch.cuda.current_stream())       # the inputs are ready on the caller's stream
+        main.wait_event(self.ready)
+        if self.prev_graph is not None:
+            main.wait_event(self.prev_graph)                 # one similarity phase at a time
+        with torch.cuda.stream(main):
+            s["shallow"].run_graph(K, V)
+            s["graph"].record(main)
+            s["shallow"].run_codebook(K, V)
+        side.wait_event(s["graph"])
+        with torch.cuda.stream(side):
+            s["deep"].run(K, V, Qw)
+            s["join"].record(side)
+        main.wait_event(s["join"])                           # the set is free again once main gets here
+        s["done"].record(main)
+        self.prev_graph = s["graph"]
+        return s
+
+    def finish(self):
+        """The caller's stream waits for every layer enqueued so far."""
+        import torch
+        cur = torch.cuda.current_stream()
+        for s in self.sets:
+            cur.wait_event(s["done"])
+
+
 def compress_shallow(K, V, dtype, theta_k, theta_v, max_codes, debug=False):
     ref = K if K is not None else V
     tensors = tuple(t for t, x in (("k", K), ("v", V)) if x is not None)

@@ -177,3 +177,28 @@ def gpu_layer_two_streams(L: wl.Layer, cap=None, reps=2):
         res[k] = sb.to_host_bits(v, L.dtype) if k.startswith("C_") else v.cpu().numpy()
     return (kept.cpu().numpy(), sb.to_host_bits(Ko, L.dtype), sb.to_host_bits(Vo, L.dtype),
             sc.cpu().numpy().astype(np.float64)), res
+
+
+def gpu_layers_pipelined(L: wl.Layer, steps=5, cap=None):
+    """`steps` runs of one layer the way bench.py launches consecutive steps: pipelined over two sets of
+    buffers.  Returns, per set, (gpu_deep-style tuple, gpu_shallow-style dict) of the last run into it."""
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    K, V, Q = (sb.to_device(x, L.dtype) for x in (L.K, L.V, L.Qw))
+
+    def make():
+        return (sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, scale=scale_of(L.head_dim)),
+                sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, cap or L.max_codes))
+
+    pipe = sb.PipelinedLayers(make)
+    for _ in range(steps):
+        pipe.run(K, V, Q)
+    pipe.finish()
+    torch.cuda.synchronize()
+    res = []
+    for s in pipe.sets:
+        d, sh = s["deep"], s["shallow"]
+        g = {k: (sb.to_host_bits(v, L.dtype) if k.startswith("C_") else v.cpu().numpy()) for k, v in sh.out.items()}
+        res.append(((d.kept.cpu().numpy(), sb.to_host_bits(d.K_out, L.dtype), sb.to_host_bits(d.V_out, L.dtype),
+                     d.scores.cpu().numpy().astype(np.float64)), g))
+    return res

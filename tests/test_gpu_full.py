@@ -53,13 +53,27 @@ def test_config4_shallow(oracle):
 
 
 def test_config4_two_streams(oracle):
-    # the launch configuration bench.py times: the eviction call on a side stream beside the second
-    # half of the codebook call, run twice into the same buffers
+    # the eviction call on a side stream beside the second half of the codebook call (bench.py
+    # --no-pipeline), run twice into the same buffers
     L = wl.config4(0)
     got, g = parity.gpu_layer_two_streams(L)
     rep = parity.check_deep_layer(oracle, L, got=got)
     res, _ = parity.check_shallow_layer(oracle, L, g=g)
     print("config4 on two streams", rep, [o["n_codes_uncapped"] for o in res][:4], flush=True)
+
+
+def test_config4_pipelined(oracle):
+    # the launch configuration bench.py times: consecutive steps pipelined over two sets of buffers.
+    # Seven steps; the first set against the oracle in full, the second identical to the first
+    L = wl.config4(0)
+    (got0, g0), (got1, g1) = parity.gpu_layers_pipelined(L, steps=7)
+    rep = parity.check_deep_layer(oracle, L, got=got0)
+    res, _ = parity.check_shallow_layer(oracle, L, g=g0)
+    for a, b in zip(got0, got1):
+        assert np.array_equal(a, b)
+    for k in g0:
+        assert np.array_equal(g0[k], g1[k]), k
+    print("config4 pipelined", rep, [o["n_codes_uncapped"] for o in res][:4], flush=True)
 
 
 def test_config4_adjacency_rows(oracle):

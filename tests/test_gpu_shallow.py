@@ -146,6 +146,16 @@ def test_two_halves_with_the_eviction_call_beside_the_second(oracle, dtype, l, c
     parity.check_shallow_layer(oracle, L, g=g)
 
 
+@pytest.mark.parametrize("dtype,l,cap", [("f16", 1500, 80), ("bf16", 2100, 2100)])
+def test_consecutive_layers_pipelined(oracle, dtype, l, cap):
+    # five runs over two sets of buffers, the similarity phase of a run beside the codebook phase and the
+    # eviction call of the run before: what both sets hold at the end against the oracle
+    L = wl.small_random(32, dtype, B=1, H=3, l=l, lw=16, budget=l // 5, cap=cap, n_centroids=60, noise_frac=0.2)
+    for got, g in parity.gpu_layers_pipelined(L):
+        parity.check_deep_layer(oracle, L, got=got)
+        parity.check_shallow_layer(oracle, L, g=g)
+
+
 def test_cut_tokens_with_many_equidistant_entries(oracle):
     # zero vectors have cosine 0 with every entry: when their own entry is cut, every stored entry
     # ties, the candidate lists of the matrix-core search run full and the exhaustive search must
