@@ -26,6 +26,10 @@ PEAK_HBM_GBS = 8000.0
 PEAK_VALU_F64_TFLOPS = 78.6         # 256 CUs x 64 lanes x 2 flop x 2.4 GHz
 
 
+# sets of buffers the pipelined steps rotate over (2.60 ms per step with two, 2.56 with three, 2.60 with four)
+PIPELINE_SETS = 3
+
+
 def cpu_baseline(L, wl, sample_n=24576):
     """The oracle as it stands, timed on this host: the eviction path on one full unit and
     the codebook path on the first `sample_n` tokens of one K unit; scaled to a whole layer
@@ -139,7 +143,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="one step at a time (two streams within the step); default: consecutive steps are "
-                         "pipelined over two sets of buffers, the similarity phase of a step beside the codebook "
+                         "pipelined over three sets of buffers, the similarity phase of a step beside the codebook "
                          "phase and the eviction call of the step before")
     ap.add_argument("--one-stream", action="store_true",
                     help="time the eviction call and the codebook call one after the other on one stream "
@@ -171,7 +175,7 @@ def main():
     first = [(deep, shallow)]
     pipe = sb.PipelinedLayers(lambda: first.pop() if first else (
         sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, want_scores=False),
-        sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes))) if mode == "pipelined" else None
+        sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)), depth=PIPELINE_SETS) if mode == "pipelined" else None
 
     def step():
         if mode == "one-stream":
@@ -280,7 +284,7 @@ def main():
         "streams": {"one-stream": "one: the eviction call, then the codebook call",
                     "two-streams": "two: the eviction call runs on a side stream beside the second half of the "
                                    "codebook call (spindle_shallow_graph, event, spindle_shallow_codebook)",
-                    "pipelined": "consecutive steps pipelined over two sets of buffers: the similarity phase of a "
+                    "pipelined": "consecutive steps pipelined over three sets of buffers: the similarity phase of a "
                                  "step (spindle_shallow_graph) runs beside the codebook phase "
                                  "(spindle_shallow_codebook) and the eviction call of the step before; two "
                                  "similarity phases never overlap"}[mode],

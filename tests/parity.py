@@ -179,8 +179,8 @@ def gpu_layer_two_streams(L: wl.Layer, cap=None, reps=2):
             sc.cpu().numpy().astype(np.float64)), res
 
 
-def gpu_layers_pipelined(L: wl.Layer, steps=5, cap=None):
-    """`steps` runs of one layer the way bench.py launches consecutive steps: pipelined over two sets of
+def gpu_layers_pipelined(L: wl.Layer, steps=5, cap=None, depth=2):
+    """`steps` runs of one layer the way bench.py launches consecutive steps: pipelined over `depth` sets of
     buffers.  Returns, per set, (gpu_deep-style tuple, gpu_shallow-style dict) of the last run into it."""
     import torch
     from paper_2507_06517_amd import binding as sb
@@ -190,7 +190,7 @@ def gpu_layers_pipelined(L: wl.Layer, steps=5, cap=None):
         return (sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, scale=scale_of(L.head_dim)),
                 sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, cap or L.max_codes))
 
-    pipe = sb.PipelinedLayers(make)
+    pipe = sb.PipelinedLayers(make, depth=depth)
     for _ in range(steps):
         pipe.run(K, V, Q)
     pipe.finish()

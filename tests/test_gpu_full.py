@@ -63,16 +63,18 @@ def test_config4_two_streams(oracle):
 
 
 def test_config4_pipelined(oracle):
-    # the launch configuration bench.py times: consecutive steps pipelined over two sets of buffers.
-    # Seven steps; the first set against the oracle in full, the second identical to the first
+    # the launch configuration bench.py times: consecutive steps pipelined over three sets of buffers.
+    # Ten steps; the first set against the oracle in full, the others identical to the first
     L = wl.config4(0)
-    (got0, g0), (got1, g1) = parity.gpu_layers_pipelined(L, steps=7)
+    (got0, g0), *others = parity.gpu_layers_pipelined(L, steps=10, depth=3)
     rep = parity.check_deep_layer(oracle, L, got=got0)
     res, _ = parity.check_shallow_layer(oracle, L, g=g0)
-    for a, b in zip(got0, got1):
-        assert np.array_equal(a, b)
-    for k in g0:
-        assert np.array_equal(g0[k], g1[k]), k
+    assert len(others) == 2
+    for got1, g1 in others:
+        for a, b in zip(got0, got1):
+            assert np.array_equal(a, b)
+        for k in g0:
+            assert np.array_equal(g0[k], g1[k]), k
     print("config4 pipelined", rep, [o["n_codes_uncapped"] for o in res][:4], flush=True)
 
 
