@@ -5,6 +5,8 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <atomic>
+
 #include "spindle.h"
 
 namespace spindle {
@@ -50,6 +52,15 @@ struct ProfScope {
   ProfScope(const char *name, hipStream_t s);
   ~ProfScope();
 };
+
+// A kernel may only be launched with more dynamic LDS than the default limit after that limit
+// was raised for it, per device.  allow_lds raises it to `bytes`, the largest size the kernel is
+// ever launched with, on the first call per device (one LdsLimit object per kernel), so that
+// no call depends on what another thread asked for and later calls cost nothing.
+struct LdsLimit {
+  std::atomic<uint64_t> devices{0};   // bit d: done on device d
+};
+spindle_status allow_lds(LdsLimit &state, const void *kernel, size_t bytes);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -546,10 +546,9 @@ spindle_status launch_passes(const DeepParams &p, int U, hipStream_t st) {
   typedef Stage<DT> S;
   const size_t smem_stats = 2 * (size_t)S::kBytes > 65536 ? 2 * (size_t)S::kBytes : 65536;
   const size_t smem_acc = 2 * (size_t)S::kBytes + 2 * 2 * WR * kStageKeys * sizeof(float);
-  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&deep_pass<DT, WR, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_stats));
-  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&deep_pass<DT, WR, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_acc));
+  static LdsLimit lim_stats, lim_acc;                     // one pair per instantiation; the sizes are constants of it
+  if (spindle_status e = allow_lds(lim_stats, reinterpret_cast<const void *>(&deep_pass<DT, WR, false>), smem_stats)) return e;
+  if (spindle_status e = allow_lds(lim_acc, reinterpret_cast<const void *>(&deep_pass<DT, WR, true>), smem_acc)) return e;
   { ProfScope ps("deep_stats", st);
   hipLaunchKernelGGL((deep_pass<DT, WR, false>), dim3(p.nchunks, U), dim3(kDeepThreads), smem_stats, st, p); }
   if (p.lc > 0) {
@@ -644,8 +643,8 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   {
     const int vals_in_lds = lc <= kSelInLds;
     const size_t sel_lds = vals_in_lds ? (size_t)lc * sizeof(uint32_t) : 0;
-    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&deep_select),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_lds));
+    static LdsLimit lim_select;
+    if (spindle_status e = allow_lds(lim_select, reinterpret_cast<const void *>(&deep_select), kSelInLds * sizeof(uint32_t))) return e;
     ProfScope ps("deep_select", st);
     hipLaunchKernelGGL(deep_select, dim3(U), dim3(kSelThreads), sel_lds, st, sp, vals_in_lds);
   }

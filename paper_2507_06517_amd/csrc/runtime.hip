@@ -46,6 +46,16 @@ spindle_status kv_layout(const spindle_kv_desc *d, KvLayout *out) {
   return SPINDLE_OK;
 }
 
+spindle_status allow_lds(LdsLimit &state, const void *kernel, size_t bytes) {
+  int dev = 0;
+  SPINDLE_HIP(hipGetDevice(&dev));
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev < 64 && (state.devices.load(std::memory_order_acquire) & bit)) return SPINDLE_OK;
+  SPINDLE_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  if (dev < 64) state.devices.fetch_or(bit, std::memory_order_release);
+  return SPINDLE_OK;
+}
+
 struct ProfRec {
   char name[32];
   hipEvent_t a, b;

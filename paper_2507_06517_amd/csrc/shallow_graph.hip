@@ -854,8 +854,8 @@ spindle_status launch_graph(const ShallowParams &p, hipStream_t st, int force) {
   else hipLaunchKernelGGL(shallow_edge_lists<0>, eg, dim3(kEdgeThreads), 0, st, p, force); }
   const int T1k = (n + 1023) / 1024, npairs = T1k * (T1k - 1) / 2;
   if (npairs > 0) {
-    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_mirror),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMirrorLds));
+    static LdsLimit lim_mirror;
+    if (spindle_status e = allow_lds(lim_mirror, reinterpret_cast<const void *>(&shallow_mirror), kMirrorLds)) return e;
     ProfScope ps("shallow_mirror", st);
     const int items = 16 * ((p.UT * npairs + 7) / 8);
     hipLaunchKernelGGL(shallow_mirror, dim3(items < 512 ? items : 512), dim3(kMirrorThreads), kMirrorLds, st, p, force, items);

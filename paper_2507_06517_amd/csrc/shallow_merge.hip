@@ -749,11 +749,12 @@ spindle_status launch_merge(const ShallowParams &p, hipStream_t st) {
   const size_t key_lds = keys_in_lds ? (size_t)((n + 3) & ~3) * sizeof(uint32_t) : 0;
   int ox = (n + 4 * (kMergeThreads / kSegW) - 1) / (4 * (kMergeThreads / kSegW));
   if (ox > 16) ox = 16;
-  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_onehop),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)key_lds));
+  static LdsLimit lim_onehop, lim_update, lim_merge;      // raised once per device to the largest size in use
+  if (spindle_status e = allow_lds(lim_onehop, reinterpret_cast<const void *>(&merge_onehop), kKeysInLds * sizeof(uint32_t))) return e;
   const size_t dead_lds = (size_t)p.n16;
-  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_update),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)dead_lds));
+  if (spindle_status e = allow_lds(lim_update, reinterpret_cast<const void *>(&merge_update), 65536)) return e;
+  if (spindle_status e = allow_lds(lim_merge, reinterpret_cast<const void *>(&shallow_merge),
+                                   (kKeysInLds + kKeysInLds / 32) * sizeof(uint32_t))) return e;
   for (int round = 0; round < kGridRounds; ++round) {
     ProfScope ps("shallow_merge_grid", st);
     hipLaunchKernelGGL(merge_onehop, dim3(ox, p.UT), dim3(kMergeThreads), key_lds, st, p, round, keys_in_lds);
@@ -761,8 +762,6 @@ spindle_status launch_merge(const ShallowParams &p, hipStream_t st) {
     hipLaunchKernelGGL(merge_update, dim3(ox, p.UT), dim3(kMergeThreads), dead_lds, st, p, round);   // 1024 threads: fewer copies of the flags
   }
   const size_t merge_lds = n <= kKeysInLds ? ((size_t)((n + 3) & ~3) + (n + 31) / 32) * sizeof(uint32_t) : 0;
-  SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&shallow_merge),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds));
   { ProfScope ps("shallow_merge", st);
   hipLaunchKernelGGL(shallow_merge, dim3(p.UT), dim3(kMergeThreads), merge_lds, st, p); }
   SPINDLE_HIP(hipGetLastError());
