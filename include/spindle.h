@@ -264,6 +264,31 @@ spindle_status spindle_decode_merge(const spindle_kv_desc *desc, const void *X_n
                                     int32_t *n_matched, int32_t *ref, float *mag, void *workspace,
                                     size_t workspace_bytes, void *stream);
 
+/*
+ * spindle_decode_merge for callers that cannot allocate device memory or carry a workspace
+ * around: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments, results and errors as spindle_decode_merge, without `workspace`:
+ * the scratch memory (the new tokens as doubles, their magnitudes, one partial result per 512
+ * stored entries) is an array of spindle_decode_static_capacity() bytes (6 MiB) inside the
+ * library's code object, which every GPU the library runs on holds until the process ends.
+ * The call allocates and frees nothing on host or device and only enqueues on `stream`, which
+ * must belong to the current device.  (With per-kernel timing switched on, spindle_profile
+ * creates HIP events; leave it off for such callers.)
+ *   - A call whose spindle_decode_workspace_bytes exceeds the capacity is refused with
+ *     SPINDLE_ERR_UNSUPPORTED and a message that names both sizes; nothing is enqueued.
+ *     Roughly: batch * n_kv_heads * (new tokens rounded up to 16) <= 5000 at max_codes <= 8192,
+ *     e.g. 32 problems x 128 tokens.
+ *   - All calls on one GPU share the array: calls that may overlap on one GPU (two streams, two
+ *     threads) race; order them on one stream or with events.  Nothing in it needs clearing:
+ *     every element a kernel reads was written earlier in the same call.
+ */
+spindle_status spindle_decode_merge_static(const spindle_kv_desc *desc, const void *X_new, float theta,
+                                           int32_t max_codes, void *C, int32_t *n_codes, int32_t *n_found,
+                                           int32_t *n_matched, int32_t *ref, float *mag, void *stream);
+
+/* Bytes of the built-in scratch array of spindle_decode_merge_static. */
+size_t spindle_decode_static_capacity(void);
+
 /* ------------------------------------------------------------------------- */
 /* Host helpers (plain arithmetic on the host, no GPU work)                    */
 /* ------------------------------------------------------------------------- */

@@ -28,9 +28,10 @@ EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_sha
            "spindle_compress_shallow", "spindle_shallow_graph", "spindle_shallow_codebook",
            "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
            "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_decode_workspace_bytes", "spindle_decode_merge",
-           "spindle_profile_read",
+           "spindle_decode_merge_static",
+           "spindle_profile_read", "spindle_decode_static_capacity",
            "spindle_last_error", "spindle_version"]
-N_STATUS = 13
+N_STATUS = 14
 
 
 class KvDesc(C.Structure):
@@ -72,6 +73,9 @@ def lib():
         L.spindle_reserve_ratio.argtypes = [C.c_int64, C.c_int64, C.c_int64, i32, i32, i32, C.POINTER(C.c_double)]
         L.spindle_decode_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_decode_merge.argtypes = [C.POINTER(KvDesc), vp, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.spindle_decode_merge_static.argtypes = [C.POINTER(KvDesc), vp, f32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.spindle_decode_static_capacity.argtypes = []
+        L.spindle_decode_static_capacity.restype = sz
         for name in EXPORTS[:N_STATUS]:
             getattr(L, name).restype = C.c_int
         L.spindle_last_error.restype = C.c_char_p
@@ -214,6 +218,16 @@ def spindle_decode_merge(desc, X_new, theta, max_codes, Cb, n_codes, n_found, n_
     _check(lib().spindle_decode_merge(C.byref(desc), _ptr(X_new), float(theta), int(max_codes), _ptr(Cb),
                                       _ptr(n_codes), _ptr(n_found), _ptr(n_matched), _ptr(ref), _ptr(mag),
                                       _ptr(workspace), int(workspace_bytes), stream or _stream()))
+
+
+def spindle_decode_merge_static(desc, X_new, theta, max_codes, Cb, n_codes, n_found, n_matched, ref, mag, stream=None):
+    _check(lib().spindle_decode_merge_static(C.byref(desc), _ptr(X_new), float(theta), int(max_codes), _ptr(Cb),
+                                             _ptr(n_codes), _ptr(n_found), _ptr(n_matched), _ptr(ref), _ptr(mag),
+                                             stream or _stream()))
+
+
+def spindle_decode_static_capacity() -> int:
+    return int(lib().spindle_decode_static_capacity())
 
 
 def decode_merge(X_new, dtype, theta, Cb, n_codes):

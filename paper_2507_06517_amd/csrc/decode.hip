@@ -14,7 +14,15 @@
 //   decode_small   all of it in one launch when a call brings at most four tokens per problem
 #include <math.h>
 
+#include <mutex>
+
 #include "common.h"
+
+// Scratch memory of spindle_decode_merge_static: lives in the code object, one copy per GPU
+// the library is loaded on, for the life of the process.  In host code this name is only a
+// handle for hipGetSymbolAddress; the address kernels get is looked up per device below.
+constexpr size_t kStaticScratchBytes = (size_t)6 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace spindle {
 namespace {
@@ -598,21 +606,29 @@ extern "C" spindle_status spindle_decode_workspace_bytes(const spindle_kv_desc *
   return SPINDLE_OK;
 }
 
-extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, const void *X_new, float theta,
-                                               int32_t max_codes, void *C, int32_t *n_codes, int32_t *n_found,
-                                               int32_t *n_matched, int32_t *ref, float *mag, void *workspace,
-                                               size_t workspace_bytes, void *stream) {
+namespace {
+
+// Validation both entry points share; *need = bytes of scratch memory the call uses.
+spindle_status decode_check_args(const spindle_kv_desc *desc, const void *X_new, float theta, int32_t max_codes,
+                                 const void *C, const int32_t *n_codes, const int32_t *n_found, const int32_t *ref,
+                                 const float *mag, size_t *need) {
   spindle_status s = check_decode(desc);
   if (s != SPINDLE_OK) return s;
   if (max_codes < 1) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "max_codes must be >= 1");
   if (!(theta > -1.f && theta < 1.f)) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "theta must lie in (-1, 1)");
-  if (!X_new || !C || !n_codes || !n_found || !ref || !mag || !workspace)
-    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "X_new, C, n_codes, n_found, ref, mag and workspace are required");
-  if ((reinterpret_cast<uintptr_t>(X_new) | reinterpret_cast<uintptr_t>(C) | reinterpret_cast<uintptr_t>(workspace)) & 15)
+  if (!X_new || !C || !n_codes || !n_found || !ref || !mag)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "X_new, C, n_codes, n_found, ref and mag are required");
+  if ((reinterpret_cast<uintptr_t>(X_new) | reinterpret_cast<uintptr_t>(C)) & 15)
     SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-  const size_t need = decode_carve(desc, max_codes, nullptr, nullptr);
-  if (workspace_bytes < need) SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, need);
-  hipStream_t st = static_cast<hipStream_t>(stream);
+  *need = decode_carve(desc, max_codes, nullptr, nullptr);
+  return SPINDLE_OK;
+}
+
+// Enqueues the kernels of one merge; `scratch_mem` holds decode_carve's arrays and needs no
+// initial content: every element a kernel reads was written by an earlier kernel of the same call.
+spindle_status decode_enqueue(const spindle_kv_desc *desc, const void *X_new, float theta, int32_t max_codes,
+                              void *C, int32_t *n_codes, int32_t *n_found, int32_t *n_matched, int32_t *ref,
+                              float *mag, void *scratch_mem, hipStream_t st) {
   DecodeParams p;
   p.X = static_cast<const char *>(X_new);
   p.C = static_cast<char *>(C);
@@ -621,7 +637,7 @@ extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, cons
   p.n_matched = n_matched;
   p.ref = ref;
   p.mag = mag;
-  decode_carve(desc, max_codes, workspace, &p);
+  decode_carve(desc, max_codes, scratch_mem, &p);
   p.dtype = desc->dtype;
   p.U = desc->batch * desc->n_kv_heads;
   p.m = desc->seq_len;
@@ -641,8 +657,10 @@ extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, cons
   const size_t lds = build_lds_words(p.m) * sizeof(uint32_t);
 #define SPINDLE_DECODE_LAUNCH(DT)                                                                          \
   do {                                                                                                     \
-    SPINDLE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_build<DT>),                     \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                \
+    static LdsLimit lim;                                                                                   \
+    if (spindle_status e = allow_lds(lim, reinterpret_cast<const void *>(&decode_build<DT>),               \
+                                     build_lds_words(kDecodeMax) * sizeof(uint32_t)))                      \
+      return e;                                                                                            \
     {                                                                                                      \
       ProfScope ps("decode_prep", st);                                                                     \
       hipLaunchKernelGGL(decode_prep<DT>, pg, dim3(kMatchThreads), 0, st, p);                              \
@@ -662,4 +680,65 @@ extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, cons
 #undef SPINDLE_DECODE_LAUNCH
   SPINDLE_HIP(hipGetLastError());
   return SPINDLE_OK;
+}
+
+}  // namespace
+
+extern "C" spindle_status spindle_decode_merge(const spindle_kv_desc *desc, const void *X_new, float theta,
+                                               int32_t max_codes, void *C, int32_t *n_codes, int32_t *n_found,
+                                               int32_t *n_matched, int32_t *ref, float *mag, void *workspace,
+                                               size_t workspace_bytes, void *stream) {
+  size_t need = 0;
+  spindle_status s = decode_check_args(desc, X_new, theta, max_codes, C, n_codes, n_found, ref, mag, &need);
+  if (s != SPINDLE_OK) return s;
+  if (!workspace) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "workspace is required");
+  if (reinterpret_cast<uintptr_t>(workspace) & 15) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  if (workspace_bytes < need) SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, need);
+  return decode_enqueue(desc, X_new, theta, max_codes, C, n_codes, n_found, n_matched, ref, mag, workspace,
+                        static_cast<hipStream_t>(stream));
+}
+
+namespace {
+
+constexpr int kStaticMaxDevices = 64;
+std::mutex g_static_mu;
+void *g_static_ptr[kStaticMaxDevices] = {};     // device address of `scratch` on each GPU, once looked up
+
+// Device address of `scratch` on the current device (each GPU holds its own copy of the array
+// at its own address).
+spindle_status static_scratch(void **out) {
+  int dev = 0;
+  SPINDLE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kStaticMaxDevices) SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "device %d: at most %d devices", dev, kStaticMaxDevices);
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void *ptr = nullptr;
+    SPINDLE_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) SPINDLE_FAIL(SPINDLE_ERR_HIP, "hipGetSymbolAddress returned a null address for the scratch array");
+    g_static_ptr[dev] = ptr;
+  }
+  *out = g_static_ptr[dev];
+  return SPINDLE_OK;
+}
+
+}  // namespace
+
+extern "C" size_t spindle_decode_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" spindle_status spindle_decode_merge_static(const spindle_kv_desc *desc, const void *X_new, float theta,
+                                                      int32_t max_codes, void *C, int32_t *n_codes, int32_t *n_found,
+                                                      int32_t *n_matched, int32_t *ref, float *mag, void *stream) {
+  size_t need = 0;
+  spindle_status s = decode_check_args(desc, X_new, theta, max_codes, C, n_codes, n_found, ref, mag, &need);
+  if (s != SPINDLE_OK) return s;
+  if (need > kStaticScratchBytes)
+    SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED,
+                 "this call needs %zu bytes of scratch memory, the built-in buffer holds %zu: fewer new tokens or "
+                 "problems per call, a smaller max_codes, or spindle_decode_merge with a workspace",
+                 need, kStaticScratchBytes);
+  void *mem = nullptr;
+  s = static_scratch(&mem);
+  if (s != SPINDLE_OK) return s;
+  return decode_enqueue(desc, X_new, theta, max_codes, C, n_codes, n_found, n_matched, ref, mag, mem,
+                        static_cast<hipStream_t>(stream));
 }
