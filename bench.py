@@ -312,9 +312,11 @@ def main():
     # Eq. 15 on this layer: eviction alone (r1) and replacement alone (r2 r3), each on the full layer
     stored = int(shallow.out["n_codes_k"].sum().item() + shallow.out["n_codes_v"].sum().item())
     bits = 8 * torch.empty(0, dtype=sb.torch_dtype(L.dtype)).element_size()
-    r1 = sb.spindle_reserve_ratio(2 * units * min(L.budget, L.seq_len), 2 * units * L.seq_len, 1, L.head_dim, 16, bits)[0]
-    _, r2, r3, r23 = sb.spindle_reserve_ratio(2 * units * L.seq_len, 2 * units * L.seq_len, stored, L.head_dim, 16, bits)
-    out["reserve_ratio"] = {"eviction_r1": r1, "replacement_r2": r2, "r3": r3, "replacement_r2_r3": r23}
+    # (16-bit references as the library's 65535-token limit allows; the magnitudes it writes are float32)
+    r1 = sb.spindle_reserve_ratio(2 * units * min(L.budget, L.seq_len), 2 * units * L.seq_len, 1, L.head_dim, 16, bits, 32)[0]
+    _, r2, r3, r23 = sb.spindle_reserve_ratio(2 * units * L.seq_len, 2 * units * L.seq_len, stored, L.head_dim, 16, bits, 32)
+    out["reserve_ratio"] = {"eviction_r1": r1, "replacement_r2": r2, "r3": r3, "replacement_r2_r3": r23,
+                            "index_bits": 16, "magnitude_bits": 32, "element_bits": bits}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, wl)
     print(json.dumps(out), flush=True)

@@ -302,8 +302,9 @@ size_t spindle_decode_static_capacity(void);
  *   alpha < r_c          layer 0 gets 1, the last layer 2 r_c - 1
  * (the printed "0.05" is beta and the printed "1 - 2 r_c" is read as 2 r_c - 1, which keeps the
  * mean at r_c and is continuous at alpha); layers in between are interpolated linearly (Eq. 6).
- *   budgets  HOST buffer of n_layers int32: window + floor(r_c(layer) * l_c + 0.5), the
- *            `budget` argument of spindle_compress_deep (it counts the window).
+ *   budgets  HOST buffer of n_layers int32: window + floor(r_c(layer) * l_c), Eq. 7's k plus the
+ *            window: the `budget` argument of spindle_compress_deep (it counts the window).
+ *            Eq. 6 is evaluated in doubles in the printed order of operations.
  *   ratios   optional HOST buffer of n_layers doubles: r_c(layer).
  * Errors: INVALID_ARG for n_layers < 1, window < 1, window > seq_len, beta outside [0, 1],
  * reserve_ratio outside [0, 1] or a null `budgets`.
@@ -315,13 +316,17 @@ spindle_status spindle_layer_budgets(double reserve_ratio, int32_t seq_len, int3
  * Sec. "Experiments", Eq. 15: reserve ratio of one layer, r = r1 * r2 * r3 with
  *   r1 = kept_tokens / total_tokens           (eviction; token counts summed over heads, K and V)
  *   r2 = codebook_entries / kept_tokens       (replacement; entries of the K and V codebooks)
- *   r3 = (head_dim + index_bits / elem_bits + 1) / head_dim   (one index and one magnitude per
- *        token, in units of cache elements; the printed fraction is garbled and read this way).
- * `out` is a HOST buffer of 4 doubles: r1, r2, r3, r.  Errors: INVALID_ARG for counts < 1,
- * kept_tokens > total_tokens, codebook_entries > kept_tokens or a null `out`.
+ *   r3 = (head_dim + index_bits / elem_bits + magnitude_bits / elem_bits) / head_dim
+ *        (one index and one magnitude per token, in units of cache elements.  The printed
+ *        fraction is garbled; it is read as (d_h + int_bit / key_bit + 1) / d_h, whose "+ 1" is a
+ *        magnitude as wide as a cache element: magnitude_bits = elem_bits gives exactly that.
+ *        The magnitudes spindle_compress_shallow writes are float32: magnitude_bits = 32.)
+ * `out` is a HOST buffer of 4 doubles: r1, r2, r3, r.  Errors: INVALID_ARG for counts or widths
+ * < 1, kept_tokens > total_tokens, codebook_entries > kept_tokens or a null `out`.
  */
 spindle_status spindle_reserve_ratio(int64_t kept_tokens, int64_t total_tokens, int64_t codebook_entries,
-                                     int32_t head_dim, int32_t index_bits, int32_t elem_bits, double *out);
+                                     int32_t head_dim, int32_t index_bits, int32_t elem_bits,
+                                     int32_t magnitude_bits, double *out);
 
 /* ------------------------------------------------------------------------- */
 /* Per-kernel timing (measurement aid for the roofline figures)                */

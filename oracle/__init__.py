@@ -78,7 +78,9 @@ def lib():
         L.oracle_decode_merge.restype = C.c_int
         L.oracle_layer_ratios.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int, C.c_double, _f64p]
         L.oracle_layer_ratios.restype = None
-        L.oracle_reserve_ratio.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int, C.c_int, C.c_int, _f64p]
+        L.oracle_layer_budgets.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int, C.c_double, _i32p]
+        L.oracle_layer_budgets.restype = None
+        L.oracle_reserve_ratio.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int, C.c_int, C.c_int, C.c_int, _f64p]
         L.oracle_reserve_ratio.restype = None
         _lib = L
     return _lib
@@ -216,6 +218,29 @@ def shallow_unit(X, theta, cap, literal=False):
                 ref=ref[:n].copy(), C=Cb[:k].copy())
 
 
+def shallow_unit_caps(X, theta, caps):
+    """One codebook problem under several caps: Eq. 8, Eq. 9 and the loop of Alg. 1 run once (they
+    do not depend on the cap), then the cap step and the codebook rows per cap, by the same C
+    functions oracle_shallow_unit calls in the same order.  Returns {cap: dict as shallow_unit,
+    without G and deg}."""
+    X = _c(X)
+    n, d = X.shape
+    mag = magnitudes(X)
+    G, deg = adjacency(X, theta, mag)
+    picks, ref0 = merge(G)
+    del G
+    nc = len(picks)
+    out = {}
+    for cap in caps:
+        ref = ref0.copy()
+        lib().oracle_cap_assign(X, mag, n, d, picks, nc, int(cap), ref)
+        k = min(nc, int(cap))
+        Cb = np.zeros((max(k, 1), d), dtype=np.float64)
+        lib().oracle_codebook(X, mag, d, picks, k, Cb)
+        out[int(cap)] = dict(mag=mag, picks=picks, n_codes_uncapped=nc, n_codes=k, ref=ref, C=Cb[:k].copy())
+    return out
+
+
 def shallow_layer(X, theta, cap, threads=8):
     """X [B, H, n, d] float64 -> list of per-unit dicts in (b, h) order."""
     B, H = X.shape[:2]
@@ -258,7 +283,14 @@ def layer_ratios(r, l, lw, m, beta=0.05):
     return out
 
 
-def reserve_ratio(kept, total, entries, dh=128, int_bit=16, key_bit=16):
+def layer_budgets(r, l, lw, m, beta=0.05):
+    out = np.empty(m, dtype=np.int32)
+    lib().oracle_layer_budgets(float(r), int(l), int(lw), int(m), float(beta), out)
+    return out
+
+
+def reserve_ratio(kept, total, entries, dh=128, int_bit=16, key_bit=16, mag_bit=None):
     out = np.empty(4, dtype=np.float64)
-    lib().oracle_reserve_ratio(float(kept), float(total), float(entries), int(dh), int(int_bit), int(key_bit), out)
+    lib().oracle_reserve_ratio(float(kept), float(total), float(entries), int(dh), int(int_bit), int(key_bit),
+                               int(key_bit if mag_bit is None else mag_bit), out)
     return out

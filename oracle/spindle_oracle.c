@@ -456,16 +456,40 @@ void oracle_layer_ratios(double r, int l, int lw, int m, double beta, double *rc
 }
 
 /*
+ * Eq. 7: tokens kept in layer lam, k = floor(r_c(lam) * l_c) as printed, plus the window,
+ * which is always kept (the budget counts it: r l = r_c l_c + l_w).  budgets_out [m].
+ * READING: k is kept within [0, l_c]; Eq. 6 evaluated in doubles can leave r_c(m-1) an ulp
+ * below an endpoint that is exactly 0 (beta = 0), whose floor would be -1.
+ */
+void oracle_layer_budgets(double r, int l, int lw, int m, double beta, int *budgets_out)
+{
+    double *rc = (double *)malloc(sizeof(double) * (size_t)m);
+    oracle_layer_ratios(r, l, lw, m, beta, rc);
+    for (int lam = 0; lam < m; ++lam) {
+        int k = (int)floor(rc[lam] * (double)(l - lw));
+        if (k < 0) k = 0;
+        if (k > l - lw) k = l - lw;
+        budgets_out[lam] = lw + k;
+    }
+    free(rc);
+}
+
+/*
  * Sec. "Experiments", Eq. 15: reserve ratio of one layer.  r1 = share of the tokens kept by
  * eviction, r2 = codebook entries per kept token, r3 = storage of a replaced token relative
- * to its d_h elements (one index of int_bit bits and one magnitude of one element on top;
- * the printed fraction is garbled and read as (d_h + int_bit / key_bit + 1) / d_h).
+ * to its d_h elements: one index of int_bit bits and one magnitude of mag_bit bits on top,
+ * both counted in cache elements of key_bit bits.
+ * READING: the printed fraction, int_bit over (key_bit + 1), is garbled; it is read as
+ * (d_h + int_bit / key_bit + 1) / d_h, the "+ 1" being a magnitude as wide as a cache
+ * element; a magnitude of another width (the text below the equation stores a float)
+ * counts mag_bit / key_bit elements.
  * out = {r1, r2, r3, r1 r2 r3}.
  */
-void oracle_reserve_ratio(double kept, double total, double entries, int dh, int int_bit, int key_bit, double *out)
+void oracle_reserve_ratio(double kept, double total, double entries, int dh, int int_bit, int key_bit,
+                          int mag_bit, double *out)
 {
     out[0] = kept / total;
     out[1] = entries / kept;
-    out[2] = (dh + (double)int_bit / key_bit + 1.0) / dh;
+    out[2] = (dh + (double)int_bit / key_bit + (double)mag_bit / key_bit) / dh;
     out[3] = out[0] * out[1] * out[2];
 }

@@ -70,7 +70,7 @@ def lib():
         L.spindle_shallow_stats.argtypes = [C.POINTER(KvDesc), i32, vp, vp, C.POINTER(C.c_int32)]
         L.spindle_layer_budgets.argtypes = [C.c_double, i32, i32, i32, C.c_double, C.POINTER(C.c_int32),
                                             C.POINTER(C.c_double)]
-        L.spindle_reserve_ratio.argtypes = [C.c_int64, C.c_int64, C.c_int64, i32, i32, i32, C.POINTER(C.c_double)]
+        L.spindle_reserve_ratio.argtypes = [C.c_int64, C.c_int64, C.c_int64, i32, i32, i32, i32, C.POINTER(C.c_double)]
         L.spindle_decode_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_decode_merge.argtypes = [C.POINTER(KvDesc), vp, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spindle_decode_merge_static.argtypes = [C.POINTER(KvDesc), vp, f32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -199,11 +199,12 @@ def spindle_layer_budgets(reserve_ratio, seq_len, window, n_layers, beta=0.05):
     return np.array(budgets[:], dtype=np.int32), np.array(ratios[:], dtype=np.float64)
 
 
-def spindle_reserve_ratio(kept_tokens, total_tokens, codebook_entries, head_dim=128, index_bits=16, elem_bits=16):
-    """Returns (r1, r2, r3, r) of one layer."""
+def spindle_reserve_ratio(kept_tokens, total_tokens, codebook_entries, head_dim=128, index_bits=16, elem_bits=16,
+                          magnitude_bits=32):
+    """Returns (r1, r2, r3, r) of one layer; the library's magnitudes are float32."""
     out = (C.c_double * 4)()
     _check(lib().spindle_reserve_ratio(int(kept_tokens), int(total_tokens), int(codebook_entries), int(head_dim),
-                                       int(index_bits), int(elem_bits), out))
+                                       int(index_bits), int(elem_bits), int(magnitude_bits), out))
     return tuple(out[:])
 
 

@@ -111,6 +111,18 @@ struct Elem<SPINDLE_BF16> {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
+// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at
+// lds_addr + 16 i (lds_addr wave-uniform).  Issued as assembly on purpose: the compiler
+// would put a wait for the load in front of every later LDS read of the kernel, since it
+// cannot tell which of them touch the destination.  Completion is the caller's business
+// (s_waitcnt vmcnt + barrier before any lane reads the destination).
+__device__ __forceinline__ void lds_dma16(const void *src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(src)
+               : "memory", "m0");
+}
+
 // Spread the four nibbles of a 16-bit value to bits [8k, 8k+4) of a 32-bit word.
 __device__ __forceinline__ uint32_t spread_nibbles(uint32_t p) {
   return (p & 0xFu) | ((p & 0xF0u) << 4) | ((p & 0xF00u) << 8) | ((p & 0xF000u) << 12);

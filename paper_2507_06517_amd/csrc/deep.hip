@@ -1,12 +1,20 @@
 // Attention-weight token eviction (Sec. "Attention Weight Based Token Eviction").
 //
 // Kernels, all enqueued on the caller's stream:
-//   deep_pass<.., false>  window logits by MFMA, per-row softmax statistics (Eq. 1)
-//   deep_pass<.., true>   merges the per-chunk statistics into (max, 1/sum) per query row,
-//                         recomputes the logits, forms softmax weights, sums them over
-//                         the window queries and the GQA group (Eq. 2, 3)
-//   deep_select           max-pool, radix select of the k largest, ordered compaction (Eq. 7)
-//   deep_gather           K_out = K[kept], V_out = V[kept]
+//   deep_stats        window logits by MFMA, per-row softmax statistics of a chunk of keys (Eq. 1)
+//   deep_accumulate   merges the per-chunk statistics into max + log2(sum) per query row,
+//                     recomputes the logits, forms softmax weights, sums them over the window
+//                     queries and the GQA group (Eq. 2, 3)
+//   deep_select       max-pool, 4096-bin histogram of the pooled scores over many workgroups;
+//                     the last workgroup of a unit finds the k-th largest score from the
+//                     histogram and the few scores that share its bin, then writes the kept
+//                     positions in order (Eq. 7)
+//   deep_gather       K_out = K[kept], V_out = V[kept]
+//
+// Both passes over K stream 64-KiB stages of keys through LDS with direct global->LDS loads
+// (two stages, the next one in flight while the current one is multiplied); the 16-byte pieces
+// of a row are XOR-swizzled by the row number so that the fragment reads of sixteen
+// consecutive rows fall into different banks.
 #include <math.h>
 
 #include "common.h"
@@ -15,85 +23,286 @@
 namespace spindle {
 namespace {
 
-constexpr int kStageKeys = 128;      // keys per LDS stage
-constexpr int kMaxStagesPerBlock = 8; // at most 1024 keys per block
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kMaxStagesPerBlock = 4;
+constexpr int kBins = 4096;          // histogram over the top 12 bits of the order-preserving score keys
+
+// Staging geometry of one element type: a stage is 64 KiB of keys.
+template <int DT>
+struct Geo {
+  typedef Mma<DT> M;
+  static constexpr int kRowBytes = M::kRowBytes;
+  static constexpr int kPieces = kRowBytes / 16;                   // 16-byte pieces per key
+  static constexpr int kStageKeys = DT == SPINDLE_F32 ? 128 : 256;
+  static constexpr int kStageBytes = kStageKeys * kRowBytes;
+  static constexpr int kWaves = DT == SPINDLE_F32 ? 4 : 8;
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kTiles = kStageKeys / 32;                   // 32-key MFMA tiles per stage
+  static constexpr int kRowsPerLoad = 1024 / kRowBytes;            // keys one wave-wide load brings
+  static constexpr int kLoadsPerWave = kStageBytes / 1024 / kWaves;
+
+  // Stage of keys key0 .. key0 + kStageKeys - 1 into the LDS buffer at byte address `lds`; keys
+  // past the end of the sequence repeat the last one (the callers never use their results).
+  static __device__ __forceinline__ void load(const char *Kunit, size_t pitch, int key0, int l, uint32_t lds,
+                                              int wave, int lane) {
+#pragma unroll
+    for (int j = 0; j < kLoadsPerWave; ++j) {
+      const int q = wave * kLoadsPerWave + j;
+      const int r = q * kRowsPerLoad + lane / kPieces;
+      const int piece = (lane % kPieces) ^ (r & (kPieces - 1));
+      int key = key0 + r;
+      key = key < l ? key : l - 1;
+      lds_dma16(Kunit + (size_t)key * pitch + piece * 16, lds + q * 1024);
+    }
+  }
+  // MFMA operand fragment ks of staged key `row` for lane group g
+  static __device__ __forceinline__ typename M::frag frag(const char *buf, int row, int ks, int g) {
+    if constexpr (DT == SPINDLE_F32) {
+      const int e = 2 * ks + g;
+      return *reinterpret_cast<const float *>(buf + row * kRowBytes + ((((e >> 2) ^ (row & 31)) << 4) | ((e & 3) << 2)));
+    } else {
+      return *reinterpret_cast<const typename M::frag *>(buf + row * kRowBytes + (((2 * ks + g) ^ (row & 15)) << 4));
+    }
+  }
+};
+
 // Stages a block takes: as many as leave about one block per compute unit.  The fixed cost of
 // a block (query fragments, the merge of the chunk statistics) outweighs idle units only while
 // the grid still covers the chip.
-inline int stages_per_block(int U, int l) {
-  const long total = (long)U * ((l + kStageKeys - 1) / kStageKeys);
+inline int stages_per_block(int U, int l, int stage_keys) {
+  const long total = (long)U * ((l + stage_keys - 1) / stage_keys);
   const long s = total / 256;
   return s < 1 ? 1 : (s > kMaxStagesPerBlock ? kMaxStagesPerBlock : (int)s);
 }
-constexpr int kDeepThreads = 256;
-constexpr float kLog2e = 1.4426950408889634f;
 
 struct DeepParams {
   const char *K;       // [U][l][128] elements
   const char *Q;       // [U][R][128] elements (R = hn*lw rows, head-major)
-  float2 *partial;     // [U][nchunks][Rpad] (max, sum) per chunk of keys
+  float2 *partial;     // [U][nchunks][Rpad] (max, sum) per chunk of keys, logits in base-2 units
   float *scores;       // [U][lc] group-averaged accumulated attention
+  int *hist;           // [U][kBins] cleared here for deep_select
+  int *done;           // [U]
   int l, lc, lw, hn, R, Rpad, nchunks;
-  int stages;          // 128-key stages per block
+  int stages;          // stages per block
   KvLayout lay;        // rows of K
   float sc2;           // scale * log2(e): logits are kept in base-2 units
   float inv_hn;
   int norm;
 };
 
-// ---------------------------------------------------------------- stage loading
-template <int DT>
-struct Stage {
+// (max, sum of exp2(. - max)) of two disjoint sets of logits
+__device__ __forceinline__ void merge_stats(float &m, float &z, float m2, float z2) {
+  const float mm = fmaxf(m, m2);
+  if (mm == -INFINITY) return;                         // both empty
+  z = z * __builtin_amdgcn_exp2f(m - mm) + z2 * __builtin_amdgcn_exp2f(m2 - mm);
+  m = mm;
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *ptr) {
+  return (uint32_t)(size_t)(__attribute__((address_space(3))) const char *)ptr;
+}
+
+// Pass 1.  Grid (chunks, units).  WR waves split the (padded) query rows in groups of 64, the
+// other kWaves / WR split the 32-key tiles of a stage.  The matrix product is taken as keys x
+// query rows, so a lane owns one query row (its column of the result) and the sixteen results
+// in its registers are sixteen keys: the running (max, sum) of a row is two registers per lane
+// and needs no exchange until the end of the block.
+template <int DT, int WR>
+__global__ __launch_bounds__(Geo<DT>::kThreads) void deep_stats(DeepParams p) {
+  typedef Geo<DT> S;
   typedef Mma<DT> M;
-  static constexpr int kThreadsPerRow = M::kRowBytes / 16;
-  static constexpr int kRowsPerPass = kDeepThreads / kThreadsPerRow;
-  static constexpr int kPasses = kStageKeys / kRowsPerPass;
-  static constexpr int kBytes = kStageKeys * M::kLdsRow;
+  constexpr int WK = S::kWaves / WR;
+  constexpr int kTilesPerWave = S::kTiles / WK;
+  constexpr bool kPrefetch = DT != SPINDLE_F32;        // the 64 one-register fragments of a float tile are read as they are used
+  static_assert(kTilesPerWave >= 1, "every wave needs a tile of each stage");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-  // global -> registers; keys at or beyond `l` read as zero
-  static __device__ __forceinline__ void fetch(u4 (&r)[kPasses], const char *Kunit, size_t pitch, int k0, int l) {
-    const int tr = threadIdx.x / kThreadsPerRow, tc = threadIdx.x % kThreadsPerRow;
-#pragma unroll
-    for (int p = 0; p < kPasses; ++p) {
-      const int key = k0 + p * kRowsPerPass + tr;
-      u4 v = {0, 0, 0, 0};
-      if (key < l) v = *reinterpret_cast<const u4 *>(Kunit + (size_t)key * pitch + tc * 16);
-      r[p] = v;
-    }
-  }
-  static __device__ __forceinline__ void store(const u4 (&r)[kPasses], char *lds) {
-    const int tr = threadIdx.x / kThreadsPerRow, tc = threadIdx.x % kThreadsPerRow;
-#pragma unroll
-    for (int p = 0; p < kPasses; ++p)
-      *reinterpret_cast<u4 *>(lds + (p * kRowsPerPass + tr) * M::kLdsRow + tc * 16) = r[p];
-  }
-};
-
-// One pass over a block's keys.  ACCUM = false: softmax statistics; true: weights.
-// WR waves split the (padded) query rows in groups of 64, the other 4/WR split the
-// four 32-key tiles of a stage.
-template <int DT, int WR, bool ACCUM>
-__global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
-  typedef Mma<DT> M;
-  typedef Stage<DT> S;
-  constexpr int WK = 4 / WR;
-  constexpr int kTilesPerWave = 4 / WK;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  // ACCUM: column partial sums [2][2*WR][kStageKeys] placed after the stage buffers
-  float *colpart = reinterpret_cast<float *>(smem + 2 * S::kBytes);
-
-  const int u = blockIdx.y;
-  const int chunk = blockIdx.x;
+  const int u = blockIdx.y, chunk = blockIdx.x;
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int g = lane >> 5, c = lane & 31;
   const int wr = wave % WR, wk = wave / WR;
-  const int key_begin = chunk * p.stages * kStageKeys;
-  const int key_limit = ACCUM ? p.lc : p.l;   // keys at or beyond this index are not needed
+  if (chunk == 0) {                                    // counters of this unit's selection
+    for (int i = threadIdx.x; i < kBins; i += S::kThreads) p.hist[(size_t)u * kBins + i] = 0;
+    if (threadIdx.x == 0) p.done[u] = 0;
+  }
+  const int key_begin = chunk * p.stages * S::kStageKeys;
+  int nst = (p.l - key_begin + S::kStageKeys - 1) / S::kStageKeys;
+  nst = nst < p.stages ? nst : p.stages;
   const char *Kunit = p.K + kv_unit_offset(p.lay, u);
   const size_t kpitch = (size_t)p.lay.st;
   const char *Qunit = p.Q + (size_t)u * p.R * M::kRowBytes;
+  const uint32_t lds0 = lds_address(smem);
+
+  S::load(Kunit, kpitch, key_begin, p.l, lds0, wave, lane);
 
   // query fragments stay in registers for the whole block
+  typename M::frag qf[2][M::kSteps];
+  int klim[2];                                         // last key this lane's query row may attend to
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = 64 * wr + 32 * rb + c;
+#pragma unroll
+    for (int ks = 0; ks < M::kSteps; ++ks)
+      qf[rb][ks] = row < p.R ? M::load(Qunit + (size_t)row * M::kRowBytes, ks, g) : M::zero();
+    klim[rb] = row < p.R ? p.lc + row % p.lw : -1;    // causal mask: query b of the window sits at l_c + b
+  }
+  float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
+  __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wave's part of the stage has landed
+  __syncthreads();
+
+  for (int s = 0; s < nst; ++s) {
+    const int k0 = key_begin + s * S::kStageKeys;
+    if (s + 1 < nst) S::load(Kunit, kpitch, k0 + S::kStageKeys, p.l, lds0 + ((s + 1) & 1) * S::kStageBytes, wave, lane);
+    const char *buf = smem + (s & 1) * S::kStageBytes;
+    const bool tail = k0 + S::kStageKeys > p.lc;       // causal mask / end of the sequence
+    // The fragments of a tile are fetched from LDS together, those of the wave's next tile right
+    // after the matrix instructions of the current one are issued, so that the LDS latency falls
+    // into the vector work on the results (the other wave of the SIMD multiplies meanwhile).
+    typename M::frag kf[kPrefetch ? M::kSteps : 1];
+    if (kPrefetch && k0 + wk * 32 < p.l) {
+#pragma unroll
+      for (int ks = 0; ks < M::kSteps; ++ks) kf[kPrefetch ? ks : 0] = S::frag(buf, wk * 32 + c, ks, g);
+    }
+#pragma unroll
+    for (int t = 0; t < kTilesPerWave; ++t) {
+      const int ct = wk + t * WK;
+      const int tk0 = k0 + ct * 32;
+      if (tk0 >= p.l) continue;                        // wave-uniform
+      f16v acc[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
+      if (kPrefetch) {
+#pragma unroll
+        for (int ks = 0; ks < M::kSteps; ++ks) {
+          acc[0] = M::mma(kf[kPrefetch ? ks : 0], qf[0][ks], acc[0]);
+          acc[1] = M::mma(kf[kPrefetch ? ks : 0], qf[1][ks], acc[1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < kTilesPerWave && tk0 + WK * 32 < p.l) {
+#pragma unroll
+          for (int ks = 0; ks < M::kSteps; ++ks) kf[kPrefetch ? ks : 0] = S::frag(buf, (ct + WK) * 32 + c, ks, g);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < M::kSteps; ++ks) {
+          const typename M::frag f = S::frag(buf, ct * 32 + c, ks, g);
+          acc[0] = M::mma(f, qf[0][ks], acc[0]);
+          acc[1] = M::mma(f, qf[1][ks], acc[1]);
+        }
+      }
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        if (!tail) {
+          float hi = acc[rb][0], lo = acc[rb][0];
+#pragma unroll
+          for (int v = 1; v < 16; ++v) hi = fmaxf(hi, acc[rb][v]);
+          if (p.sc2 < 0.f) {                           // uniform; a negative scale turns the order round
+#pragma unroll
+            for (int v = 1; v < 16; ++v) lo = fminf(lo, acc[rb][v]);
+            hi = lo;
+          }
+          const float mn = fmaxf(m[rb], hi * p.sc2);
+          float sum = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][v], p.sc2, -mn));
+          z[rb] = z[rb] * __builtin_amdgcn_exp2f(m[rb] - mn) + sum;
+          m[rb] = mn;
+        } else {
+          float tv[16];
+          float hi = -INFINITY;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = tk0 + mma_row(v, g);
+            tv[v] = key <= klim[rb] && key < p.l ? acc[rb][v] * p.sc2 : -INFINITY;
+            hi = fmaxf(hi, tv[v]);
+          }
+          const float mn = fmaxf(m[rb], hi);
+          if (mn > -INFINITY) {
+            float sum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(tv[v] - mn);
+            z[rb] = z[rb] * __builtin_amdgcn_exp2f(m[rb] - mn) + sum;
+            m[rb] = mn;
+          }
+        }
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  }
+
+  // the two lane groups of a wave hold different keys of the same rows; then the WK waves of a
+  // row group through LDS, in wave order
+  float2 *red = reinterpret_cast<float2 *>(smem);      // [WK][64 * WR]
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const float m2 = __shfl_xor(m[rb], 32), z2 = __shfl_xor(z[rb], 32);
+    float mm = g ? m2 : m[rb], zz = g ? z2 : z[rb];    // same operand order in both lane groups
+    merge_stats(mm, zz, g ? m[rb] : m2, g ? z[rb] : z2);
+    if (g == 0) red[wk * (64 * WR) + 64 * wr + 32 * rb + c] = make_float2(mm, zz);
+  }
+  __syncthreads();
+  const int row = threadIdx.x;
+  if (row < 64 * WR) {
+    float2 e = red[row];
+#pragma unroll
+    for (int j = 1; j < WK; ++j) {
+      const float2 o = red[j * (64 * WR) + row];
+      merge_stats(e.x, e.y, o.x, o.y);
+    }
+    p.partial[((size_t)u * p.nchunks + chunk) * p.Rpad + row] = e;
+  }
+}
+
+// Pass 2.  Grid (chunks of context keys, units).  Here the product is taken as query rows x
+// keys: a lane owns one key and its registers hold sixteen query rows, so the sum over the
+// window queries and the heads of the group is a sum over the lane's own registers.  The
+// weight of (row, key) is exp2(logit - c_row) with c_row = max + log2(sum) of the row.
+template <int DT, int WR>
+__global__ __launch_bounds__(Geo<DT>::kThreads) void deep_accumulate(DeepParams p) {
+  typedef Geo<DT> S;
+  typedef Mma<DT> M;
+  constexpr int WK = S::kWaves / WR;
+  constexpr int kTilesPerWave = S::kTiles / WK;
+  constexpr bool kPrefetch = DT != SPINDLE_F32;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  float *colpart = reinterpret_cast<float *>(smem + 2 * S::kStageBytes);      // [2][WR][kStageKeys]
+  float *row_const = colpart + 2 * WR * S::kStageKeys;                          // [256]
+
+  const int u = blockIdx.y, chunk = blockIdx.x;
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int g = lane >> 5, c = lane & 31;
+  const int wr = wave % WR, wk = wave / WR;
+  const int key_begin = chunk * p.stages * S::kStageKeys;
+  int nst = (p.lc - key_begin + S::kStageKeys - 1) / S::kStageKeys;            // only context keys get a score
+  nst = nst < p.stages ? nst : p.stages;
+  const char *Kunit = p.K + kv_unit_offset(p.lay, u);
+  const size_t kpitch = (size_t)p.lay.st;
+  const char *Qunit = p.Q + (size_t)u * p.R * M::kRowBytes;
+  const uint32_t lds0 = lds_address(smem);
+
+  S::load(Kunit, kpitch, key_begin, p.l, lds0, wave, lane);
+
+  // max + log2(sum) of every query row from the per-chunk statistics of the first pass, merged
+  // in chunk order by one thread per row (every block of the unit does the same sum in the same
+  // order)
+  if ((int)threadIdx.x < p.Rpad) {
+    const int row = threadIdx.x;
+    const float2 *part = p.partial + (size_t)u * p.nchunks * p.Rpad + row;
+    float mm = -INFINITY, zz = 0.f;
+    for (int ch0 = 0; ch0 < p.nchunks; ch0 += 32) {   // 32 records in flight: one trip for 32 k keys
+      float2 e[32];
+#pragma unroll
+      for (int j = 0; j < 32; ++j) e[j] = ch0 + j < p.nchunks ? part[(size_t)(ch0 + j) * p.Rpad] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+      for (int j = 0; j < 32; ++j) merge_stats(mm, zz, e[j].x, e[j].y);
+    }
+    row_const[row] = row < p.R && zz > 0.f ? mm + log2f(zz) : INFINITY;        // rows of the padding weigh nothing
+  }
+
   typename M::frag qf[2][M::kSteps];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
@@ -102,185 +311,76 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
     for (int ks = 0; ks < M::kSteps; ++ks)
       qf[rb][ks] = row < p.R ? M::load(Qunit + (size_t)row * M::kRowBytes, ks, g) : M::zero();
   }
-
-  // accumulate pass: (max, 1/sum) of every query row from the per-chunk statistics of the
-  // first pass, merged in chunk order by one thread per row (every block of the unit does
-  // the same sum in the same order)
-  __shared__ float2 row_stats[ACCUM ? 256 : 1];
-  if (ACCUM) {
-    if ((int)threadIdx.x < p.Rpad) {
-      const int row = threadIdx.x;
-      const float2 *part = p.partial + (size_t)u * p.nchunks * p.Rpad + row;
-      float m = -INFINITY, z = 0.f;
-#pragma unroll 8
-      for (int ch = 0; ch < p.nchunks; ++ch) {
-        const float2 e = part[(size_t)ch * p.Rpad];
-        if (e.y > 0.f) {
-          if (e.x > m) {
-            z = z * __builtin_amdgcn_exp2f(m - e.x) + e.y;
-            m = e.x;
-          } else {
-            z += e.y * __builtin_amdgcn_exp2f(e.x - m);
-          }
-        }
-      }
-      const bool ok = row < p.R && z > 0.f;
-      row_stats[row] = make_float2(ok ? m : 0.f, ok ? 1.f / z : 0.f);
-    }
-    __syncthreads();
-  }
-
-  // per-row state of this lane: stats pass (reference, sum); accumulate pass (max, weight)
-  float s0[2][16], s1[2][16];
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  float cst[2][16];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (ACCUM) {
-        const int row = 64 * wr + 32 * rb + mma_row(v, g);
-        const float2 st = row_stats[row];
-        s0[rb][v] = st.x;
-        s1[rb][v] = st.y;
-      } else {
-        s0[rb][v] = -INFINITY;
-        s1[rb][v] = 0.f;
-      }
-    }
+    for (int v = 0; v < 16; ++v) cst[rb][v] = row_const[64 * wr + 32 * rb + mma_row(v, g)];
 
-  u4 regs[S::kPasses];
-  S::fetch(regs, Kunit, kpitch, key_begin, key_limit);
-  S::store(regs, smem);
-  __syncthreads();
-
-  for (int s = 0; s < p.stages; ++s) {
-    const int k0 = key_begin + s * kStageKeys;
-    if (k0 >= key_limit) break;                       // uniform over the block
-    const bool more = (s + 1 < p.stages) && (k0 + kStageKeys < key_limit);
-    if (more) S::fetch(regs, Kunit, kpitch, k0 + kStageKeys, key_limit);
-
-    if (ACCUM && s > 0 && threadIdx.x < kStageKeys) {
-      // finish the previous stage: fixed-order sum of the partial column sums
-      const float *cp = colpart + ((s - 1) & 1) * (2 * WR * kStageKeys);
-      float sum = 0.f;
+  for (int s = 0; s < nst; ++s) {
+    const int k0 = key_begin + s * S::kStageKeys;
+    if (s + 1 < nst) S::load(Kunit, kpitch, k0 + S::kStageKeys, p.l, lds0 + ((s + 1) & 1) * S::kStageBytes, wave, lane);
+    const char *buf = smem + (s & 1) * S::kStageBytes;
+    float *cp = colpart + (s & 1) * (WR * S::kStageKeys);
+    typename M::frag kf[kPrefetch ? M::kSteps : 1];    // as in deep_stats
+    if (kPrefetch && k0 + wk * 32 < p.lc) {
 #pragma unroll
-      for (int j = 0; j < 2 * WR; ++j) sum += cp[j * kStageKeys + threadIdx.x];
-      const int a = k0 - kStageKeys + threadIdx.x;
-      if (a < p.lc) {
-        float v = sum * p.inv_hn;
-        if (p.norm == SPINDLE_NORM_PAPER) v = v / (float)(p.l - a);
-        p.scores[(size_t)u * p.lc + a] = v;
-      }
+      for (int ks = 0; ks < M::kSteps; ++ks) kf[kPrefetch ? ks : 0] = S::frag(buf, wk * 32 + c, ks, g);
     }
-
-    const char *lds = smem + (s & 1) * S::kBytes;
-    const bool tail = !ACCUM && (k0 + kStageKeys > p.lc);   // causal mask / end of sequence
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t) {
       const int ct = wk + t * WK;
+      if (k0 + ct * 32 >= p.lc) continue;              // wave-uniform
       f16v acc[2];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
-      const char *krow = lds + (ct * 32 + c) * M::kLdsRow;
+      if (kPrefetch) {
 #pragma unroll
-      for (int ks = 0; ks < M::kSteps; ++ks) {
-        const typename M::frag kf = M::load(krow, ks, g);
-        acc[0] = M::mma(qf[0][ks], kf, acc[0]);
-        acc[1] = M::mma(qf[1][ks], kf, acc[1]);
-      }
-      if (ACCUM) {
-        float cs0 = 0.f, cs1 = 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          cs0 = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[0][v], p.sc2, -s0[0][v])), s1[0][v], cs0);
-          cs1 = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[1][v], p.sc2, -s0[1][v])), s1[1][v], cs1);
+        for (int ks = 0; ks < M::kSteps; ++ks) {
+          acc[0] = M::mma(qf[0][ks], kf[kPrefetch ? ks : 0], acc[0]);
+          acc[1] = M::mma(qf[1][ks], kf[kPrefetch ? ks : 0], acc[1]);
         }
-        colpart[(s & 1) * (2 * WR * kStageKeys) + (2 * wr + g) * kStageKeys + ct * 32 + c] = cs0 + cs1;
-      } else if (!tail) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < kTilesPerWave && k0 + (ct + WK) * 32 < p.lc) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          float d[16], t_[16];
-          float dmax = -INFINITY;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            t_[v] = acc[rb][v] * p.sc2;
-            d[v] = t_[v] - s0[rb][v];
-            dmax = fmaxf(dmax, d[v]);
-          }
-          if (__any(dmax > 40.f)) {      // move the reference up (always on the first tile)
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-              if (d[v] > 0.f) {
-                s1[rb][v] *= __builtin_amdgcn_exp2f(s0[rb][v] - t_[v]);
-                s0[rb][v] = t_[v];
-                d[v] = 0.f;
-              }
-          }
-#pragma unroll
-          for (int v = 0; v < 16; ++v) s1[rb][v] += __builtin_amdgcn_exp2f(d[v]);
+          for (int ks = 0; ks < M::kSteps; ++ks) kf[kPrefetch ? ks : 0] = S::frag(buf, (ct + WK) * 32 + c, ks, g);
         }
+        __builtin_amdgcn_sched_barrier(0);
       } else {
-        const int key = k0 + ct * 32 + c;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = 64 * wr + 32 * rb + mma_row(v, g);
-            const bool valid = row < p.R && key < p.l && key <= p.lc + (row % p.lw);
-            if (valid) {
-              const float t = acc[rb][v] * p.sc2;
-              if (t > s0[rb][v]) {
-                s1[rb][v] = s1[rb][v] * __builtin_amdgcn_exp2f(s0[rb][v] - t) + 1.f;
-                s0[rb][v] = t;
-              } else {
-                s1[rb][v] += __builtin_amdgcn_exp2f(t - s0[rb][v]);
-              }
-            }
-          }
+        for (int ks = 0; ks < M::kSteps; ++ks) {
+          const typename M::frag f = S::frag(buf, ct * 32 + c, ks, g);
+          acc[0] = M::mma(qf[0][ks], f, acc[0]);
+          acc[1] = M::mma(qf[1][ks], f, acc[1]);
+        }
       }
-    }
-    if (more) S::store(regs, smem + ((s + 1) & 1) * S::kBytes);
-    __syncthreads();
-    if (ACCUM && !more && threadIdx.x < kStageKeys) {
-      const float *cp = colpart + (s & 1) * (2 * WR * kStageKeys);
-      float sum = 0.f;
+      float cs0 = 0.f, cs1 = 0.f;
 #pragma unroll
-      for (int j = 0; j < 2 * WR; ++j) sum += cp[j * kStageKeys + threadIdx.x];
+      for (int v = 0; v < 16; ++v) {
+        cs0 += __builtin_amdgcn_exp2f(fmaf(acc[0][v], p.sc2, -cst[0][v]));
+        cs1 += __builtin_amdgcn_exp2f(fmaf(acc[1][v], p.sc2, -cst[1][v]));
+      }
+      // the other sixteen rows of each block of 32 sit in the other lane group
+      const uint32_t csb = __float_as_uint(cs0 + cs1);
+      const auto both = __builtin_amdgcn_permlane32_swap(csb, csb, false, false);   // [0]: group 0's value, [1]: group 1's
+      if (g == 0) cp[wr * S::kStageKeys + ct * 32 + c] = __uint_as_float(both[0]) + __uint_as_float(both[1]);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if ((int)threadIdx.x < S::kStageKeys) {            // fixed-order sum over the row groups
       const int a = k0 + threadIdx.x;
       if (a < p.lc) {
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < WR; ++j) sum += cp[j * S::kStageKeys + threadIdx.x];
         float v = sum * p.inv_hn;
         if (p.norm == SPINDLE_NORM_PAPER) v = v / (float)(p.l - a);
         p.scores[(size_t)u * p.lc + a] = v;
       }
-    }
-  }
-
-  if (!ACCUM) {
-    // lane partials -> LDS (swizzled slot so that the row-wise readers spread over banks)
-    constexpr int kSlots = WK * 32;
-    __syncthreads();
-    float2 *red = reinterpret_cast<float2 *>(smem);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = 64 * wr + 32 * rb + mma_row(v, g);
-        const int slot = (wk * 32 + c + row) % kSlots;
-        red[row * kSlots + slot] = make_float2(s0[rb][v], s1[rb][v]);
-      }
-    __syncthreads();
-    const int row = threadIdx.x;
-    if (row < 64 * WR) {
-      float m = -INFINITY;
-      for (int j = 0; j < kSlots; ++j) m = fmaxf(m, red[row * kSlots + (j + row) % kSlots].x);
-      float z = 0.f;
-      if (m > -INFINITY)
-        for (int j = 0; j < kSlots; ++j) {
-          const float2 e = red[row * kSlots + (j + row) % kSlots];
-          if (e.y > 0.f) z += e.y * __builtin_amdgcn_exp2f(e.x - m);
-        }
-      p.partial[((size_t)u * p.nchunks + chunk) * p.Rpad + row] = make_float2(m, z);
     }
   }
 }
@@ -288,33 +388,153 @@ __global__ __launch_bounds__(kDeepThreads) void deep_pass(DeepParams p) {
 // ---------------------------------------------------------------- pool + top-k
 struct SelectParams {
   const float *scores;   // [U][lc]
-  float *pooled;         // [U][lc]
+  uint32_t *pooled;      // [U][lc] pooled scores as order-preserving keys
   float *scores_out;     // optional [U][lc]
+  int *hist;             // [U][kBins], zero on entry
+  int *done;             // [U], zero on entry
   const int32_t *budgets;
   int32_t *kept;         // [U][out_stride]
-  int l, lc, lw, pool, budget, out_stride;
+  int l, lc, lw, pool, budget, out_stride, nseg;
 };
 
 constexpr int kSelThreads = 1024;
+constexpr int kSegLen = 2048;        // context positions per workgroup
+constexpr int kHaloMax = 256;        // pooling radius up to which the raw scores of a segment sit in LDS
+constexpr int kCandMax = 8192;       // scores sharing the threshold's bin that are ranked in LDS
 
 __device__ __forceinline__ uint32_t orderable(float f) {
   const uint32_t b = __float_as_uint(f);
   return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 
-constexpr int kSelInLds = 36 * 1024;   // pooled scores of a unit that fit in LDS
+// Stores and loads that workgroups of one launch use to hand data to each other: performed at
+// device scope (they go through to, and come from, memory that every compute unit sees), so
+// that no cache has to be written back or invalidated as a fence would do; the writer waits for
+// its stores (s_waitcnt vmcnt(0)) before it takes its ticket.
+__device__ __forceinline__ void store_shared(uint32_t *ptr, uint32_t v) {
+  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t load_shared(const uint32_t *ptr) {
+  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-__global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p, int vals_in_lds) {
-  extern __shared__ __attribute__((aligned(16))) uint32_t sel_lds[];
-  __shared__ int hist[256];
+// Counts, from the top, the digits of the keys `src[0 .. nsrc)` that match `prefix` above
+// `bits_left`, and narrows (prefix, krem) by one digit of width w: afterwards the krem-th
+// largest matching key still matches.  All threads of the block call it with the same arguments.
+__device__ void radix_step(const uint32_t *src, int nsrc, bool other_groups_wrote, uint32_t &prefix, int &krem, int &bits_left, int *hist,
+                           uint32_t *sh_prefix, int *sh_krem) {
+  const int tid = threadIdx.x, lane = lane_id();
+  const int w = bits_left < 8 ? bits_left : 8, shift = bits_left - w;
+  const uint32_t dmask = (1u << w) - 1u;
+  if (tid < 256) hist[tid] = 0;
+  __syncthreads();
+  constexpr int kAtOnce = 4;                           // independent keys per thread and trip
+  for (int a0 = 0; a0 < nsrc; a0 += kAtOnce * kSelThreads) {
+    uint32_t x[kAtOnce];
+#pragma unroll
+    for (int q = 0; q < kAtOnce; ++q) {
+      const int a = a0 + q * kSelThreads + tid;
+      x[q] = a < nsrc ? (other_groups_wrote ? load_shared(src + a) : src[a]) : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < kAtOnce; ++q) {
+      const int a = a0 + q * kSelThreads + tid;
+      const bool in = a < nsrc && (bits_left == 32 || (x[q] >> bits_left) == (prefix >> bits_left));
+      const int d = (int)((x[q] >> shift) & dmask);
+      if (in) {
+        // keys crowd into few digits: the digit of the first lane that takes part is counted
+        // once for all lanes that share it
+        const int d0 = __builtin_amdgcn_readfirstlane(d);
+        const unsigned long long same = __ballot(d == d0);
+        if (d != d0) atomicAdd(&hist[d], 1);
+        else if (lane == __builtin_ctzll(same)) atomicAdd(&hist[d0], __popcll(same));
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {
+    // lane t owns counters 4t .. 4t+3; find the digit at which the count from the top reaches krem
+    const int h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+    const int mine = h0 + h1 + h2 + h3;
+    int above = mine;                                  // inclusive sum over lanes >= t
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int x = __shfl_down(above, o);
+      if (tid + o < 64) above += x;
+    }
+    above -= mine;                                     // keys in counters of higher lanes
+    const int hh[4] = {h0, h1, h2, h3};
+    int run = above;
+#pragma unroll
+    for (int j = 3; j >= 0; --j) {
+      if (run < krem && krem <= run + hh[j]) {
+        *sh_prefix = prefix | ((uint32_t)(4 * tid + j) << shift);
+        *sh_krem = krem - run;
+      }
+      run += hh[j];
+    }
+  }
+  __syncthreads();
+  prefix = *sh_prefix;
+  krem = *sh_krem;
+  bits_left = shift;
+  __syncthreads();
+}
+
+// Grid (segments, units).  Every workgroup pools its segment of the raw scores, stores the
+// pooled scores as keys and adds its 4096-bin histogram to the unit's.  The workgroup that
+// finishes last for a unit carries on alone: threshold bin from the histogram, exact value of
+// the k-th largest key among the keys of that bin, ordered compaction of the unit.
+__global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p) {
+  __shared__ float rawl[kSegLen + 2 * kHaloMax];
+  __shared__ int hist[kBins];
+  __shared__ uint32_t cand[kCandMax];
   __shared__ int wsum[kSelThreads / 64][2];
-  __shared__ uint32_t sh_prefix, sh_min, sh_max;
-  __shared__ int sh_krem;
-  const int u = blockIdx.x, tid = threadIdx.x, lane = lane_id();
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_krem, sh_last, sh_ncand;
+  const int seg = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
   const int lc = p.lc;
   const float *raw = p.scores + (size_t)u * lc;
-  // pooled scores as order-preserving unsigned keys: in LDS when they fit, else in the workspace
-  uint32_t *pooled = vals_in_lds ? sel_lds : reinterpret_cast<uint32_t *>(p.pooled + (size_t)u * lc);
+  uint32_t *pooled = p.pooled + (size_t)u * lc;
+  int *ghist = p.hist + (size_t)u * kBins;
+
+  // ---- every workgroup: pooling and histogram of its segment
+  for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
+  const int a_begin = seg * kSegLen;
+  const int a_end = a_begin + kSegLen < lc ? a_begin + kSegLen : lc;
+  const int r = (p.pool - 1) / 2;
+  const bool in_lds = r <= kHaloMax;
+  const int h_begin = a_begin - r < 0 ? 0 : a_begin - r;
+  const int h_end = a_end + r > lc ? lc : a_end + r;
+  if (in_lds)
+    for (int a = h_begin + tid; a < h_end; a += kSelThreads) rawl[a - h_begin] = raw[a];
+  __syncthreads();
+  for (int a = a_begin + tid; a < a_end; a += kSelThreads) {
+    const int lo = a - r < 0 ? 0 : a - r, hi = a + r >= lc ? lc - 1 : a + r;
+    float mx = -INFINITY;
+    if (in_lds) for (int j = lo; j <= hi; ++j) mx = fmaxf(mx, rawl[j - h_begin]);
+    else for (int j = lo; j <= hi; ++j) mx = fmaxf(mx, raw[j]);
+    const uint32_t x = orderable(mx);
+    store_shared(pooled + a, x);
+    if (p.scores_out) p.scores_out[(size_t)u * lc + a] = mx;
+    const int d = (int)(x >> 20);
+    const int d0 = __builtin_amdgcn_readfirstlane(d);
+    const unsigned long long same = __ballot(d == d0);
+    if (d != d0) atomicAdd(&hist[d], 1);
+    else if (lane == __builtin_ctzll(same)) atomicAdd(&hist[d0], __popcll(same));
+  }
+  __syncthreads();
+  for (int i = tid; i < kBins; i += kSelThreads) {
+    const int v = hist[i];
+    if (v) __hip_atomic_fetch_add(&ghist[i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this thread's keys and counts have arrived
+  __syncthreads();
+  if (tid == 0) sh_last = __hip_atomic_fetch_add(&p.done[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nseg - 1;
+  __syncthreads();
+  if (!sh_last) return;
+
+  // ---- the last workgroup of the unit
   int32_t *kept = p.kept + (size_t)u * p.out_stride;
   int budget = p.budgets ? p.budgets[u] : p.budget;
   if (budget < p.lw) budget = p.lw;
@@ -322,169 +542,115 @@ __global__ __launch_bounds__(kSelThreads) void deep_select(SelectParams p, int v
   if (k > lc) k = lc;
   if (k > p.out_stride - p.lw) k = p.out_stride - p.lw;   // never write past the row pitch
 
-  // 1-D max pooling, window clipped to the context; smallest and largest key of the unit
-  if (tid == 0) { sh_min = 0xFFFFFFFFu; sh_max = 0u; }
-  __syncthreads();
-  const int r = (p.pool - 1) / 2;
-  uint32_t mn = 0xFFFFFFFFu, mx = 0u;
-  if (vals_in_lds) {
-    // raw scores to LDS with independent coalesced loads, pooled in registers, keys back in place
-    constexpr int kPer = kSelInLds / kSelThreads;
-    float *rawl = reinterpret_cast<float *>(sel_lds);
-    float pm[kPer];
+  constexpr int kWaves = kSelThreads / 64;
+  constexpr int kBatch = 32;
+  const int run = (((lc + kWaves - 1) / kWaves) + 63) & ~63;      // positions per wave
+  const int w0 = wave * run, w1 = w0 + run < lc ? w0 + run : lc;
+  const bool one_trip = run <= 64 * kBatch;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  uint32_t x[kBatch];
+  auto load_keys = [&](int b0) {
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {                 // all loads of the thread in flight together
-      const int a = tid + i * kSelThreads;
-      pm[i] = a < lc ? raw[a] : 0.f;
+    for (int i = 0; i < kBatch; ++i) {
+      const int a = b0 + 64 * i + lane;
+      x[i] = a < w1 ? load_shared(pooled + a) : 0u;
     }
+  };
+  uint32_t prefix = 0;                                 // key of the k-th largest pooled score
+  int krem = k;                                        // how many keys equal to it are taken
+  if (k > 0 && k < lc) {
+    if (one_trip) load_keys(w0);
+    // threshold bin: thread t owns bins 4t .. 4t+3, counts from the top
+    {
+      int h[4];
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-      const int a = tid + i * kSelThreads;
-      if (a < lc) rawl[a] = pm[i];
-    }
-    __syncthreads();
+      for (int j = 0; j < 4; ++j) h[j] = (int)load_shared(reinterpret_cast<const uint32_t *>(ghist) + 4 * tid + j);
+      const int mine = h[0] + h[1] + h[2] + h[3];
+      int above = mine;                                // inclusive sum over the higher lanes of the wave
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-      const int a = tid + i * kSelThreads;
-      float m = -INFINITY;
-      if (a < lc) {
-        const int lo = a - r < 0 ? 0 : a - r, hi = a + r >= lc ? lc - 1 : a + r;
-        for (int j = lo; j <= hi; ++j) m = fmaxf(m, rawl[j]);
+      for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_down(above, o);
+        if (lane + o < 64) above += up;
       }
-      pm[i] = m;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-      const int a = tid + i * kSelThreads;
-      if (a < lc) {
-        const uint32_t x = orderable(pm[i]);
-        pooled[a] = x;
-        mn = x < mn ? x : mn;
-        mx = x > mx ? x : mx;
-        if (p.scores_out) p.scores_out[(size_t)u * lc + a] = pm[i];
-      }
-    }
-  } else {
-    for (int a = tid; a < lc; a += kSelThreads) {
-      float m = raw[a];
-      const int lo = a - r < 0 ? 0 : a - r, hi = a + r >= lc ? lc - 1 : a + r;
-      for (int j = lo; j <= hi; ++j) m = fmaxf(m, raw[j]);
-      const uint32_t x = orderable(m);
-      pooled[a] = x;
-      mn = x < mn ? x : mn;
-      mx = x > mx ? x : mx;
-      if (p.scores_out) p.scores_out[(size_t)u * lc + a] = m;
-    }
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const uint32_t a = __shfl_xor(mn, o), b = __shfl_xor(mx, o);
-    mn = a < mn ? a : mn;
-    mx = b > mx ? b : mx;
-  }
-  if (lane == 0) { atomicMin(&sh_min, mn); atomicMax(&sh_max, mx); }
-  __syncthreads();
-
-  // Value of the k-th largest pooled score by most-significant-digit radix select.  The bits
-  // all keys share (scores of one unit have similar exponents) are skipped: they would send
-  // every key to the same counter.
-  uint32_t prefix = sh_max;
-  int krem = k;   // how many still to take among the keys matching `prefix`
-  if (k > 0 && k < lc && sh_min != sh_max) {
-    int bits_left = 32 - __builtin_clz(sh_min ^ sh_max);      // 1 .. 32 low bits still undecided
-    prefix = bits_left == 32 ? 0u : (sh_max >> bits_left) << bits_left;
-    while (bits_left > 0) {
-      const int w = bits_left < 8 ? bits_left : 8, shift = bits_left - w;
-      const uint32_t dmask = (1u << w) - 1u;
-      if (tid < 256) hist[tid] = 0;
+      if (lane == 0) wsum[wave][0] = above;            // total of the wave
       __syncthreads();
-      constexpr int kAtOnce = 4;                        // independent keys per thread and trip
-      for (int a0 = 0; a0 < lc; a0 += kAtOnce * kSelThreads) {
-        uint32_t x[kAtOnce];
+      above -= mine;
+      for (int w2 = wave + 1; w2 < kSelThreads / 64; ++w2) above += wsum[w2][0];
+      int seen = above;
 #pragma unroll
-        for (int q = 0; q < kAtOnce; ++q) {
-          const int a = a0 + q * kSelThreads + tid;
-          x[q] = a < lc ? pooled[a] : 0u;
+      for (int j = 3; j >= 0; --j) {
+        if (seen < k && k <= seen + h[j]) {
+          sh_prefix = (uint32_t)(4 * tid + j) << 20;
+          sh_krem = k - seen;
         }
-#pragma unroll
-        for (int q = 0; q < kAtOnce; ++q) {
-          const int a = a0 + q * kSelThreads + tid;
-          const bool in = a < lc && (bits_left == 32 || (x[q] >> bits_left) == (prefix >> bits_left));
-          const int d = (int)((x[q] >> shift) & dmask);
-          if (in) {
-            // scores of one unit crowd into few digits: the digit of the first lane that takes
-            // part is counted once for all lanes that share it
-            const int d0 = __builtin_amdgcn_readfirstlane(d);
-            const unsigned long long same = __ballot(d == d0);
-            if (d != d0) atomicAdd(&hist[d], 1);
-            else if (lane == __builtin_ctzll(same)) atomicAdd(&hist[d0], __popcll(same));
-          }
-        }
+        seen += h[j];
       }
-      __syncthreads();
-      if (tid < 64) {
-        // lane t owns counters 4t .. 4t+3; find the digit at which the count from the top reaches krem
-        const int h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
-        const int mine = h0 + h1 + h2 + h3;
-        int above = mine;                                     // inclusive sum over lanes >= t
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int x = __shfl_down(above, o);
-          if (tid + o < 64) above += x;
-        }
-        above -= mine;                                        // keys in counters of higher lanes
-        const int hh[4] = {h0, h1, h2, h3};
-        int run = above;
-#pragma unroll
-        for (int j = 3; j >= 0; --j) {
-          if (run < krem && krem <= run + hh[j]) {
-            sh_prefix = prefix | ((uint32_t)(4 * tid + j) << shift);
-            sh_krem = krem - run;
-          }
-          run += hh[j];
-        }
-      }
+      if (tid == 0) sh_ncand = 0;
       __syncthreads();
       prefix = sh_prefix;
       krem = sh_krem;
-      bits_left = shift;
-      __syncthreads();
     }
+    // The unit's keys, dealt to the waves in contiguous runs (the order of the compaction below),
+    // thirty-two 64-position steps per lane and trip, all loads of a trip in flight together.  A
+    // unit of up to 32768 positions is one trip: its keys stay in registers for all three uses.
+    // First use: the keys of the threshold's bin, ranked in LDS when they fit (a few hundred as a
+    // rule), else where they are.
+    for (int b0 = w0; b0 < w1; b0 += 64 * kBatch) {
+      if (!one_trip) load_keys(b0);
+#pragma unroll
+      for (int i = 0; i < kBatch; ++i) {
+        const int a = b0 + 64 * i + lane;
+        const bool in = a < w1 && (x[i] >> 20) == (prefix >> 20);
+        const unsigned long long mk = __ballot(in);
+        if (mk) {                                      // wave-uniform
+          int at = 0;
+          if (lane == __builtin_ctzll(mk)) at = atomicAdd(&sh_ncand, __popcll(mk));
+          at = __shfl(at, __builtin_ctzll(mk)) + __popcll(mk & below);
+          if (in && at < kCandMax) cand[at] = x[i];
+        }
+      }
+    }
+    __syncthreads();
+    const int ncand = sh_ncand;
+    const uint32_t *src = ncand <= kCandMax ? cand : pooled;
+    const int nsrc = ncand <= kCandMax ? ncand : lc;
+    int bits_left = 20;
+    while (bits_left > 0) radix_step(src, nsrc, ncand > kCandMax, prefix, krem, bits_left, hist, &sh_prefix, &sh_krem);
   }
   // ordered compaction: everything above the threshold, then the first `krem` equal to it.
-  // Each wave owns a contiguous run of positions and walks it 64 at a time (coalesced,
-  // conflict-free); ranks within a step come from ballots, the offset of the wave from a
-  // count pass and a scan over the waves.
+  // Ranks within a 64-position step come from ballots, the offset of the wave from a count pass
+  // and a scan over the waves.
   if (k >= lc) {
     for (int a = tid; a < lc; a += kSelThreads) kept[a] = a;
   } else if (k > 0) {
-    constexpr int kWaves = kSelThreads / 64;
-    const int wave = tid >> 6;
-    const int run = (((lc + kWaves - 1) / kWaves) + 63) & ~63;
-    const int w0 = wave * run, w1 = w0 + run < lc ? w0 + run : lc;
-    const unsigned long long below = (1ull << lane) - 1ull;
     int ngt = 0, neq = 0;                              // wave-uniform
-    for (int a0 = w0; a0 < w1; a0 += 64) {
-      const int a = a0 + lane;
-      const uint32_t x = a < w1 ? pooled[a] : 0u;
-      ngt += __popcll(__ballot(a < w1 && x > prefix));
-      neq += __popcll(__ballot(a < w1 && x == prefix));
+    for (int b0 = w0; b0 < w1; b0 += 64 * kBatch) {
+      if (!one_trip) load_keys(b0);
+#pragma unroll
+      for (int i = 0; i < kBatch; ++i) {
+        const int a = b0 + 64 * i + lane;
+        ngt += __popcll(__ballot(a < w1 && x[i] > prefix));
+        neq += __popcll(__ballot(a < w1 && x[i] == prefix));
+      }
     }
+    __syncthreads();                                   // wsum was read above
     if (lane == 0) { wsum[wave][0] = ngt; wsum[wave][1] = neq; }
     __syncthreads();
     int gt_seen = 0, eq_seen = 0;
     for (int w = 0; w < wave; ++w) { gt_seen += wsum[w][0]; eq_seen += wsum[w][1]; }
-    for (int a0 = w0; a0 < w1; a0 += 64) {
-      const int a = a0 + lane;
-      const uint32_t x = a < w1 ? pooled[a] : 0u;
-      const bool gt = a < w1 && x > prefix, eq = a < w1 && x == prefix;
-      const unsigned long long mgt = __ballot(gt), meq = __ballot(eq);
-      const int gt_before = gt_seen + __popcll(mgt & below), eq_before = eq_seen + __popcll(meq & below);
-      if (gt) kept[gt_before + (eq_before < krem ? eq_before : krem)] = a;
-      else if (eq && eq_before < krem) kept[gt_before + eq_before] = a;
-      gt_seen += __popcll(mgt);
-      eq_seen += __popcll(meq);
+    for (int b0 = w0; b0 < w1; b0 += 64 * kBatch) {
+      if (!one_trip) load_keys(b0);
+#pragma unroll
+      for (int i = 0; i < kBatch; ++i) {
+        const int a = b0 + 64 * i + lane;
+        const bool gt = a < w1 && x[i] > prefix, eq = a < w1 && x[i] == prefix;
+        const unsigned long long mgt = __ballot(gt), meq = __ballot(eq);
+        const int gt_before = gt_seen + __popcll(mgt & below), eq_before = eq_seen + __popcll(meq & below);
+        if (gt) kept[gt_before + (eq_before < krem ? eq_before : krem)] = a;
+        else if (eq && eq_before < krem) kept[gt_before + eq_before] = a;
+        gt_seen += __popcll(mgt);
+        eq_seen += __popcll(meq);
+      }
     }
   }
   for (int b = tid; b < p.lw; b += kSelThreads) kept[k + b] = lc + b;
@@ -522,19 +688,28 @@ __global__ __launch_bounds__(256) void deep_gather(GatherParams p) {
 // ---------------------------------------------------------------- host side
 struct DeepLayout {
   float2 *partial;
-  float *scores, *pooled;
+  float *scores;
+  uint32_t *pooled;
+  int *hist, *done;
+  int stages, nchunks;
   size_t bytes;
 };
 
-DeepLayout deep_layout(void *ws, int U, int l, int lw, int Rpad) {
+int stage_keys_of(int dtype) { return dtype == SPINDLE_F32 ? Geo<SPINDLE_F32>::kStageKeys : Geo<SPINDLE_F16>::kStageKeys; }
+static_assert(Geo<SPINDLE_F16>::kStageKeys == Geo<SPINDLE_BF16>::kStageKeys, "one stage size for the 16-bit types");
+
+DeepLayout deep_layout(void *ws, int U, int l, int lw, int Rpad, int dtype) {
   Carver cv(ws);
   DeepLayout L;
-  const int keys = stages_per_block(U, l) * kStageKeys;
-  const int nchunks = (l + keys - 1) / keys;
+  const int sk = stage_keys_of(dtype);
+  L.stages = stages_per_block(U, l, sk);
+  L.nchunks = (l + L.stages * sk - 1) / (L.stages * sk);
   const int lc = l - lw;
-  L.partial = cv.take<float2>((size_t)U * nchunks * Rpad);
+  L.partial = cv.take<float2>((size_t)U * L.nchunks * Rpad);
   L.scores = cv.take<float>((size_t)U * (lc > 0 ? lc : 1));
-  L.pooled = cv.take<float>((size_t)U * (lc > 0 ? lc : 1));
+  L.pooled = cv.take<uint32_t>((size_t)U * (lc > 0 ? lc : 1));
+  L.hist = cv.take<int>((size_t)U * kBins);
+  L.done = cv.take<int>((size_t)U);
   L.bytes = cv.total();
   return L;
 }
@@ -543,18 +718,18 @@ int padded_rows(int R) { return R <= 64 ? 64 : (R <= 128 ? 128 : 256); }
 
 template <int DT, int WR>
 spindle_status launch_passes(const DeepParams &p, int U, hipStream_t st) {
-  typedef Stage<DT> S;
-  const size_t smem_stats = 2 * (size_t)S::kBytes > 65536 ? 2 * (size_t)S::kBytes : 65536;
-  const size_t smem_acc = 2 * (size_t)S::kBytes + 2 * 2 * WR * kStageKeys * sizeof(float);
-  static LdsLimit lim_stats, lim_acc;                     // one pair per instantiation; the sizes are constants of it
-  if (spindle_status e = allow_lds(lim_stats, reinterpret_cast<const void *>(&deep_pass<DT, WR, false>), smem_stats)) return e;
-  if (spindle_status e = allow_lds(lim_acc, reinterpret_cast<const void *>(&deep_pass<DT, WR, true>), smem_acc)) return e;
+  typedef Geo<DT> S;
+  const size_t smem_stats = 2 * (size_t)S::kStageBytes;
+  const size_t smem_acc = 2 * (size_t)S::kStageBytes + (2 * WR * S::kStageKeys + 256) * sizeof(float);
+  static LdsLimit lim_stats, lim_acc;                  // one pair per instantiation; the sizes are constants of it
+  if (spindle_status e = allow_lds(lim_stats, reinterpret_cast<const void *>(&deep_stats<DT, WR>), smem_stats)) return e;
+  if (spindle_status e = allow_lds(lim_acc, reinterpret_cast<const void *>(&deep_accumulate<DT, WR>), smem_acc)) return e;
   { ProfScope ps("deep_stats", st);
-  hipLaunchKernelGGL((deep_pass<DT, WR, false>), dim3(p.nchunks, U), dim3(kDeepThreads), smem_stats, st, p); }
+  hipLaunchKernelGGL((deep_stats<DT, WR>), dim3(p.nchunks, U), dim3(S::kThreads), smem_stats, st, p); }
   if (p.lc > 0) {
-    const int nacc = (p.lc + p.stages * kStageKeys - 1) / (p.stages * kStageKeys);
+    const int per = p.stages * S::kStageKeys;
     ProfScope ps("deep_accumulate", st);
-    hipLaunchKernelGGL((deep_pass<DT, WR, true>), dim3(nacc, U), dim3(kDeepThreads), smem_acc, st, p);
+    hipLaunchKernelGGL((deep_accumulate<DT, WR>), dim3((p.lc + per - 1) / per, U), dim3(S::kThreads), smem_acc, st, p);
   }
   SPINDLE_HIP(hipGetLastError());
   return SPINDLE_OK;
@@ -581,7 +756,7 @@ extern "C" spindle_status spindle_deep_workspace_bytes(const spindle_kv_desc *de
   if (desc->group_size < 1 || (int64_t)window * desc->group_size > 256)
     SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "window * group_size must be in [1, 256]");
   const int U = desc->batch * desc->n_kv_heads;
-  *bytes = deep_layout(nullptr, U, desc->seq_len, window, padded_rows(window * desc->group_size)).bytes;
+  *bytes = deep_layout(nullptr, U, desc->seq_len, window, padded_rows(window * desc->group_size), desc->dtype).bytes;
   return SPINDLE_OK;
 }
 
@@ -614,7 +789,7 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int U = desc->batch * desc->n_kv_heads;
   const int R = lw * desc->group_size, Rpad = padded_rows(R);
-  DeepLayout L = deep_layout(workspace, U, l, lw, Rpad);
+  DeepLayout L = deep_layout(workspace, U, l, lw, Rpad, desc->dtype);
 
   DeepParams p;
   KvLayout lay;
@@ -625,9 +800,11 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
   p.Q = static_cast<const char *>(Qw);
   p.partial = L.partial;
   p.scores = L.scores;
+  p.hist = L.hist;
+  p.done = L.done;
   p.l = l; p.lc = lc; p.lw = lw; p.hn = desc->group_size; p.R = R; p.Rpad = Rpad;
-  p.stages = stages_per_block(U, l);
-  p.nchunks = (l + p.stages * kStageKeys - 1) / (p.stages * kStageKeys);
+  p.stages = L.stages;
+  p.nchunks = L.nchunks;
   p.sc2 = scale * kLog2e;
   p.inv_hn = 1.0f / (float)desc->group_size;
   p.norm = norm;
@@ -638,15 +815,13 @@ extern "C" spindle_status spindle_compress_deep(const spindle_kv_desc *desc, con
 
   SelectParams sp;
   sp.scores = L.scores; sp.pooled = L.pooled; sp.scores_out = scores_out;
+  sp.hist = L.hist; sp.done = L.done;
   sp.budgets = budgets; sp.kept = kept_idx;
   sp.l = l; sp.lc = lc; sp.lw = lw; sp.pool = pool_kernel; sp.budget = budget; sp.out_stride = out_stride;
+  sp.nseg = lc > 0 ? (lc + kSegLen - 1) / kSegLen : 1;
   {
-    const int vals_in_lds = lc <= kSelInLds;
-    const size_t sel_lds = vals_in_lds ? (size_t)lc * sizeof(uint32_t) : 0;
-    static LdsLimit lim_select;
-    if (spindle_status e = allow_lds(lim_select, reinterpret_cast<const void *>(&deep_select), kSelInLds * sizeof(uint32_t))) return e;
     ProfScope ps("deep_select", st);
-    hipLaunchKernelGGL(deep_select, dim3(U), dim3(kSelThreads), sel_lds, st, sp, vals_in_lds);
+    hipLaunchKernelGGL(deep_select, dim3(sp.nseg, U), dim3(kSelThreads), 0, st, sp);
   }
 
   GatherParams gp;

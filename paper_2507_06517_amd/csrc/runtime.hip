@@ -1,4 +1,5 @@
 // Error reporting, descriptor validation and version of the C ABI.
+#include <math.h>
 #include <stdarg.h>
 #include <string.h>
 
@@ -138,10 +139,11 @@ extern "C" spindle_status spindle_layer_budgets(double reserve_ratio, int32_t se
     last = beta;
   }
   for (int layer = 0; layer < n_layers; ++layer) {
-    const double t = n_layers > 1 ? (double)layer / (double)(n_layers - 1) : 0.0;
-    const double share = n_layers > 1 ? first + (last - first) * t : mean;
+    // Eq. 6 in the printed order of operations (slope per layer, times the layer), so that the
+    // integer of Eq. 7 below is the one any evaluation of the printed formulas in doubles gives
+    const double share = n_layers > 1 ? first + (last - first) / (double)(n_layers - 1) * layer : mean;
     if (ratios) ratios[layer] = share;
-    long kept = (long)(share * context + 0.5);
+    long kept = (long)floor(share * (double)context);         // Eq. 7: k = floor(r_c(layer) l_c)
     kept = kept < 0 ? 0 : (kept > context ? context : kept);
     budgets[layer] = window + (int32_t)kept;
   }
@@ -150,15 +152,18 @@ extern "C" spindle_status spindle_layer_budgets(double reserve_ratio, int32_t se
 
 // Reserve ratio of a layer, Eq. 15 (Sec. "Experiments").
 extern "C" spindle_status spindle_reserve_ratio(int64_t kept_tokens, int64_t total_tokens, int64_t codebook_entries,
-                                                int32_t head_dim, int32_t index_bits, int32_t elem_bits, double *out) {
+                                                int32_t head_dim, int32_t index_bits, int32_t elem_bits,
+                                                int32_t magnitude_bits, double *out) {
   if (!out) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "out is NULL");
-  if (kept_tokens < 1 || total_tokens < 1 || codebook_entries < 1 || head_dim < 1 || index_bits < 1 || elem_bits < 1)
+  if (kept_tokens < 1 || total_tokens < 1 || codebook_entries < 1 || head_dim < 1 || index_bits < 1 || elem_bits < 1 ||
+      magnitude_bits < 1)
     SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "counts and widths must be >= 1");
   if (kept_tokens > total_tokens || codebook_entries > kept_tokens)
     SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "need codebook_entries <= kept_tokens <= total_tokens");
   out[0] = (double)kept_tokens / (double)total_tokens;
   out[1] = (double)codebook_entries / (double)kept_tokens;
-  out[2] = ((double)head_dim + (double)index_bits / (double)elem_bits + 1.0) / (double)head_dim;
+  out[2] = ((double)head_dim + (double)index_bits / (double)elem_bits + (double)magnitude_bits / (double)elem_bits) /
+           (double)head_dim;
   out[3] = out[0] * out[1] * out[2];
   return SPINDLE_OK;
 }

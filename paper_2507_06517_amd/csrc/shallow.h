@@ -171,18 +171,6 @@ constexpr int kListCap = 256;
 // out to the lanes in turn and a short row occupies all eight lanes instead of the first one.
 __host__ __device__ constexpr int list_slot(int p) { return (p & ~127) | ((p & 7) << 4) | ((p & 127) >> 3); }
 
-// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at
-// lds_addr + 16 i (lds_addr wave-uniform).  Issued as assembly on purpose: the compiler
-// would put a wait for the load in front of every later LDS read of the kernel, since it
-// cannot tell which of them touch the destination.  Completion is the caller's business
-// (s_waitcnt vmcnt + barrier before any lane reads the destination).
-__device__ __forceinline__ void lds_dma16(const void *src, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :
-               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(src)
-               : "memory", "m0");
-}
-
 // Entries per cut token and lane group that shallow_assign hands to the exact comparison.
 constexpr int kCandCap = 8;
 

@@ -122,11 +122,12 @@ def check_codebook_vectors(C_gpu_bits, C64, dtype):
     assert np.all(err <= tol), f"codebook entry off by {err.max()}"
 
 
-def check_shallow_unit(orc, X64, theta, cap, dtype, g, t, b, h, full_adj=True):
-    """Compare unit (b, h) of tensor t ('k'|'v') of the GPU result g with the oracle."""
-    o = orc.shallow_unit(X64, float(np.float32(theta)), cap)
-    n = X64.shape[0]
-    if full_adj and f"adj_{t}" in g:
+def check_shallow_unit(orc, X64, theta, cap, dtype, g, t, b, h, full_adj=True, o=None):
+    """Compare unit (b, h) of tensor t ('k'|'v') of the GPU result g with the oracle (o: the
+    oracle's result for this problem and cap if the caller already has it)."""
+    if o is None:
+        o = orc.shallow_unit(X64, float(np.float32(theta)), cap)
+    if full_adj and f"adj_{t}" in g and "G" in o:
         assert np.array_equal(g[f"adj_{t}"][b, h], o["G"]), "adjacency bits differ"
         assert np.array_equal(g[f"deg_{t}"][b, h], o["deg"]), "degrees differ"
     assert g[f"n_found_{t}"][b, h] == o["n_codes_uncapped"]
@@ -139,7 +140,9 @@ def check_shallow_unit(orc, X64, theta, cap, dtype, g, t, b, h, full_adj=True):
     return o
 
 
-def check_shallow_layer(orc, L: wl.Layer, cap=None, units=None, tensors=("k", "v"), g=None, debug=True):
+def check_shallow_layer(orc, L: wl.Layer, cap=None, units=None, tensors=("k", "v"), g=None, debug=True, cache=None):
+    """cache: a dict that keeps the oracle's results of this layer and cap between calls (tests that
+    run the same layer through several launch configurations compute them once)."""
     cap = cap or L.max_codes
     if g is None:
         g = gpu_shallow(L, cap, debug=debug, tensors=tensors)
@@ -151,10 +154,38 @@ def check_shallow_layer(orc, L: wl.Layer, cap=None, units=None, tensors=("k", "v
     def run(job):
         t, b, h = job
         X = wl.to_f64((L.K if t == "k" else L.V)[b, h], L.dtype)
-        return check_shallow_unit(orc, X, L.theta_k if t == "k" else L.theta_v, cap, L.dtype, g, t, b, h)
+        o = cache.get((t, b, h, cap)) if cache is not None else None
+        o = check_shallow_unit(orc, X, L.theta_k if t == "k" else L.theta_v, cap, L.dtype, g, t, b, h, o=o)
+        if cache is not None:
+            o.pop("G", None)                         # 128 MiB per problem at l = 32768
+            cache[(t, b, h, cap)] = o
+        return o
 
     with ThreadPoolExecutor(max_workers=16) as ex:
         return list(ex.map(run, jobs)), g
+
+
+def check_shallow_layer_caps(orc, L: wl.Layer, gs: dict, units=None, tensors=("k", "v")):
+    """gs: {cap: gpu_shallow result of L under that cap}.  Every listed (batch, head) problem of K
+    and V is compared with the oracle under every cap; the oracle builds the graph of a problem
+    once and applies each cap to it.  Returns the oracle results, [(t, b, h, {cap: dict})]."""
+    B, H, l, d = L.K.shape
+    todo = units if units is not None else [(b, h) for b in range(B) for h in range(H)]
+    from concurrent.futures import ThreadPoolExecutor
+    jobs = [(t, b, h) for t in tensors for (b, h) in todo]
+
+    def run(job):
+        t, b, h = job
+        X = wl.to_f64((L.K if t == "k" else L.V)[b, h], L.dtype)
+        theta = L.theta_k if t == "k" else L.theta_v
+        os_ = orc.shallow_unit_caps(X, float(np.float32(theta)), sorted(gs))
+        for cap, o in os_.items():
+            check_shallow_unit(orc, X, theta, cap, L.dtype, gs[cap], t, b, h, o=o)
+            o.pop("C")
+        return (t, b, h, os_)
+
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        return list(ex.map(run, jobs))
 
 
 # ------------------------------------------------------------------ both paths on two streams

@@ -10,20 +10,30 @@ import parity
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 
-def test_config3_stack(oracle):
-    # 32-layer stack at l = 8192: layers 0-7 codebook (cap 512), layers 8-31 eviction with
-    # the tapering budget.  Every layer goes through the library; the oracle checks a spread
-    # of layers in full (all units) to bound the host time.
-    for layer in (0, 7):
+@pytest.mark.parametrize("layers", [range(0, 4), range(4, 8)], ids=["0-3", "4-7"])
+def test_config3_codebook_layers(oracle, layers):
+    # 32-layer stack at l = 8192, layers 0-7: codebook replacement with cap 512.  Every layer goes
+    # through the library and every one of its 16 problems is compared with the oracle.
+    for layer in layers:
         L = wl.config3_layer(layer)
-        res, g = parity.check_shallow_layer(oracle, L)
-        print("config3 layer", layer, "codes", [o["n_codes_uncapped"] for o in res][:4], flush=True)
+        assert L.max_codes == 512
+        res, g = parity.check_shallow_layer(oracle, L, debug=layer in (0, 7))
+        assert len(res) == 16
+        print("config3 codebook layer", layer, [o["n_codes_uncapped"] for o in res][:4], flush=True)
+
+
+@pytest.mark.parametrize("layers", [range(8, 16), range(16, 24), range(24, 32)], ids=["8-15", "16-23", "24-31"])
+def test_config3_eviction_layers(oracle, layers):
+    # layers 8-31: eviction with the budget tapering from 2048 to 256; all 8 units of every layer
+    assert wl.config3_budget(8) == 2048 and wl.config3_budget(31) == 256
     rep = {}
-    for layer in (8, 15, 23, 31):
+    for layer in layers:
         L = wl.config3_layer(layer)
         assert L.budget == wl.config3_budget(layer)
-        rep[layer] = parity.check_deep_layer(oracle, L)
-    print("config3 deep", rep, flush=True)
+        r = parity.check_deep_layer(oracle, L)
+        if r:
+            rep[layer] = r
+    print("config3 eviction layers", list(layers), "selections inside the ambiguity band:", rep, flush=True)
 
 
 def test_config3_stack_folded_into_batch(oracle):
@@ -40,6 +50,11 @@ def test_config3_stack_folded_into_batch(oracle):
             parity.check_deep_unit(p64[0, h], k64[0, h], sc[j, h], kept[j, h], 32, 2048, {})
 
 
+# the oracle's codebook results of the config-4 layer, shared by the tests that run it through
+# different launch configurations (one computation of the 16 problems instead of three)
+CONFIG4_ORACLE = {}
+
+
 def test_config4_deep(oracle):
     rep = parity.check_deep_layer(oracle, wl.config4(0))
     print("config4 deep", rep, flush=True)
@@ -48,7 +63,7 @@ def test_config4_deep(oracle):
 def test_config4_shallow(oracle):
     L = wl.config4(0)
     g = parity.gpu_shallow(L, debug=False)
-    res, _ = parity.check_shallow_layer(oracle, L, g=g)
+    res, _ = parity.check_shallow_layer(oracle, L, g=g, cache=CONFIG4_ORACLE)
     print("config4 codes", [o["n_codes_uncapped"] for o in res], flush=True)
 
 
@@ -58,7 +73,7 @@ def test_config4_two_streams(oracle):
     L = wl.config4(0)
     got, g = parity.gpu_layer_two_streams(L)
     rep = parity.check_deep_layer(oracle, L, got=got)
-    res, _ = parity.check_shallow_layer(oracle, L, g=g)
+    res, _ = parity.check_shallow_layer(oracle, L, g=g, cache=CONFIG4_ORACLE)
     print("config4 on two streams", rep, [o["n_codes_uncapped"] for o in res][:4], flush=True)
 
 
@@ -68,7 +83,7 @@ def test_config4_pipelined(oracle):
     L = wl.config4(0)
     (got0, g0), *others = parity.gpu_layers_pipelined(L, steps=10, depth=3)
     rep = parity.check_deep_layer(oracle, L, got=got0)
-    res, _ = parity.check_shallow_layer(oracle, L, g=g0)
+    res, _ = parity.check_shallow_layer(oracle, L, g=g0, cache=CONFIG4_ORACLE)
     assert len(others) == 2
     for got1, g1 in others:
         for a, b in zip(got0, got1):
@@ -93,22 +108,55 @@ def test_config4_adjacency_rows(oracle):
             assert g["deg_k"][0, h, a] == sum(bin(int(w)).count("1") for w in row)
 
 
-@pytest.mark.parametrize("budget", [512, 4096])
-def test_config5_layer(oracle, budget):
-    # batch 4 x 32768, bf16, half clustered / half noise: the codebook overflows its cap by
-    # far.  The whole layer runs on the GPU; the oracle checks the eviction path on every
-    # unit and the codebook path on one (batch, head) unit of K and one of V.
-    L = wl.config5_layer(0, budget)
-    rep = parity.check_deep_layer(oracle, L)
-    print("config5 deep", budget, rep, flush=True)
-    g = parity.gpu_shallow(L, debug=False)
-    res, _ = parity.check_shallow_layer(oracle, L, units=[(1, 2)], g=g)
-    assert all(o["n_codes_uncapped"] > budget for o in res)
-    # invariants on every unit
-    for t in ("k", "v"):
-        assert (g[f"n_codes_{t}"] == budget).all()
-        assert g[f"ref_{t}"].min() >= 0 and g[f"ref_{t}"].max() < budget
-    print("config5 codes found", [o["n_codes_uncapped"] for o in res], flush=True)
+CONFIG5_CAPS = (512, 4096)
+
+
+@pytest.fixture(scope="module")
+def config5_on_gpu():
+    """Layer -> ({cap: Layer}, {cap: library result of the codebook path}) of the batch-4 bf16
+    stack, both caps of the sweep; one layer is held at a time."""
+    held = {}
+
+    def get(layer):
+        if layer not in held:
+            held.clear()
+            Ls = {c: wl.config5_layer(layer, c) for c in CONFIG5_CAPS}
+            L = Ls[CONFIG5_CAPS[0]]
+            assert all(np.array_equal(Ls[c].K, L.K) and np.array_equal(Ls[c].V, L.V) for c in CONFIG5_CAPS)
+            gs = {c: parity.gpu_shallow(Ls[c], debug=False) for c in CONFIG5_CAPS}
+            for c in CONFIG5_CAPS:                     # invariants on every unit
+                for t in ("k", "v"):
+                    assert (gs[c][f"n_codes_{t}"] == c).all()
+                    assert gs[c][f"ref_{t}"].min() >= 0 and gs[c][f"ref_{t}"].max() < c
+            held[layer] = (Ls, gs)
+        return held[layer]
+
+    yield get
+    held.clear()
+
+
+@pytest.mark.parametrize("layer,part", [(0, "eviction"), (0, 0), (0, 1), (0, 2), (0, 3), (31, "eviction"), (31, "spread")])
+def test_config5_layer(oracle, config5_on_gpu, layer, part):
+    # batch 4 x 32768, bf16, pool 15, half of the tokens isolated noise; budgets and caps 512 and
+    # 4096.  The whole layer runs on the GPU under both.
+    # "eviction": every unit of the layer under both budgets.
+    # Codebook path: every problem overflows both caps by far (some 12 k tokens lose their entry
+    # and go through the cap step); the oracle builds the graph of a problem once and applies
+    # both caps to it.  Layer 0: every (batch, head) problem of K and V, the 16 problems of one
+    # batch entry per test case (one per host core); layer 31: one head of each batch entry.
+    Ls, gs = config5_on_gpu(layer)
+    if part == "eviction":
+        for c in CONFIG5_CAPS:
+            rep = parity.check_deep_layer(oracle, Ls[c])
+            print("config5 layer", layer, "eviction, budget", c, rep, flush=True)
+        return
+    units = [(part, h) for h in range(8)] if part != "spread" else [(0, 5), (1, 2), (2, 7), (3, 0)]
+    res = parity.check_shallow_layer_caps(oracle, Ls[CONFIG5_CAPS[0]], gs, units=units)
+    assert len(res) == 2 * len(units)
+    found = [o[CONFIG5_CAPS[0]]["n_codes_uncapped"] for (_, _, _, o) in res]
+    assert min(found) > CONFIG5_CAPS[1], "every problem is meant to overflow both caps"
+    print("config5 layer", layer, part, "codebook problems checked:", len(res), "entries found",
+          min(found), "-", max(found), flush=True)
 
 
 def test_max_seq_len_codebook(oracle):
@@ -169,8 +217,9 @@ def test_eviction_then_codebook_on_the_kept_tokens(oracle):
     # Eq. 15 for this layer from the counts of both stages
     from paper_2507_06517_amd import binding as sb
     stored = int(g["n_codes_k"].sum() + g["n_codes_v"].sum())
-    r1, r2, r3, r = sb.spindle_reserve_ratio(2 * H * L.budget, 2 * H * l, stored, d, 16, 16)
-    assert r1 == L.budget / l and 0 < r2 <= 256 / L.budget and abs(r - r1 * r2 * (d + 2) / d) < 1e-15
+    r1, r2, r3, r = sb.spindle_reserve_ratio(2 * H * L.budget, 2 * H * l, stored, d, 16, 16, 32)
+    assert r1 == L.budget / l and 0 < r2 <= 256 / L.budget and abs(r - r1 * r2 * (d + 3) / d) < 1e-15
+    assert np.array_equal(np.array([r1, r2, r3, r]), oracle.reserve_ratio(2 * H * L.budget, 2 * H * l, stored, d, 16, 16, 32))
 
 
 def test_unfolded_gqa_then_one_codebook_per_kv_head(oracle):

@@ -173,22 +173,54 @@ def test_config2(oracle):
     print("config2 codes", [o["n_codes_uncapped"] for o in res])
 
 
-def test_reconstruct(oracle):
+@pytest.mark.parametrize("dtype,l,cap", [("f16", 500, 500), ("f16", 777, 60), ("bf16", 1301, 2000), ("bf16", 333, 25),
+                                         ("f32", 513, 600), ("f32", 1000, 48)])
+def test_reconstruct(oracle, dtype, l, cap):
+    # Eq. 14 on the library's own codebook, references and magnitudes against the oracle's
+    # reconstruction from its own: ragged lengths, with and without references moved by the cap.
+    # Tolerance: max(1e-3, one unit in the last place of the storage type) relative per element
+    # (two roundings to the storage type, each half a unit: the stored entry and the product),
+    # plus the spacing of the type's subnormals times the magnitude for components near zero.
     import torch
     from paper_2507_06517_amd import binding as sb
-    L = wl.small_random(11, "f16", B=1, H=2, l=500, lw=1, cap=500)
-    K = sb.to_device(L.K, "f16")
-    out = sb.compress_shallow(K, None, "f16", L.theta_k, L.theta_v, 500)
-    R = sb.reconstruct(out["C_k"], out["ref_k"], out["mag_k"], "f16")
+    L = wl.small_random(11 + l, dtype, B=1, H=2, l=l, lw=1, cap=cap, n_centroids=40, noise_frac=0.2)
+    K, V = sb.to_device(L.K, dtype), sb.to_device(L.V, dtype)
+    out = sb.compress_shallow(K, V, dtype, L.theta_k, L.theta_v, cap)
+    Rk = sb.reconstruct(out["C_k"], out["ref_k"], out["mag_k"], dtype)
+    Rv = sb.reconstruct(out["C_v"], out["ref_v"], out["mag_v"], dtype)
     torch.cuda.synchronize()
-    R = R.cpu().numpy().astype(np.float64)
-    for h in range(2):
-        X = wl.to_f64(L.K[0, h], "f16")
-        o = oracle.shallow_unit(X, float(np.float32(L.theta_k)), 500)
-        want = oracle.reconstruct(o["C"], o["ref"], o["mag"])
-        np.testing.assert_allclose(R[0, h], want, rtol=2e-3, atol=1e-3)
-        c = np.einsum("ad,ad->a", R[0, h], X) / (np.linalg.norm(R[0, h], axis=1) * np.linalg.norm(X, axis=1))
-        assert np.all(c > L.theta_k - 1e-3)
+    rel = max(parity.RTOL, parity.ULP[dtype])
+    tiny = {"f16": 2.0 ** -24, "bf16": 2.0 ** -126, "f32": 2.0 ** -126}[dtype]
+    capped = 0
+    for R, src, theta in ((Rk, L.K, L.theta_k), (Rv, L.V, L.theta_v)):
+        Rh = wl.to_f64(sb.to_host_bits(R, dtype), dtype)
+        for h in range(2):
+            X = wl.to_f64(src[0, h], dtype)
+            o = oracle.shallow_unit(X, float(np.float32(theta)), cap)
+            capped += o["n_codes_uncapped"] > cap
+            want = oracle.reconstruct(o["C"], o["ref"], o["mag"])
+            err = np.abs(Rh[0, h] - want)
+            assert np.all(err <= np.abs(want) * rel + tiny * np.maximum(o["mag"], 1.0)[:, None]), err.max()
+            # every row has its token's magnitude, and its direction is that of the token's entry
+            nr = np.linalg.norm(Rh[0, h], axis=1)
+            assert np.allclose(nr, o["mag"], rtol=2 * rel, atol=1e-30)
+            if o["n_codes_uncapped"] <= cap:          # Alg. 1's guarantee holds when nothing was cut
+                c = np.einsum("ad,ad->a", Rh[0, h], X) / np.maximum(nr * o["mag"], 1e-300)
+                assert np.all(c[o["mag"] > 0] > theta - 2 * rel)
+    assert (capped > 0) == (cap < 100), "the small caps are meant to cut entries, the large ones not"
+
+
+def test_reconstruct_ignores_rows_without_an_entry():
+    # references outside [0, max_codes) (what a full table leaves at decode time: -1) give zero rows
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    Cb = torch.randn((1, 1, 4, 128), device="cuda").half()
+    ref = torch.tensor([[[0, -1, 3, 4, 2]]], dtype=torch.int32, device="cuda")
+    mag = torch.tensor([[[2.0, 3.0, 0.5, 1.0, 0.0]]], dtype=torch.float32, device="cuda")
+    R = sb.reconstruct(Cb, ref, mag, "f16")
+    torch.cuda.synchronize()
+    assert torch.equal(R[0, 0, 0], (Cb[0, 0, 0].float() * 2.0).half()) and torch.equal(R[0, 0, 2], (Cb[0, 0, 3].float() * 0.5).half())
+    assert not R[0, 0, 1].any() and not R[0, 0, 3].any() and not R[0, 0, 4].any()
 
 
 def test_deterministic_across_runs():

@@ -160,3 +160,28 @@ def test_layer_ratio_pins(oracle):
     assert abs(out[0] - 1.0) < 1e-12 and abs(out[-1] - beta) < 1e-12
     just_above = oracle.layer_ratios(((alpha + 1e-9) * lc + lw) / l, l, lw, m, beta)
     assert abs(just_above[0] - 1.0) < 1e-6 and abs(just_above[-1] - beta) < 1e-6
+
+
+def test_layer_budget_pins(oracle):
+    # Eq. 7 by hand: l_c = 1000, window 32, three layers, r_c = 0.3007 (between beta and alpha):
+    # r_c(0) = 2 r_c - beta = 0.5514, r_c(2) = beta = 0.05, r_c(1) = their mean 0.3007
+    # -> k = floor(551.4), floor(300.7), floor(50.0 +- an ulp); the window is added to each
+    l, lw, m, beta = 1032, 32, 3, 0.05
+    r = (0.3007 * 1000 + lw) / l
+    b = oracle.layer_budgets(r, l, lw, m, beta)
+    assert b[0] == 32 + 551 and b[1] == 32 + 300 and b[2] in (32 + 49, 32 + 50)
+    # above alpha: r_c = 0.8004 -> r_c(0) = 1, r_c(2) = 0.6008, r_c(1) = 0.8004 -> 1000, 800, 600
+    b = oracle.layer_budgets((0.8004 * 1000 + lw) / l, l, lw, m, beta)
+    assert b[0] in (32 + 999, 32 + 1000) and b[1] == 32 + 800 and b[2] == 32 + 600
+    # r = 1 keeps everything in every layer; one layer gets the mean
+    assert np.array_equal(oracle.layer_budgets(1.0, 5000, 64, 7, beta), np.full(7, 5000))
+    assert oracle.layer_budgets((0.25 * 900 + 100.5) / 1000, 1000, 100, 1, beta)[0] == 100 + 225
+    # beta = 0: the last layer keeps the window alone, never less (the printed Eq. 6 in doubles
+    # ends an ulp below zero for these arguments)
+    b = oracle.layer_budgets(0.33344103305169476, 52801, 92, 19, 0.0)
+    assert b[-1] == 92 and b.min() == 92
+    # floor never exceeds the share: the budgets sum to at most the requested total
+    for rc in (0.07, 0.31, 0.77):
+        b = oracle.layer_budgets((rc * 8160 + 32) / 8192, 8192, 32, 32, beta)
+        want = 32 * (rc * 8160 + 32)
+        assert want - 32 - 1e-6 <= b.sum() <= want + 1e-6

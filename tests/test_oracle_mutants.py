@@ -15,6 +15,7 @@ DEEP = ["tests/test_oracle_deep.py"]
 SHALLOW = ["tests/test_oracle_shallow.py"]
 DECODE = ["tests/test_oracle_decode.py"]
 HELPERS = ["tests/test_oracle_deep.py::test_layer_ratio_pins", "tests/test_host_helpers.py"]
+BUDGETS = ["tests/test_oracle_deep.py::test_layer_budget_pins"]       # the oracle's own pin, not the comparison with the library
 
 # (name, text in the source, what it becomes, which occurrence, pin files)
 MUTANTS = [
@@ -64,8 +65,16 @@ MUTANTS = [
     ("budget_first_case_without_beta", "r0 = 2.0 * rc - beta; r1 = beta;", "r0 = 2.0 * rc; r1 = beta;", 0, HELPERS),
     ("r1_inverted", "out[0] = kept / total;", "out[0] = total / kept;", 0, HELPERS),
     ("alpha_without_the_half", "double alpha = 0.5 * (1.0 + beta);", "double alpha = 1.0 + beta;", 0, HELPERS),
-    ("r3_without_the_magnitude", "out[2] = (dh + (double)int_bit / key_bit + 1.0) / dh;",
+    ("r3_without_the_magnitude", "out[2] = (dh + (double)int_bit / key_bit + (double)mag_bit / key_bit) / dh;",
      "out[2] = (dh + (double)int_bit / key_bit) / dh;", 0, HELPERS),
+    ("r3_magnitude_always_one_element", "out[2] = (dh + (double)int_bit / key_bit + (double)mag_bit / key_bit) / dh;",
+     "out[2] = (dh + (double)int_bit / key_bit + 1.0) / dh;", 0, HELPERS),
+    ("budget_rounded_to_nearest", "int k = (int)floor(rc[lam] * (double)(l - lw));",
+     "int k = (int)floor(rc[lam] * (double)(l - lw) + 0.5);", 0, BUDGETS),
+    ("budget_without_the_window", "budgets_out[lam] = lw + k;", "budgets_out[lam] = k;", 0, BUDGETS),
+    ("budget_of_the_whole_length", "int k = (int)floor(rc[lam] * (double)(l - lw));",
+     "int k = (int)floor(rc[lam] * (double)l);", 0, BUDGETS),
+    ("budget_not_kept_at_zero", "if (k < 0) k = 0;", "", 0, BUDGETS),
 ]
 
 
