@@ -109,8 +109,8 @@ constexpr int kPairBuf = 256;   // queued pairs per wave before a flush
 constexpr int kWordList = 384;  // listed pieces per wave before they are turned into records
 
 // Moves a wave's queued pairs to the global list of its ut.  When that list is full the
-// pairs are dropped and a flag is raised: shallow_gram<true> then decides every close
-// pair of every tile in place (slow, but only for inputs with an extreme number of
+// pairs are dropped and need_full is raised: the fallback variant of shallow_gram then decides
+// every close pair of every tile in place (slow, but only for inputs with an extreme number of
 // similarities within the guard band of theta).
 __device__ __forceinline__ void flush_pairs(const ShallowParams &p, int ut, const uint32_t *buf, int count) {
   const int lane = lane_id();
@@ -118,7 +118,10 @@ __device__ __forceinline__ void flush_pairs(const ShallowParams &p, int ut, cons
   if (lane == 0) base = atomicAdd(p.fix_count + ut, (unsigned)count);
   base = __shfl(base, 0);
   uint32_t *list = p.fix + (size_t)ut * p.fix_cap;
-  if (base + (unsigned)count > p.fix_cap && lane == 0) atomicExch(p.fix_overflow, 1u);
+  if (base + (unsigned)count > p.fix_cap && lane == 0) {
+    atomicExch(p.fix_overflow, 1u);
+    atomicOr(p.need_full, 1u);                         // the fallback pass decides every close pair in place
+  }
   for (int i = lane; i < count; i += kWave)
     if (base + i < p.fix_cap) list[base + i] = buf[i];
 }
@@ -133,10 +136,17 @@ __device__ __forceinline__ float min3_abs(float m, float a, float b, uint32_t af
   return r;
 }
 
-// kExact = false: the fast pass described above, one block per (row panel, column chunk).
-// kExact = true: fallback pass over the same tiles, run by a fixed grid that exits at once
-// unless a pair list overflowed; it stores no words and decides the close pairs in place.
-template <bool kExact>
+// Three variants of one kernel:
+//   <false, false>  the usual pass, one block per (row panel, column chunk group): set bits go out
+//                   as edge records only and close pairs are queued; the bitmap G is not written
+//                   (the sparse path never reads it, and its 1.1 GB per 32k-token layer were
+//                   most of the kernel's HBM traffic)
+//   <true, false>   the same plus the words of G, for a caller that exports the adjacency matrix
+//   <true, true>    fallback, run by a fixed grid that exits at once unless need_full is raised
+//                   (a record segment, a pair list or a neighbour list ran full): writes every
+//                   word of G with the close pairs decided in place in double precision; no
+//                   records, no queue (degrees and lists then come from the bitmap)
+template <bool kStore, bool kExact>
 __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p) {
   typedef Mma<SPINDLE_F16> M;
   // two stages of 64 tokens, filled by direct global->LDS loads.  Row r keeps its 16-byte piece
@@ -147,17 +157,16 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   // the 32 words (one 128-byte line) of each of a wave's 64 rows for the current chunk;
   // written out as whole lines, because partially written lines cost several times their
   // size in HBM write traffic.  Row pitch 36 words keeps 16-byte alignment.
-  __shared__ __attribute__((aligned(16))) uint32_t wstage[kGramThreads / 64][64][36];
+  __shared__ __attribute__((aligned(16))) uint32_t wstage[kStore ? kGramThreads / 64 : 1][kStore ? 64 : 1][36];
   __shared__ uint32_t wordlist[kGramThreads / 64][kWordList];   // the 16-byte pieces of a chunk that have a set bit
+  // ... and, when G is not written, their words (they are listed as they are produced)
+  __shared__ __attribute__((aligned(16))) u4 wordvals[kStore ? 1 : kGramThreads / 64][kStore ? 1 : kWordList];
   const int n = p.n;
   const int nI = (n + kPanelRows - 1) / kPanelRows;
   const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
   // blocks are dealt round-robin to the 8 XCDs: give each XCD one (ut, chunk) at a time
   // and let it sweep the row panels, so the chunk is re-read from that XCD's L2
-  if (kExact) {
-    if (*p.fix_overflow == 0) return;
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(p.need_full, 1u);   // bits set here leave no edge records
-  }
+  if (kExact && *p.need_full == 0) return;
   const int nitems = 8 * nI * ((p.UT * nJ + 7) / 8);
   for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
   const int xcd = item & 7, s_ = item >> 3;
@@ -326,6 +335,17 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       q0 &= ~cm0;
       q1 &= ~cm1;
       rest = (cm0 & 0xFFFFu) | (cm1 << 16);
+      if (kExact) {                                     // decided here, so that the stored words are final
+        while (rest) {
+          const int i = __builtin_ctz(rest);
+          rest &= rest - 1;
+          const int row = arow0 + 32 * (i >> 4) + c;          // row of G
+          const int bit = bcol0 + 16 * g + (i & 15);           // staged token
+          if (row < n && bit < n && row != bit && cos64(p, ut, row, bit) > (double)p.theta[ut / p.U]) {
+            if (i >> 4) q1 |= 1u << (i & 15); else q0 |= 1u << (i & 15);
+          }
+        }
+      }
     }
     if (bcol0 < arow0 + 64 && bcol0 + 32 > arow0) {   // tile touches the diagonal: G_aa = 1
 #pragma unroll
@@ -353,7 +373,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     r1 = M::mma(f7, af[1][7], r1);
     // lane group 0 keeps the word of row block 0 (low halves), group 1 that of block 1
     const uint32_t word = __builtin_amdgcn_perm(halves[1], halves[0], wsel);
-    if (any_close) {
+    if (!kExact && any_close) {
       while (__any(rest != 0)) {
         const bool has = rest != 0;
         const int i = has ? __builtin_ctz(rest) : 0;
@@ -361,11 +381,6 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
         const int row = arow0 + 32 * (i >> 4) + c;          // row of G
         const int bit = bcol0 + 16 * g + (i & 15);           // staged token
         const bool valid = has && row < n && bit < n && row != bit;
-        if (kExact) {
-          if (valid && cos64(p, ut, row, bit) > (double)p.theta[ut / p.U])
-            atomicOr(p.G + ((size_t)ut * n + row) * p.Wp + (bit >> 5), 1u << (bit & 31));
-          continue;
-        }
         const unsigned long long m = __ballot(valid);
         if (m) {                                    // wave-uniform
           if (nbuf > kPairBuf - 64) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
@@ -395,6 +410,43 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     pf1 = frag_at(0, 1, 1);
   }
   u4 words = {0, 0, 0, 0};
+  // The set bits go out as (row, column) records, a segment per wave and chunk: sparse graphs get
+  // their neighbour lists from these without a pass over G.  Few of the 512 16-byte pieces of a
+  // chunk (64 rows x 8) have a bit set: the pieces that have one are listed, then every lane takes
+  // a listed piece and the wave peels off one bit of each per pass.
+  const int nJc = (n + kChunkCols - 1) / kChunkCols;
+  const size_t seg = (((size_t)ut * nJc + J) * nI + I) * 4 + wave;
+  uint32_t *eseg = p.edges + seg * p.seg_cap;
+  int ecnt = 0;                                      // wave-uniform
+  const unsigned long long below = (1ull << lane) - 1ull;
+  uint32_t *wl = wordlist[wave];
+  int nw = 0;                                        // wave-uniform
+  auto expand = [&]() {
+    for (int e0 = 0; e0 < nw; e0 += kWave) {
+      const int e = e0 + lane;
+      const uint32_t key = e < nw ? wl[e] : 0u;      // row in the wave << 3 | piece
+      u4 v;
+      if (kStore) v = *reinterpret_cast<const u4 *>(&wstage[kStore ? wave : 0][kStore ? key >> 3 : 0][(key & 7u) * 4]);
+      else v = wordvals[kStore ? 0 : wave][kStore ? 0 : (e < nw ? e : 0)];
+      if (e >= nw) v = u4{0, 0, 0, 0};
+      const uint32_t rec0 = ((uint32_t)(arow0 + (int)(key >> 3)) << 16) | (uint32_t)(col_begin + (int)(key & 7u) * 128);
+      for (;;) {
+        const bool has = (v[0] | v[1] | v[2] | v[3]) != 0;
+        const unsigned long long mk = __ballot(has);
+        if (mk == 0) break;
+        if (has) {
+          const int j = v[0] ? 0 : v[1] ? 1 : v[2] ? 2 : 3;
+          const uint32_t w = v[j];
+          const int t = __builtin_ctz(w);
+          v[j] = w & (w - 1);
+          const int at = ecnt + __popcll(mk & below);
+          if (at < p.seg_cap) eseg[at] = rec0 + (uint32_t)(j * 32 + t);
+        }
+        ecnt += __popcll(mk);
+      }
+    }
+    nw = 0;
+  };
   // four tiles (two stages) per trip: their words are one aligned 16-byte piece of the row.
   // The trip is branch-free: tiles past the end of the chunk only occur at the end of the
   // sequence and give zero words.  Step j packs tile t0 + j and multiplies tile x = t0 + j + 1.
@@ -408,61 +460,46 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       cur0 = nxt0;
       cur1 = nxt1;
     }
-    if (!kExact) *reinterpret_cast<u4 *>(&wstage[wave][lane][t0]) = words;
-  }
-  if (!kExact) {
-    const int npieces = (ntiles + 3) / 4, piece = lane & 7;
-    // the set bits also go out as (row, column) records, a segment per wave and chunk: sparse
-    // graphs get their neighbour lists from these without another pass over G
-    const int nJc = (n + kChunkCols - 1) / kChunkCols;
-    const size_t seg = (((size_t)ut * nJc + J) * nI + I) * 4 + wave;
-    uint32_t *eseg = p.edges + seg * p.seg_cap;
-    int ecnt = 0;                                    // wave-uniform
-    const unsigned long long below = (1ull << lane) - 1ull;
-    // Few of the 512 16-byte pieces of a chunk (64 rows x 8) have a bit set.  First the pieces
-    // that have one are listed (one ballot per eight rows), then every lane takes a listed piece
-    // and the wave peels off one bit of each per pass: far fewer passes than over all pieces.
-    uint32_t *wl = wordlist[wave];
-    int nw = 0;                                      // wave-uniform
-    auto expand = [&]() {
-      for (int e0 = 0; e0 < nw; e0 += kWave) {
-        const int e = e0 + lane;
-        const uint32_t key = e < nw ? wl[e] : 0u;    // row in the wave << 3 | piece
-        u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][key >> 3][(key & 7u) * 4]);
-        if (e >= nw) v = u4{0, 0, 0, 0};
-        const uint32_t rec0 = ((uint32_t)(arow0 + (int)(key >> 3)) << 16) | (uint32_t)(col_begin + (int)(key & 7u) * 128);
-        for (;;) {
-          const bool has = (v[0] | v[1] | v[2] | v[3]) != 0;
-          const unsigned long long mk = __ballot(has);
-          if (mk == 0) break;
-          if (has) {
-            const int j = v[0] ? 0 : v[1] ? 1 : v[2] ? 2 : 3;
-            const uint32_t w = v[j];
-            const int t = __builtin_ctz(w);
-            v[j] = w & (w - 1);
-            const int at = ecnt + __popcll(mk & below);
-            if (at < p.seg_cap) eseg[at] = rec0 + (uint32_t)(j * 32 + t);
-          }
-          ecnt += __popcll(mk);
-        }
-      }
-      nw = 0;
-    };
-    for (int it = 0; it < 8; ++it) {
-      const int r = it * 8 + (lane >> 3);
-      const u4 v = *reinterpret_cast<const u4 *>(&wstage[wave][r][piece * 4]);
-      const bool live = arow0 + r < n && piece < npieces;
-      if (live)
-        *reinterpret_cast<u4 *>(p.G + ((size_t)ut * n + arow0 + r) * p.Wp + (col_begin >> 5) + piece * 4) = v;
-      const bool nz = live && (v[0] | v[1] | v[2] | v[3]) != 0;
+    if (kStore) {
+      *reinterpret_cast<u4 *>(&wstage[kStore ? wave : 0][kStore ? lane : 0][t0]) = words;
+    } else {
+      // (rows and tokens past the end of the sequence have no bits: the step masks them)
+      const bool nz = (words[0] | words[1] | words[2] | words[3]) != 0;
       const unsigned long long mk = __ballot(nz);
-      if (mk) {                                      // wave-uniform
+      if (mk) {                                      // wave-uniform, and rare: most pieces are empty
         const int add = __popcll(mk);
         if (nw + add > kWordList) expand();
-        if (nz) wl[nw + __popcll(mk & below)] = (uint32_t)(r << 3 | piece);
+        if (nz) {
+          const int at = nw + __popcll(mk & below);
+          wl[at] = (uint32_t)(lane << 3 | (t0 >> 2));
+          wordvals[kStore ? 0 : wave][kStore ? 0 : at] = words;
+        }
         nw += add;
       }
     }
+  }
+  if (kStore) {
+    // the 32 words of each row go out as whole 128-byte lines
+    const int npieces = (ntiles + 3) / 4, piece = lane & 7;
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 8 + (lane >> 3);
+      const u4 v = *reinterpret_cast<const u4 *>(&wstage[kStore ? wave : 0][kStore ? r : 0][piece * 4]);
+      const bool live = arow0 + r < n && piece < npieces;
+      if (live)
+        *reinterpret_cast<u4 *>(p.G + ((size_t)ut * n + arow0 + r) * p.Wp + (col_begin >> 5) + piece * 4) = v;
+      if (!kExact) {
+        const bool nz = live && (v[0] | v[1] | v[2] | v[3]) != 0;
+        const unsigned long long mk = __ballot(nz);
+        if (mk) {                                    // wave-uniform
+          const int add = __popcll(mk);
+          if (nw + add > kWordList) expand();
+          if (nz) wl[nw + __popcll(mk & below)] = (uint32_t)(r << 3 | piece);
+          nw += add;
+        }
+      }
+    }
+  }
+  if (!kExact) {
     expand();
     if (lane == 0) {
       p.ecount[seg] = (unsigned)(ecnt < p.seg_cap ? ecnt : p.seg_cap);
@@ -612,7 +649,7 @@ __global__ __launch_bounds__(kMirrorThreads, 2) void shallow_mirror(ShallowParam
 }
 
 // ---------------------------------------------------------------- exact fix-up
-__global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
+__global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p, int store_bits) {
   const int ut = blockIdx.y;                         // all problems side by side: each list is short
   const unsigned stride = gridDim.x * blockDim.x;
   unsigned count = p.fix_count[ut];
@@ -623,7 +660,7 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p) {
     const uint32_t e = list[i];
     const int b = (int)(e >> 16), a = (int)(e & 0xFFFFu);
     const bool adj = cos64(p, ut, a, b) > theta;
-    if (adj) atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
+    if (adj && store_bits) atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
     // ... and as a record for the neighbour lists, filed under the panel of the row; a pair of
     // two different 1024-token tiles was only evaluated in this orientation, so it also
     // extends the list of its column
@@ -840,11 +877,10 @@ spindle_status launch_graph(const ShallowParams &p, hipStream_t st, int force) {
   const int nJ = (n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
   const int pairs8 = (p.UT * nJ + 7) / 8;
   { ProfScope ps("shallow_gram", st);
-  hipLaunchKernelGGL(shallow_gram<false>, dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p); }
-  { ProfScope ps("shallow_gram_exact", st);
-  hipLaunchKernelGGL(shallow_gram<true>, dim3(1024), dim3(kGramThreads), 0, st, p); }
+  if (force) hipLaunchKernelGGL((shallow_gram<true, false>), dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p);
+  else hipLaunchKernelGGL((shallow_gram<false, false>), dim3(8 * nI * pairs8), dim3(kGramThreads), 0, st, p); }
   { ProfScope ps("shallow_fixup", st);
-  hipLaunchKernelGGL(shallow_fixup, dim3(128, p.UT), dim3(256), 0, st, p); }
+  hipLaunchKernelGGL(shallow_fixup, dim3(128, p.UT), dim3(256), 0, st, p, force); }
 
   // sparse graphs: lists from the edge records; otherwise (or when the caller wants the
   // adjacency matrix) the lower triangle is written and the lists come from the bitmap
@@ -852,6 +888,11 @@ spindle_status launch_graph(const ShallowParams &p, hipStream_t st, int force) {
   const dim3 eg(nI, p.UT);
   if (p.seg_cap == 512) hipLaunchKernelGGL(shallow_edge_lists<512>, eg, dim3(kEdgeThreads), 0, st, p, force);
   else hipLaunchKernelGGL(shallow_edge_lists<0>, eg, dim3(kEdgeThreads), 0, st, p, force); }
+  // fallback chain, three launches that exit at once unless need_full was raised (or, the last
+  // two, the caller exports the adjacency matrix): every word of G with exact decisions, its
+  // lower triangle, degrees and lists from the bitmap
+  { ProfScope ps("shallow_gram_exact", st);
+  hipLaunchKernelGGL((shallow_gram<true, true>), dim3(1024), dim3(kGramThreads), 0, st, p); }
   const int T1k = (n + 1023) / 1024, npairs = T1k * (T1k - 1) / 2;
   if (npairs > 0) {
     static LdsLimit lim_mirror;
