@@ -259,72 +259,60 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   // fetch_b0 ..) and makes the next stage, loaded one barrier earlier, visible.
   auto step = [&](int bufx, int ctx, int bufn, int ctn, bool sync_fetch, int fetch_b0, int bcol0, const f16v &a0,
                   const f16v &a1, f16v &r0, f16v &r1) -> uint32_t {
-    M::frag f2 = frag_at(bufx, ctx, 2), f3 = frag_at(bufx, ctx, 3);
-    r0 = M::mma(pf0, af[0][0], cinit);
-    r1 = M::mma(pf0, af[1][0], cinit);
-    __builtin_amdgcn_sched_barrier(0);               // matrix instructions first: the vector work below waits for the previous tile
+    // Sixteen slots, each one matrix instruction followed by a slice of at most four vector
+    // instructions (16 cycles of issue under the 32 cycles the matrix instruction occupies its
+    // pipeline): with two matrix instructions back to back the second one waits for the pipeline
+    // and holds up the wave's vector work behind it.  The 48 packing instructions (sign of a0[v]
+    // into sg0, of a1[v] into sg1, guard band) run in slots 0-11, results of the row block that
+    // finished first (a0) first; the word is assembled in slots 12-15.
     uint32_t sg0 = 0, sg1 = 0;
     float mn = INFINITY;
-#pragma unroll
-    for (int v = 15; v >= 12; --v) {
-      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
-      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
-      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(pf1, af[0][1], r0);
-    r1 = M::mma(pf1, af[1][1], r1);
+#define SPINDLE_PACK(k)                                                                              \
+  do {                                                                                               \
+    constexpr int v_ = 15 - (k) % 16;                                                                \
+    if ((k) < 16) sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v_]), 31);                 \
+    else if ((k) < 32) sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v_]), 31);            \
+    else mn = min3_abs(mn, a0[v_], a1[v_], sg0, sg1);                                                \
+  } while (0)
+#define SPINDLE_SLOT(mfma, k)                                                                        \
+  do {                                                                                               \
+    mfma;                                                                                            \
+    SPINDLE_PACK(k); SPINDLE_PACK((k) + 1); SPINDLE_PACK((k) + 2); SPINDLE_PACK((k) + 3);            \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+  } while (0)
+    M::frag f2 = frag_at(bufx, ctx, 2), f3 = frag_at(bufx, ctx, 3);
+    SPINDLE_SLOT(r0 = M::mma(pf0, af[0][0], cinit), 0);
+    SPINDLE_SLOT(r1 = M::mma(pf0, af[1][0], cinit), 4);
     M::frag f4 = frag_at(bufx, ctx, 4), f5 = frag_at(bufx, ctx, 5);
-#pragma unroll
-    for (int v = 11; v >= 9; --v) {
-      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
-      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
-      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(f2, af[0][2], r0);
-    r1 = M::mma(f2, af[1][2], r1);
+    SPINDLE_SLOT(r0 = M::mma(pf1, af[0][1], r0), 8);
+    SPINDLE_SLOT(r1 = M::mma(pf1, af[1][1], r1), 12);
     M::frag f6 = frag_at(bufx, ctx, 6), f7 = frag_at(bufx, ctx, 7);
-#pragma unroll
-    for (int v = 8; v >= 6; --v) {
-      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
-      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
-      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(f3, af[0][3], r0);
-    r1 = M::mma(f3, af[1][3], r1);
-#pragma unroll
-    for (int v = 5; v >= 3; --v) {
-      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
-      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
-      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
+    SPINDLE_SLOT(r0 = M::mma(f2, af[0][2], r0), 16);
+    SPINDLE_SLOT(r1 = M::mma(f2, af[1][2], r1), 20);
+    SPINDLE_SLOT(r0 = M::mma(f3, af[0][3], r0), 24);
+    SPINDLE_SLOT(r1 = M::mma(f3, af[1][3], r1), 28);
     if (sync_fetch) {
       __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): own loads landed, own reads done
       __builtin_amdgcn_s_barrier();
       dma(fetch_b0, bufx);
     }
     __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(f4, af[0][4], r0);
-    r1 = M::mma(f4, af[1][4], r1);
+    SPINDLE_SLOT(r0 = M::mma(f4, af[0][4], r0), 32);
     pf0 = frag_at(bufn, ctn, 0);
     pf1 = frag_at(bufn, ctn, 1);
-#pragma unroll
-    for (int v = 2; v >= 0; --v) {
-      sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v]), 31);
-      sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v]), 31);
-      mn = min3_abs(mn, a0[v], a1[v], sg0, sg1);
-    }
+    SPINDLE_SLOT(r1 = M::mma(f4, af[1][4], r1), 36);
+    SPINDLE_SLOT(r0 = M::mma(f5, af[0][5], r0), 40);
+    SPINDLE_SLOT(r1 = M::mma(f5, af[1][5], r1), 44);
+#undef SPINDLE_SLOT
+#undef SPINDLE_PACK
+    r0 = M::mma(f6, af[0][6], r0);
     uint32_t q0 = ~sg0 & 0xFFFFu, q1 = ~sg1 & 0xFFFFu;   // bit v: staged token 16*g + v
     // pairs too close to theta for fp16: clear their bits now, queue them for the exact
     // decision.  Bit 16*cb + v of `rest` = close.
     uint32_t rest = 0;
     const bool any_close = __any(mn < band);
     __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(f5, af[0][5], r0);
-    r1 = M::mma(f5, af[1][5], r1);
+    r1 = M::mma(f6, af[1][6], r1);
     if (any_close) {
       uint32_t cm0 = 0, cm1 = 0;
 #pragma unroll
@@ -363,13 +351,11 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       q1 &= keep;
     }
     __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(f6, af[0][6], r0);
-    r1 = M::mma(f6, af[1][6], r1);
+    r0 = M::mma(f7, af[0][7], r0);
     // halves[0] = the value of the lane with g = 0 of this column, halves[1] = that of g = 1
     const uint32_t own = q0 | (q1 << 16);
     const auto halves = __builtin_amdgcn_permlane32_swap(own, own, false, false);
     __builtin_amdgcn_sched_barrier(0);
-    r0 = M::mma(f7, af[0][7], r0);
     r1 = M::mma(f7, af[1][7], r1);
     // lane group 0 keeps the word of row block 0 (low halves), group 1 that of block 1
     const uint32_t word = __builtin_amdgcn_perm(halves[1], halves[0], wsel);
