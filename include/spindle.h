@@ -18,9 +18,12 @@
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, contiguous in
- *     the stated shape, 16-byte aligned.  The library allocates no device memory
- *     and keeps no state between calls; scratch space is the caller's `workspace`
- *     (size from the *_workspace_bytes query, 256-byte aligned).
+ *     the stated shape, 16-byte aligned.  The library allocates no device memory;
+ *     scratch space is the caller's `workspace` (size from the *_workspace_bytes
+ *     query, 256-byte aligned).  No result depends on an earlier call: what the
+ *     library keeps per process is the records of spindle_profile, a per-device note
+ *     that a kernel's LDS limit has been raised, and the built-in scratch array of
+ *     spindle_decode_merge_static.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue
  *     work on it and return without synchronising; all data-dependent counts stay
  *     on the device.
@@ -151,7 +154,11 @@ spindle_status spindle_shallow_workspace_bytes(const spindle_kv_desc *desc, int3
  *
  *   K, V        either may be NULL (with all of its outputs) to process one tensor.
  *   Ck, Cv      [B, h_g, max_codes, d] unit vectors in `dtype`; rows >= n_codes are zero.
- *   n_codes_*   [B, h_g] int32 stored entries = min(found, max_codes).
+ *   n_codes_*   [B, h_g] int32 stored entries = min(found, max_codes).  -1 marks a problem whose
+ *               construction did not finish; its other outputs are then undefined.  Every
+ *               round takes at least the remaining token of the largest key, so this cannot
+ *               happen unless the workspace was overwritten while the call ran (a second
+ *               call on another stream with the same workspace, or between the two halves).
  *   n_found_*   optional [B, h_g] int32 entries found before the cap, else NULL.
  *   ref_*       [B, h_g, l] int32 code index of each token, in [0, n_codes).
  *   mag_*       [B, h_g, l] float32 magnitudes m_a.
