@@ -30,27 +30,134 @@ PEAK_VALU_F64_TFLOPS = 78.6         # 256 CUs x 64 lanes x 2 flop x 2.4 GHz
 PIPELINE_SETS = 3
 
 
-def cpu_baseline(L, wl, sample_n=24576):
-    """The oracle as it stands, timed on this host: the eviction path on one full unit and
-    the codebook path on the first `sample_n` tokens of one K unit; scaled to a whole layer
-    (eviction linear in units, codebook quadratic in tokens and linear in units)."""
+def cpu_baseline(L, wl, max_threads=16):
+    """The oracle as it stands, timed on this host on the whole layer the GPU step processes: every
+    eviction unit and every codebook problem (K and V of every head) in full, one problem per
+    thread (the oracle itself is single-threaded; ctypes releases the interpreter lock).  `value`
+    is the layer's tokens over the wall time with `cores` threads; the time the threads spent per
+    problem (while the other cores were busy too) is reported beside it."""
     import oracle
+    from concurrent.futures import ThreadPoolExecutor
     oracle.lib()
     d = L.head_dim
     scale = float(np.float32(1.0 / np.sqrt(d)))
-    K0 = wl.to_f64(L.K[0, 0], L.dtype)
-    Q0 = wl.to_f64(L.Qw[0, :L.group_size], L.dtype)
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    cores = max(1, min(max_threads, avail))
+    units = [(b, h) for b in range(L.batch) for h in range(L.n_kv_heads)]
+    jobs = [("deep", b, h) for b, h in units] + [(t, b, h) for t in ("k", "v") for b, h in units]
+
+    def run(job):
+        kind, b, h = job
+        t0 = time.perf_counter()
+        if kind == "deep":
+            oracle.deep_unit(wl.to_f64(L.Qw[b, h * L.group_size:(h + 1) * L.group_size], L.dtype),
+                             wl.to_f64(L.K[b, h], L.dtype), scale, L.pool, L.budget)
+        else:
+            X = wl.to_f64((L.K if kind == "k" else L.V)[b, h], L.dtype)
+            theta = L.theta_k if kind == "k" else L.theta_v
+            o = oracle.shallow_unit(X, float(np.float32(theta)), L.max_codes)
+            del o
+        return kind, time.perf_counter() - t0
+
     t0 = time.perf_counter()
-    oracle.deep_unit(Q0, K0, scale, L.pool, L.budget)
-    t_deep_unit = time.perf_counter() - t0
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        times = list(ex.map(run, jobs))
+    wall = time.perf_counter() - t0
+    t_deep = [t for k, t in times if k == "deep"]
+    t_code = [t for k, t in times if k != "deep"]
+    busy = sum(t for _, t in times)
+    return {"value": L.batch * L.seq_len / wall, "unit": "tokens/s/layer", "cores": cores, "kind": "oracle",
+            "sample": f"the whole layer of the timed step, nothing scaled: {len(t_deep)} eviction units and "
+                      f"{len(t_code)} codebook problems of {L.seq_len} tokens, one per thread, {cores} threads",
+            "wall_s": wall, "thread_s_per_eviction_unit": float(np.mean(t_deep)),
+            "thread_s_per_codebook_problem": float(np.mean(t_code)),
+            "one_core_value_from_thread_time": L.batch * L.seq_len / busy}
+
+
+def deep_bytes(units, l, d, esz, kept):
+    """Algorithmic HBM bytes of one eviction call: K read once, the kept rows of K and V read and
+    written, three words per key of scores (raw, pooled, index)."""
+    return units * (l * d * esz + 2 * 2 * kept * d * esz + 3 * 4 * l)
+
+
+def time_deep_call(torch, plan, K, V, Q, reps=30):
+    """Average duration of the whole eviction call (its four kernels back to back on one stream,
+    no events between them): one pair of torch events around `reps` calls."""
+    for _ in range(3):
+        plan.run(K, V, Q)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        plan.run(K, V, Q)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def deep_folded(torch, sb, wl):
+    """The 24 eviction layers of the 8192-token stack (configs[2]) folded into the batch dimension of
+    ONE call, with the stack's per-layer budgets as per-unit budgets: 192 units."""
+    layers = list(range(8, 32))
+    Ls = [wl.config3_layer(i) for i in layers]
+    K = sb.to_device(np.concatenate([x.K for x in Ls]), "f16")
+    V = sb.to_device(np.concatenate([x.V for x in Ls]), "f16")
+    Q = sb.to_device(np.concatenate([x.Qw for x in Ls]), "f16")
+    H = Ls[0].n_kv_heads
+    per_unit = [wl.config3_budget(i) for i in layers for _ in range(H)]
+    budgets = torch.tensor(per_unit, dtype=torch.int32, device="cuda")
+    plan = sb.plan_deep(K, Ls[0].group_size, "f16", Ls[0].window, Ls[0].pool, Ls[0].window, want_scores=False,
+                        budgets=budgets, out_stride=max(per_unit))
+    ms = time_deep_call(torch, plan, K, V, Q, reps=20)
+    l, d = Ls[0].seq_len, Ls[0].head_dim
+    nbytes = deep_bytes(len(per_unit), l, d, 2, float(np.mean(per_unit)))
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"workload": "configs[2] layers 8-31 as one call: 192 units of 8192 tokens, fp16, budgets 2048 .. 256",
+            "ms_per_call": ms, "tokens_per_s": len(layers) * l / (ms * 1e-3), "bound": "hbm", "achieved": gbs,
+            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+
+
+def config5_layer(torch, sb, wl, cap=4096, steps=8, warmup=3):
+    """One layer of configs[4] (batch 4, bf16, half of the tokens isolated noise, budget = cap), the
+    two calls one after the other on one stream: a secondary figure of the same run."""
+    L = wl.config5_layer(0, cap)
+    K, V, Q = (sb.to_device(x, L.dtype) for x in (L.K, L.V, L.Qw))
+    deep = sb.plan_deep(K, L.group_size, L.dtype, L.window, L.pool, L.budget, want_scores=False)
+    shallow = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)
+    for _ in range(warmup):
+        deep.run(K, V, Q)
+        shallow.run(K, V)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    oracle.shallow_unit(K0[:sample_n], float(np.float32(L.theta_k)), min(L.max_codes, sample_n))
-    t_sh_sample = time.perf_counter() - t0
+    for _ in range(steps):
+        deep.run(K, V, Q)
+        shallow.run(K, V)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    sb.spindle_profile(1)
+    for _ in range(3):
+        deep.run(K, V, Q)
+        shallow.run(K, V)
+    torch.cuda.synchronize()
+    per = {}
+    for name, t in sb.spindle_profile_read():
+        per[name] = per.get(name, 0.0) + t / 3
+    sb.spindle_profile(0)
+    deep_ms = time_deep_call(torch, deep, K, V, Q, reps=10)
     units = L.batch * L.n_kv_heads
-    t_layer = units * t_deep_unit + 2 * units * t_sh_sample * (L.seq_len / sample_n) ** 2
-    return {"value": L.batch * L.seq_len / t_layer, "unit": "tokens/s/layer", "cores": 1, "kind": "oracle",
-            "sample": f"deep: 1 of {units} units in full ({t_deep_unit:.2f} s); shallow: first {sample_n} tokens of "
-                      f"1 of {2 * units} K/V units ({t_sh_sample:.2f} s), scaled by units and by (l/{sample_n})^2"}
+    nbytes = deep_bytes(units, L.seq_len, L.head_dim, 2, min(L.budget, L.seq_len))
+    gram_flop = 2 * units * (L.seq_len ** 2 / 2) * L.head_dim * 2
+    assert min(shallow.out["n_codes_k"].min().item(), shallow.out["n_codes_v"].min().item()) >= 1
+    out = {"workload": f"configs[4], one layer: batch 4 x {L.seq_len}, bf16, pool 15, budget = cap = {cap}; one stream",
+           "steps": steps, "ms_per_step": ms, "tokens_per_s": L.batch * L.seq_len / (ms * 1e-3), "kernel_ms": per,
+           "deep_call_ms": deep_ms, "deep_frac_of_hbm": nbytes / (deep_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+           "shallow_gram_frac_of_mfma": gram_flop / (per["shallow_gram"] * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS}
+    del deep, shallow, K, V, Q
+    torch.cuda.empty_cache()
+    return out
 
 
 def time_reconstruct(torch, sb, L, shallow, reps=20):
@@ -154,6 +261,8 @@ def main():
     ap.add_argument("--cap", type=int, default=4096, help="budget = codebook cap of --workload config5")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (scale reference for the HBM traffic counters)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the secondary measurements (folded eviction call, config-5 layer, reconstruction, decode)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "shallow_gram_config4_traffic.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -261,10 +370,15 @@ def main():
     # once: n^2/2 pairs x 128 multiply-adds x 2 flop, per (unit, K|V).
     gram_flop = 2 * units * (L.seq_len ** 2 / 2) * L.head_dim * 2
     achieved = gram_flop / (gram_ms * 1e-3) / 1e12
-    traffic = None
-    if args.workload == "config4" and os.path.exists(args.traffic_json):
+    # HBM bytes per launch of the dominant kernel: not measurable inside this process (it takes two
+    # rocprofv3 counter runs); read from the committed summary, with the source commit it names
+    traffic, traffic_source = None, None
+    if args.workload == "config4" and args.seq_len == 32768 and os.path.exists(args.traffic_json):
         try:
-            traffic = json.load(open(args.traffic_json)).get("hbm_bytes_per_launch")
+            tj = json.load(open(args.traffic_json))
+            traffic = tj.get("hbm_bytes_per_launch")
+            traffic_source = {"file": os.path.relpath(args.traffic_json, ROOT), "kernel": tj.get("kernel"),
+                              "measured_on_commit": tj.get("measured_on_commit")}
         except Exception:
             traffic = None
     out = {
@@ -292,6 +406,7 @@ def main():
                           "other on one stream and HIP events around every kernel, which lengthens the step; "
                           "roofline uses the timed steps' own events",
         "ms_per_step_one_at_a_time": ms_step_unpipelined,
+        "tokens_per_s_one_at_a_time": tokens / (ms_step_unpipelined * 1e-3) if ms_step_unpipelined else None,
         "ms_per_step_with_all_events": ms_step_all_events,
         "deep_ms": ms_deep, "shallow_ms": ms_shallow,
         "deep_tokens_per_s": tokens / (ms_deep * 1e-3), "shallow_tokens_per_s": tokens / (ms_shallow * 1e-3),
@@ -301,14 +416,20 @@ def main():
         "merge_phase_us_unit0": st[0, 4:14].tolist(),
         "roofline": {"kernel": "shallow_gram", "bound": "mfma", "kernel_ms": gram_ms, "achieved": achieved,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F16_TFLOPS,
-                     "traffic": traffic},
+                     "traffic": traffic, "traffic_source": traffic_source},
     }
-    # secondary: the eviction path against the HBM roofline (K read once + gathered rows r/w + scores)
-    deep_bytes = units * (L.seq_len * L.head_dim * 2 + 2 * 2 * L.budget * L.head_dim * 2 + 3 * 4 * L.seq_len)
-    out["deep_roofline"] = {"bound": "hbm", "achieved": deep_bytes / (ms_deep * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                            "unit": "GB/s", "frac": deep_bytes / (ms_deep * 1e-3) / 1e9 / PEAK_HBM_GBS}
-    out["reconstruct"] = time_reconstruct(torch, sb, L, shallow)
-    out["decode_merge"] = time_decode(torch, sb, L, K, shallow)
+    # secondary: the eviction call against the HBM roofline, timed on its own without events between
+    # its kernels (deep_ms above is the breakdown pass, where every kernel is followed by an event gap)
+    esz = K.element_size()
+    nbytes = deep_bytes(units, L.seq_len, L.head_dim, esz, min(L.budget, L.seq_len))
+    deep_call_ms = time_deep_call(torch, deep, K, V, Q)
+    out["deep_roofline"] = {"bound": "hbm", "call_ms": deep_call_ms, "achieved": nbytes / (deep_call_ms * 1e-3) / 1e9,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": nbytes / (deep_call_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "tokens_per_s": tokens / (deep_call_ms * 1e-3),
+                            "kernels_ms": {k: v for k, v in kernel_ms.items() if k.startswith("deep_")}}
+    if not args.no_extras:
+        out["reconstruct"] = time_reconstruct(torch, sb, L, shallow)
+        out["decode_merge"] = time_decode(torch, sb, L, K, shallow)
     # Eq. 15 on this layer: eviction alone (r1) and replacement alone (r2 r3), each on the full layer
     stored = int(shallow.out["n_codes_k"].sum().item() + shallow.out["n_codes_v"].sum().item())
     bits = 8 * torch.empty(0, dtype=sb.torch_dtype(L.dtype)).element_size()
@@ -317,6 +438,13 @@ def main():
     _, r2, r3, r23 = sb.spindle_reserve_ratio(2 * units * L.seq_len, 2 * units * L.seq_len, stored, L.head_dim, 16, bits, 32)
     out["reserve_ratio"] = {"eviction_r1": r1, "replacement_r2": r2, "r3": r3, "replacement_r2_r3": r23,
                             "index_bits": 16, "magnitude_bits": 32, "element_bits": bits}
+    del pipe, layer
+    if not args.no_extras and args.workload == "config4":
+        del deep, shallow, K, V, Q
+        torch.cuda.empty_cache()
+        out["deep_roofline_folded"] = deep_folded(torch, sb, wl)
+        out["config5_layer"] = config5_layer(torch, sb, wl)
+        deep = shallow = K = V = Q = None
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, wl)
     print(json.dumps(out), flush=True)
