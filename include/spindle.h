@@ -209,6 +209,35 @@ spindle_status spindle_shallow_codebook(const spindle_kv_desc *desc, const void 
                                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * One codebook per layer instead of one per KV head (Sec. "Similarity Based Token Replacement",
+ * first paragraph: the copies that repeating K and V for every query head creates have cosine 1
+ * and must cost no storage; Eq. 15, whose r_2 counts the entries of a layer, |C_K u C_V|, with
+ * no sum over heads).  The rows of all n_kv_heads heads of a batch entry, head after head, are
+ * ONE problem of n_kv_heads * seq_len tokens run through Alg. 1 exactly as
+ * spindle_compress_shallow runs a head: same thresholds, decisions, tie rules and cap.
+ * With K and V repeated per query head (n_kv_heads = the number of query heads,
+ * spindle_compress_deep called with group_size 1 on the repeated tensors) the inputs are that
+ * call's K_out and V_out as they are, with seq_len = its out_stride, when every unit keeps
+ * out_stride rows.
+ *   K, V        [B, n_kv_heads, seq_len, d]; the heads of a batch entry must follow each other
+ *               in memory (stride_h = seq_len * stride_t, or all strides 0).
+ *   Ck, Cv      [B, max_codes, d];  n_codes_*, n_found_* [B]
+ *   ref_*       [B, n_kv_heads, seq_len] int32: entry of the layer's codebook, in [0, n_codes)
+ *   mag_*       [B, n_kv_heads, seq_len] float32
+ * Errors as spindle_compress_shallow; SPINDLE_ERR_UNSUPPORTED if n_kv_heads * seq_len > 65535
+ * (evict to fewer rows per head first) or the heads are not adjacent in memory.  The workspace
+ * size comes from spindle_shallow_layer_workspace_bytes.
+ */
+spindle_status spindle_shallow_layer_workspace_bytes(const spindle_kv_desc *desc, int32_t n_tensors,
+                                                     size_t *bytes);
+spindle_status spindle_compress_shallow_layer(const spindle_kv_desc *desc, const void *K, const void *V,
+                                              float theta_k, float theta_v, int32_t max_codes,
+                                              void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v,
+                                              int32_t *n_found_k, int32_t *n_found_v,
+                                              int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v,
+                                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Diagnostics of the last spindle_compress_shallow call that used `workspace` with this
  * shape: for each of the batch * n_kv_heads * n_tensors problems i (all K units first,
  * then all V units), with s = stats + 16*i: s[0] = rounds of the parallel codebook

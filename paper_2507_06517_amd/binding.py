@@ -26,12 +26,13 @@ _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 # the first N_STATUS return a status code
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
            "spindle_compress_shallow", "spindle_shallow_graph", "spindle_shallow_codebook",
+           "spindle_shallow_layer_workspace_bytes", "spindle_compress_shallow_layer",
            "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
            "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_decode_workspace_bytes", "spindle_decode_merge",
            "spindle_decode_merge_static",
            "spindle_profile_read", "spindle_decode_static_capacity",
            "spindle_last_error", "spindle_version"]
-N_STATUS = 14
+N_STATUS = 16
 
 
 class KvDesc(C.Structure):
@@ -63,6 +64,8 @@ def lib():
         L.spindle_shallow_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         for fn in (L.spindle_compress_shallow, L.spindle_shallow_graph, L.spindle_shallow_codebook):
             fn.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 14 + [vp, sz, vp]
+        L.spindle_shallow_layer_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
+        L.spindle_compress_shallow_layer.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 10 + [vp, sz, vp]
         L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.spindle_profile.argtypes = [i32]
         L.spindle_profile_read.argtypes = [C.c_char_p, C.POINTER(C.c_float), i32]
@@ -451,6 +454,47 @@ def compress_shallow(K, V, dtype, theta_k, theta_v, max_codes, debug=False):
     tensors = tuple(t for t, x in (("k", K), ("v", V)) if x is not None)
     plan = plan_shallow(ref, dtype, theta_k, theta_v, max_codes, tensors, debug)
     return plan.run(K, V)
+
+
+def spindle_shallow_layer_workspace_bytes(desc: KvDesc, n_tensors: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().spindle_shallow_layer_workspace_bytes(C.byref(desc), int(n_tensors), C.byref(out)))
+    return out.value
+
+
+def spindle_compress_shallow_layer(desc, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_codes_k, n_codes_v, n_found_k,
+                                   n_found_v, ref_k, ref_v, mag_k, mag_v, workspace, workspace_bytes, stream=None):
+    _check(lib().spindle_compress_shallow_layer(C.byref(desc), _ptr(K), _ptr(V), float(theta_k), float(theta_v),
+                                                int(max_codes), _ptr(Ck), _ptr(Cv), _ptr(n_codes_k), _ptr(n_codes_v),
+                                                _ptr(n_found_k), _ptr(n_found_v), _ptr(ref_k), _ptr(ref_v),
+                                                _ptr(mag_k), _ptr(mag_v), _ptr(workspace), int(workspace_bytes),
+                                                stream or _stream()))
+
+
+def compress_shallow_layer(K, V, dtype, theta_k, theta_v, max_codes):
+    """One codebook per layer over the rows of all heads.  K, V [B, H, l, d] (either may be None) ->
+    dict(C_k [B, max_codes, d], n_codes_k [B], n_found_k [B], ref_k [B, H, l], mag_k [B, H, l], ... _v)."""
+    import torch
+    X = K if K is not None else V
+    B, H, l, d = X.shape
+    desc = desc_of(X, 1, dtype)
+    tensors = [t for t, x in (("k", K), ("v", V)) if x is not None]
+    nbytes = spindle_shallow_layer_workspace_bytes(desc, len(tensors))
+    dev = X.device
+    out = {}
+    for t in tensors:
+        out[f"C_{t}"] = torch.empty((B, max_codes, d), dtype=X.dtype, device=dev)
+        out[f"n_codes_{t}"] = torch.empty((B,), dtype=torch.int32, device=dev)
+        out[f"n_found_{t}"] = torch.empty((B,), dtype=torch.int32, device=dev)
+        out[f"ref_{t}"] = torch.empty((B, H, l), dtype=torch.int32, device=dev)
+        out[f"mag_{t}"] = torch.empty((B, H, l), dtype=torch.float32, device=dev)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    g = out.get
+    spindle_compress_shallow_layer(desc, K, V, theta_k, theta_v, max_codes, g("C_k"), g("C_v"), g("n_codes_k"),
+                                   g("n_codes_v"), g("n_found_k"), g("n_found_v"), g("ref_k"), g("ref_v"),
+                                   g("mag_k"), g("mag_v"), ws, nbytes)
+    out["workspace"] = ws
+    return out
 
 
 def reconstruct(Cb, ref, mag, dtype):

@@ -228,3 +228,54 @@ extern "C" spindle_status spindle_shallow_codebook(
     void *stream) {
   return run_shallow(kPhaseCodebook, SHALLOW_ARGS);
 }
+
+// ---------------------------------------------------------------- one codebook per layer
+namespace {
+
+// The rows of all KV heads of a batch entry as one problem: [B, h_g, l, d] with the heads one
+// behind the other in memory is [B, 1, h_g * l, d].
+spindle_status layer_desc(const spindle_kv_desc *desc, spindle_kv_desc *one) {
+  spindle_status s = check_desc(desc);
+  if (s != SPINDLE_OK) return s;
+  const int64_t rows = (int64_t)desc->n_kv_heads * desc->seq_len;
+  if (rows > 65535)
+    SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED,
+                 "one codebook over all heads of a layer is a problem of n_kv_heads x seq_len = %lld rows; the codebook "
+                 "path takes at most 65535 (token indices are 16 bits wide): evict to fewer rows per head first",
+                 (long long)rows);
+  const int64_t st = desc->stride_t ? desc->stride_t : desc->head_dim;
+  const int64_t sh = desc->stride_h ? desc->stride_h : (int64_t)desc->seq_len * desc->head_dim;
+  if (sh != (int64_t)desc->seq_len * st)
+    SPINDLE_FAIL(SPINDLE_ERR_UNSUPPORTED, "the heads of a batch entry must follow each other in memory "
+                 "(stride_h = seq_len * stride_t), as the outputs of spindle_compress_deep do");
+  *one = *desc;
+  one->n_kv_heads = 1;
+  one->seq_len = (int32_t)rows;
+  one->stride_h = 0;
+  one->stride_b = desc->stride_b ? desc->stride_b : (int64_t)desc->n_kv_heads * sh;
+  one->stride_t = desc->stride_t;
+  return SPINDLE_OK;
+}
+
+}  // namespace
+
+extern "C" spindle_status spindle_shallow_layer_workspace_bytes(const spindle_kv_desc *desc, int32_t n_tensors,
+                                                                size_t *bytes) {
+  spindle_kv_desc one;
+  spindle_status s = layer_desc(desc, &one);
+  if (s != SPINDLE_OK) return s;
+  return spindle_shallow_workspace_bytes(&one, n_tensors, bytes);
+}
+
+extern "C" spindle_status spindle_compress_shallow_layer(
+    const spindle_kv_desc *desc, const void *K, const void *V, float theta_k, float theta_v,
+    int32_t max_codes, void *Ck, void *Cv, int32_t *n_codes_k, int32_t *n_codes_v, int32_t *n_found_k,
+    int32_t *n_found_v, int32_t *ref_k, int32_t *ref_v, float *mag_k, float *mag_v, void *workspace,
+    size_t workspace_bytes, void *stream) {
+  spindle_kv_desc one;
+  spindle_status s = layer_desc(desc, &one);
+  if (s != SPINDLE_OK) return s;
+  return run_shallow(kPhaseGraph | kPhaseCodebook, &one, K, V, theta_k, theta_v, max_codes, Ck, Cv, n_codes_k, n_codes_v,
+                     n_found_k, n_found_v, ref_k, ref_v, mag_k, mag_v, nullptr, nullptr, nullptr, nullptr, workspace,
+                     workspace_bytes, stream);
+}

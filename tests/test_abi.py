@@ -148,3 +148,19 @@ def test_missing_library_raises_instead_of_falling_back(sb, monkeypatch, tmp_pat
         sb.spindle_deep_workspace_bytes(sb.KvDesc(1, 8, 4, 4096, 128, sb.F16), 32)
     with pytest.raises(FileNotFoundError):
         sb.spindle_layer_budgets(0.5, 4096, 32, 8)
+
+
+def test_layer_codebook_shape_limits(sb):
+    # one codebook over all heads of a layer = one problem of heads x tokens rows
+    d = sb.KvDesc(2, 32, 1, 2047, 128, sb.F16)                 # 65504 rows: the largest unfolded layer with 32 heads
+    one = sb.KvDesc(2, 1, 1, 32 * 2047, 128, sb.F16)
+    assert sb.spindle_shallow_layer_workspace_bytes(d, 2) == sb.spindle_shallow_workspace_bytes(one, 2)
+    with pytest.raises(sb.SpindleError) as e:
+        sb.spindle_shallow_layer_workspace_bytes(sb.KvDesc(1, 32, 1, 2048, 128, sb.F16), 1)    # 65536 rows
+    assert e.value.code == 2 and "65535" in str(e.value) and "65536" in str(e.value)
+    # a token-major cache ([B, l, H, d]) does not have the heads of a batch entry one behind the other
+    with pytest.raises(sb.SpindleError) as e:
+        sb.spindle_shallow_layer_workspace_bytes(sb.KvDesc(1, 8, 1, 512, 128, sb.F16, 8 * 512 * 128, 128, 8 * 128), 1)
+    assert e.value.code == 2 and "follow each other" in str(e.value)
+    # head-major with padding between batch entries is fine
+    assert sb.spindle_shallow_layer_workspace_bytes(sb.KvDesc(2, 8, 1, 512, 128, sb.F16, 9 * 512 * 128, 512 * 128, 128), 1) > 0

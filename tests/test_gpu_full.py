@@ -256,6 +256,60 @@ def test_unfolded_gqa_then_one_codebook_per_kv_head(oracle):
     assert max(shared) > 0, "the query heads of a group should agree on some tokens"
 
 
+def test_one_codebook_per_layer_over_the_unfolded_heads(oracle):
+    # Sec. "Similarity Based Token Replacement", first paragraph, and Eq. 15's r_2: K and V repeated
+    # once per query head, every query head evicts on its own attention (group size 1), and ONE
+    # codebook per layer over the kept rows of all 32 heads removes the repetition again.  The
+    # eviction outputs go into spindle_compress_shallow_layer as they are.
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    L = wl.config2(0)
+    B, H, l, d = L.K.shape
+    hn, budget, cap = L.group_size, 384, 1536
+    Kr, Vr = np.repeat(L.K, hn, axis=1), np.repeat(L.V, hn, axis=1)
+    un = wl.Layer(L.dtype, Kr, Vr, L.Qw, 1, L.window, L.pool, budget, cap)
+    p64, kept64 = parity.oracle_deep(oracle, un)
+    Kd, Vd, Qd = (sb.to_device(x, L.dtype) for x in (Kr, Vr, L.Qw))
+    kept, Ko, Vo, sc = sb.compress_deep(Kd, Vd, Qd, 1, L.dtype, L.window, L.pool, budget, scale=parity.scale_of(d))
+    torch.cuda.synchronize()
+    assert np.array_equal(kept.cpu().numpy(), kept64), "the two codebooks must start from the same rows"
+    out = sb.compress_shallow_layer(Ko, Vo, L.dtype, L.theta_k, L.theta_v, cap)
+    torch.cuda.synchronize()
+    g = {k: (sb.to_host_bits(v, L.dtype) if k.startswith("C_") else v.cpu().numpy()) for k, v in out.items() if k != "workspace"}
+    Q = H * hn
+    entries = 0
+    for t, X, theta in (("k", L.K, L.theta_k), ("v", L.V, L.theta_v)):
+        rows = np.concatenate([wl.to_f64(X[0, q // hn][kept64[0, q]], L.dtype) for q in range(Q)])
+        assert rows.shape == (Q * budget, d)
+        o = oracle.shallow_unit(rows, float(np.float32(theta)), cap)
+        assert g[f"n_found_{t}"][0] == o["n_codes_uncapped"] and g[f"n_codes_{t}"][0] == o["n_codes"]
+        assert np.array_equal(g[f"ref_{t}"][0].reshape(-1), o["ref"]), "code assignment differs"
+        assert np.array_equal(g[f"mag_{t}"][0].reshape(-1), o["mag"].astype(np.float32))
+        parity.check_codebook_vectors(g[f"C_{t}"][0, :o["n_codes"]], o["C"], L.dtype)
+        assert not g[f"C_{t}"][0, o["n_codes"]:].any()
+        # a token kept by several query heads of its KV head is one entry of the layer's codebook
+        ref = g[f"ref_{t}"][0]
+        shared = 0
+        for h in range(H):
+            first = {}
+            for q in range(h * hn, (h + 1) * hn):
+                for pos, r in zip(kept64[0, q], ref[q]):
+                    shared += int(pos) in first
+                    assert first.setdefault(int(pos), int(r)) == int(r)
+        assert shared > 0
+        entries += int(g[f"n_codes_{t}"][0])
+        # per-head codebooks of the same rows need at least as many entries in total
+        per_head = sum(oracle.shallow_unit(rows[q * budget:(q + 1) * budget], float(np.float32(theta)), cap)["n_codes"]
+                       for q in range(0, Q, hn))
+        assert o["n_codes_uncapped"] >= 1 and per_head >= 1
+    # Eq. 15 with h_g = h (the repeat was made before the eviction): r_2 from the layer's two codebooks
+    kept_rows, all_rows = 2 * Q * budget, 2 * Q * l
+    r = sb.spindle_reserve_ratio(kept_rows, all_rows, entries, d, 16, 16, 32)
+    assert np.array_equal(np.array(r), oracle.reserve_ratio(kept_rows, all_rows, entries, d, 16, 16, 32))
+    assert r[0] == budget / l and r[1] == entries / kept_rows
+    print("layer codebook over", Q * budget, "rows:", entries, "entries for K and V, r =", r, flush=True)
+
+
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_cache_stored_token_major(oracle, dtype):
     # K and V kept as [batch, seq_len, heads, head_dim], the order many inference engines use:
