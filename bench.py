@@ -418,6 +418,17 @@ def main():
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F16_TFLOPS,
                      "traffic": traffic, "traffic_source": traffic_source},
     }
+    # what the part sustains (measurement aids of the library): a register-resident fp16 MFMA loop, and
+    # the similarity kernel's own loop with the packing of the results left out
+    if not args.no_extras:
+        bare = [sb.spindle_calibrate_similarity(shallow) for _ in range(5)][1:]
+        mfma = max(sb.spindle_calibrate_mfma(4096) for _ in range(3))
+        out["roofline"]["calibration"] = {
+            "mfma_f16_register_loop_tflops": mfma, "mfma_f16_register_loop_frac_of_peak": mfma / PEAK_MFMA_F16_TFLOPS,
+            "similarity_loop_without_packing_ms": float(np.mean(bare)),
+            "similarity_loop_without_packing_frac_of_peak": gram_flop / (float(np.mean(bare)) * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS,
+            "note": "the kernel's matrix instructions, staging and barriers alone; what is left between this and "
+                    "roofline.frac is the vector work on the results"}
     # secondary: the eviction call against the HBM roofline, timed on its own without events between
     # its kernels (deep_ms above is the breakdown pass, where every kernel is followed by an event gap)
     esz = K.element_size()

@@ -387,6 +387,23 @@ spindle_status spindle_profile(int32_t enable);
  */
 int32_t spindle_profile_read(char *names, float *ms, int32_t max);
 
+/*
+ * What this GPU sustains, for reading the roofline figures (neither computes anything the method
+ * needs; both enqueue on `stream`, wait for it and time with a pair of HIP events):
+ *   spindle_calibrate_mfma        four independent chains of `iters` v_mfma_f32_32x32x16_f16 per
+ *                                 wave, eight waves per compute unit, operands in registers: the
+ *                                 rate of the matrix cores with no memory traffic and no other
+ *                                 work, in TFLOP/s.
+ *   spindle_calibrate_similarity  the similarity kernel of spindle_compress_shallow run again on
+ *                                 the unit vectors an earlier call with the same desc and n_tensors
+ *                                 left in `workspace`, with the same staging, barriers and matrix
+ *                                 instructions but without the packing of the results, and
+ *                                 nothing written: its duration in milliseconds.
+ */
+spindle_status spindle_calibrate_mfma(int32_t iters, void *stream, double *tflops);
+spindle_status spindle_calibrate_similarity(const spindle_kv_desc *desc, int32_t n_tensors, void *workspace,
+                                            size_t workspace_bytes, void *stream, double *ms);
+
 /* ------------------------------------------------------------------------- */
 
 /* Thread-local message of the last failing call on this thread ("" if none). */

@@ -27,12 +27,13 @@ _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
            "spindle_compress_shallow", "spindle_shallow_graph", "spindle_shallow_codebook",
            "spindle_shallow_layer_workspace_bytes", "spindle_compress_shallow_layer",
+           "spindle_calibrate_mfma", "spindle_calibrate_similarity",
            "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
            "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_decode_workspace_bytes", "spindle_decode_merge",
            "spindle_decode_merge_static",
            "spindle_profile_read", "spindle_decode_static_capacity",
            "spindle_last_error", "spindle_version"]
-N_STATUS = 16
+N_STATUS = 18
 
 
 class KvDesc(C.Structure):
@@ -66,6 +67,8 @@ def lib():
             fn.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 14 + [vp, sz, vp]
         L.spindle_shallow_layer_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_compress_shallow_layer.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 10 + [vp, sz, vp]
+        L.spindle_calibrate_mfma.argtypes = [i32, vp, C.POINTER(C.c_double)]
+        L.spindle_calibrate_similarity.argtypes = [C.POINTER(KvDesc), i32, vp, sz, vp, C.POINTER(C.c_double)]
         L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.spindle_profile.argtypes = [i32]
         L.spindle_profile_read.argtypes = [C.c_char_p, C.POINTER(C.c_float), i32]
@@ -495,6 +498,23 @@ def compress_shallow_layer(K, V, dtype, theta_k, theta_v, max_codes):
                                    g("mag_k"), g("mag_v"), ws, nbytes)
     out["workspace"] = ws
     return out
+
+
+def spindle_calibrate_mfma(iters: int = 4096, stream=None) -> float:
+    """TFLOP/s of a register-resident fp16 MFMA loop on the whole chip (measurement aid)."""
+    out = C.c_double(0.0)
+    _check(lib().spindle_calibrate_mfma(int(iters), stream or _stream(), C.byref(out)))
+    return out.value
+
+
+def spindle_calibrate_similarity(plan: "ShallowPlan", stream=None) -> float:
+    """Milliseconds of the similarity kernel's loop without its packing, on the unit vectors the
+    plan's last run left in its workspace (measurement aid)."""
+    out = C.c_double(0.0)
+    n_t = sum(1 for k in plan.out if k.startswith("ref_"))
+    _check(lib().spindle_calibrate_similarity(C.byref(plan.desc), n_t, _ptr(plan.ws), int(plan.ws_bytes),
+                                              stream or _stream(), C.byref(out)))
+    return out.value
 
 
 def reconstruct(Cb, ref, mag, dtype):

@@ -168,6 +168,64 @@ extern "C" spindle_status spindle_reserve_ratio(int64_t kept_tokens, int64_t tot
   return SPINDLE_OK;
 }
 
+// ---------------------------------------------------------------- measurement aids
+namespace spindle {
+// (external linkage on purpose: a variable nobody can read would be removed together with
+// everything that leads up to the store)
+__device__ float g_cal_sink;
+namespace {
+
+// Four independent chains of v_mfma_f32_32x32x16_f16 per wave on operands that never leave the
+// registers: what the matrix cores sustain with no memory traffic and no other work.
+__global__ __launch_bounds__(256) void cal_mfma_f16(int iters) {
+  h8 a[4], b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    b[i] = (_Float16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) a[ch][i] = (_Float16)(0.001f * (float)((threadIdx.x + i + 5 * ch) & 15));
+  }
+  f16v c[4];
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) c[ch][v] = (float)ch;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) c[ch] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ch], b, c[ch], 0, 0, 0);
+  }
+  const float sum = c[0][0] + c[1][5] + c[2][9] + c[3][15];
+  if (sum == -1.2345f) g_cal_sink = sum;               // never: no term is negative
+}
+
+}  // namespace
+}  // namespace spindle
+
+extern "C" spindle_status spindle_calibrate_mfma(int32_t iters, void *stream, double *tflops) {
+  if (!tflops || iters < 1) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tflops is required and iters must be >= 1");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipDeviceProp_t prop;
+  int dev = 0;
+  SPINDLE_HIP(hipGetDevice(&dev));
+  SPINDLE_HIP(hipGetDeviceProperties(&prop, dev));
+  const int blocks = prop.multiProcessorCount * 2;      // 8 waves per compute unit: two per SIMD
+  hipEvent_t e0, e1;
+  SPINDLE_HIP(hipEventCreate(&e0));
+  SPINDLE_HIP(hipEventCreate(&e1));
+  hipLaunchKernelGGL(spindle::cal_mfma_f16, dim3(blocks), dim3(256), 0, st, iters);     // warm-up
+  SPINDLE_HIP(hipEventRecord(e0, st));
+  hipLaunchKernelGGL(spindle::cal_mfma_f16, dim3(blocks), dim3(256), 0, st, iters);
+  SPINDLE_HIP(hipEventRecord(e1, st));
+  SPINDLE_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  SPINDLE_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  const double flop = (double)blocks * 4.0 * (double)iters * 4.0 * 2.0 * 32.0 * 32.0 * 16.0;
+  *tflops = flop / ((double)ms * 1e-3) / 1e12;
+  return SPINDLE_OK;
+}
+
 extern "C" const char *spindle_last_error(void) { return spindle::g_error; }
 
 extern "C" uint32_t spindle_version(void) { return (0u << 16) | 1u; }

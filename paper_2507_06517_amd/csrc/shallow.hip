@@ -279,3 +279,36 @@ extern "C" spindle_status spindle_compress_shallow_layer(
                      n_found_k, n_found_v, ref_k, ref_v, mag_k, mag_v, nullptr, nullptr, nullptr, nullptr, workspace,
                      workspace_bytes, stream);
 }
+
+// ---------------------------------------------------------------- measurement aid
+extern "C" spindle_status spindle_calibrate_similarity(const spindle_kv_desc *desc, int32_t n_tensors, void *workspace,
+                                                       size_t workspace_bytes, void *stream, double *ms_out) {
+  size_t need = 0;
+  spindle_status s = spindle_shallow_workspace_bytes(desc, n_tensors, &need);
+  if (s != SPINDLE_OK) return s;
+  if (!ms_out) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "ms is NULL");
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ShallowParams p;
+  memset(&p, 0, sizeof(p));
+  p.dtype = desc->dtype; p.U = desc->batch * desc->n_kv_heads; p.UT = p.U * n_tensors; p.n = desc->seq_len;
+  if ((s = kv_layout(desc, &p.lay)) != SPINDLE_OK) return s;
+  p.theta[0] = p.theta[1] = 0.98f;
+  carve(p, workspace, p.UT, p.n);
+  hipEvent_t e0, e1;
+  SPINDLE_HIP(hipEventCreate(&e0));
+  SPINDLE_HIP(hipEventCreate(&e1));
+  SPINDLE_HIP(hipEventRecord(e0, st));
+  s = launch_bare_similarity(p, st);
+  if (s == SPINDLE_OK) {
+    SPINDLE_HIP(hipEventRecord(e1, st));
+    SPINDLE_HIP(hipEventSynchronize(e1));
+    float ms = 0.f;
+    SPINDLE_HIP(hipEventElapsedTime(&ms, e0, e1));
+    *ms_out = ms;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return s;
+}

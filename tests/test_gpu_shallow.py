@@ -229,3 +229,21 @@ def test_deterministic_across_runs():
     b = parity.gpu_shallow(L)
     for k in a:
         assert np.array_equal(a[k], b[k]), k
+
+
+def test_measurement_aids_run_and_leave_results_alone():
+    # the two calibration calls compute nothing the method needs; they must run, report sane
+    # figures and not disturb a later call on the same workspace
+    import torch
+    from paper_2507_06517_amd import binding as sb
+    L = wl.config2(3)
+    K, V = sb.to_device(L.K, L.dtype), sb.to_device(L.V, L.dtype)
+    plan = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)
+    a = {k: v.clone() for k, v in plan.run(K, V).items()}
+    ms = sb.spindle_calibrate_similarity(plan)
+    tf = sb.spindle_calibrate_mfma(512)
+    assert 0.0 < ms < 50.0 and 50.0 < tf < 2600.0, (ms, tf)
+    b = plan.run(K, V)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), k
