@@ -769,6 +769,7 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force)
 // shallow_mirror and shallow_lists then redo everything from the bitmap.
 constexpr int kEdgeThreads = 1024;
 constexpr int kEdgeLds = 128;                      // list entries per row collected in LDS; later ones go straight to memory
+constexpr int kSegList = 1280;                     // segments a panel may have to visit at 65535 tokens: 4 x 64 + 16 x 63
 
 // kCap: the segment capacity when it is the smallest one (long sequences), else 0 = read it from
 // the parameters; with the constant the compiler unrolls the record loop and batches its loads
@@ -777,6 +778,8 @@ template <int kCap>
 __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams p, int force) {
   __shared__ int cursor[kPanelRows];
   __shared__ __attribute__((aligned(16))) uint16_t part[kPanelRows][kEdgeLds];
+  __shared__ uint32_t full[kSegList];                // segments that hold records: index << 16 | count
+  __shared__ int nfull;
   if (force || *p.need_full != 0) return;
   const int n = p.n, ut = blockIdx.y;
   const int nI = (n + kPanelRows - 1) / kPanelRows, nJc = (n + kChunkCols - 1) / kChunkCols;
@@ -785,6 +788,7 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
   const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
   uint16_t *lists = p.nbr + ((size_t)ut * n + row0) * kListCap;
   if (tid < kPanelRows) cursor[tid] = 0;
+  if (tid == 0) nfull = 0;
   __syncthreads();
   auto add = [&](int row, int other) {
     const int r = row - row0;
@@ -794,24 +798,46 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
   };
   const int nown = 4 * (nJc - Jm);                   // (chunk, wave) segments of this panel
   const int nin = 16 * Jm;                           // (panel, wave) segments of earlier tiles for this tile's chunk
+  auto seg_of = [&](int k) -> size_t {
+    const bool own = k < nown;
+    const int kk = own ? k : k - nown;
+    const int J = own ? Jm + (kk >> 2) : Jm;
+    const int Ip = own ? I : kk >> 2;
+    return (((size_t)ut * nJc + J) * nI + Ip) * 4 + (kk & 3);
+  };
+  // The kernel is bound by the latency of dependent loads (a segment's count, then its records),
+  // and most segments are empty: all counts are fetched in one go, the segments that hold
+  // records are listed in LDS, and only those are visited, several per wave in flight.
+  for (int k = tid; k < nown + nin; k += kEdgeThreads) {
+    const unsigned cn = p.ecount[seg_of(k)];
+    if (cn) {
+      const int at = atomicAdd(&nfull, 1);
+      if (at < kSegList) full[at] = ((uint32_t)k << 16) | (cn < 0xFFFFu ? cn : 0xFFFFu);
+    }
+  }
+  __syncthreads();
+  const int nlisted = nfull < kSegList ? nfull : kSegList;
+  const bool listed = nfull <= kSegList;             // else (never seen): every segment is visited
+  const int nvisit = listed ? nlisted : nown + nin;
   constexpr int kBatch = 4;                          // segments a wave has in flight
-  for (int k0 = wave * kBatch; k0 < nown + nin; k0 += (kEdgeThreads / 64) * kBatch) {
+  for (int k0 = wave * kBatch; k0 < nvisit; k0 += (kEdgeThreads / 64) * kBatch) {
     const uint32_t *e[kBatch];
     int cnt[kBatch];
     bool own[kBatch];
     int most = 0;
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
-      const int k = k0 + u;
+      const int v = k0 + u;
+      int k = v;
+      unsigned cn = 0;
+      if (v < nvisit) {
+        if (listed) { const uint32_t f = full[v]; k = (int)(f >> 16); cn = f & 0xFFFFu; }
+        else cn = p.ecount[seg_of(k)];
+      }
       own[u] = k < nown;
-      const int kk = own[u] ? k : k - nown;
-      const int J = own[u] ? Jm + (kk >> 2) : Jm;
-      const int Ip = own[u] ? I : kk >> 2;
-      const size_t seg = (((size_t)ut * nJc + J) * nI + Ip) * 4 + (kk & 3);
-      const unsigned cn = k < nown + nin ? p.ecount[seg] : 0u;
       const int cap = kCap ? kCap : p.seg_cap;
       cnt[u] = cn < (unsigned)cap ? (int)cn : cap;
-      e[u] = p.edges + seg * cap;
+      e[u] = p.edges + seg_of(v < nvisit ? k : 0) * cap;
       most = cnt[u] > most ? cnt[u] : most;
     }
     for (int i0 = 0; i0 < most; i0 += kWave) {
