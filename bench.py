@@ -260,7 +260,7 @@ def main():
                          "(half of the tokens isolated noise, codebook cut to --cap): a secondary figure")
     ap.add_argument("--cap", type=int, default=4096, help="budget = codebook cap of --workload config5")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (scale reference for the HBM traffic counters)")
+                    help="run the plain 1 GiB copy (scale reference for the HBM traffic counters) even with --no-extras")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (folded eviction call, config-5 layer, reconstruction, decode)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "shallow_gram_config4_traffic.json"))
@@ -303,10 +303,13 @@ def main():
     for _ in range(args.warmup):
         step()
     drain()
-    if args.calibrate_copy:
+    copy_gbs = None
+    if args.calibrate_copy or not args.no_extras:
+        # a plain 1 GiB copy by the library's own kernel (`cal_copy` in a profile): what the memory system
+        # sustains, and the known size the HBM traffic counters are scaled by
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        copy_gbs = sb.spindle_calibrate_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
 
@@ -420,6 +423,9 @@ def main():
     }
     # what the part sustains (measurement aids of the library): a register-resident fp16 MFMA loop, and
     # the similarity kernel's own loop with the packing of the results left out
+    if copy_gbs is not None:
+        out["hbm_copy_measured"] = {"gb_per_s_read_plus_write": copy_gbs, "frac_of_peak": copy_gbs / PEAK_HBM_GBS,
+                                    "bytes": 2 << 30}
     if not args.no_extras:
         bare = [sb.spindle_calibrate_similarity(shallow) for _ in range(5)][1:]
         mfma = max(sb.spindle_calibrate_mfma(4096) for _ in range(3))

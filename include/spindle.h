@@ -401,6 +401,11 @@ int32_t spindle_profile_read(char *names, float *ms, int32_t max);
  *                                 nothing written: its duration in milliseconds.
  */
 spindle_status spindle_calibrate_mfma(int32_t iters, void *stream, double *tflops);
+/*   spindle_calibrate_copy        a plain copy of `bytes` from src to dst (device buffers, 16-byte
+ *                                 aligned), run twice and the second timed: bytes read plus bytes
+ *                                 written per second, in GB/s; its known size is also what the HBM
+ *                                 traffic counters of a profiler run are scaled by. */
+spindle_status spindle_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream, double *gbs);
 spindle_status spindle_calibrate_similarity(const spindle_kv_desc *desc, int32_t n_tensors, void *workspace,
                                             size_t workspace_bytes, void *stream, double *ms);
 

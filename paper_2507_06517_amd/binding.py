@@ -27,13 +27,13 @@ _DT = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = ["spindle_deep_workspace_bytes", "spindle_compress_deep", "spindle_shallow_workspace_bytes",
            "spindle_compress_shallow", "spindle_shallow_graph", "spindle_shallow_codebook",
            "spindle_shallow_layer_workspace_bytes", "spindle_compress_shallow_layer",
-           "spindle_calibrate_mfma", "spindle_calibrate_similarity",
+           "spindle_calibrate_mfma", "spindle_calibrate_similarity", "spindle_calibrate_copy",
            "spindle_shallow_stats", "spindle_reconstruct", "spindle_profile",
            "spindle_layer_budgets", "spindle_reserve_ratio", "spindle_decode_workspace_bytes", "spindle_decode_merge",
            "spindle_decode_merge_static",
            "spindle_profile_read", "spindle_decode_static_capacity",
            "spindle_last_error", "spindle_version"]
-N_STATUS = 18
+N_STATUS = 19
 
 
 class KvDesc(C.Structure):
@@ -68,6 +68,7 @@ def lib():
         L.spindle_shallow_layer_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_compress_shallow_layer.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 10 + [vp, sz, vp]
         L.spindle_calibrate_mfma.argtypes = [i32, vp, C.POINTER(C.c_double)]
+        L.spindle_calibrate_copy.argtypes = [vp, vp, sz, vp, C.POINTER(C.c_double)]
         L.spindle_calibrate_similarity.argtypes = [C.POINTER(KvDesc), i32, vp, sz, vp, C.POINTER(C.c_double)]
         L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.spindle_profile.argtypes = [i32]
@@ -504,6 +505,14 @@ def spindle_calibrate_mfma(iters: int = 4096, stream=None) -> float:
     """TFLOP/s of a register-resident fp16 MFMA loop on the whole chip (measurement aid)."""
     out = C.c_double(0.0)
     _check(lib().spindle_calibrate_mfma(int(iters), stream or _stream(), C.byref(out)))
+    return out.value
+
+
+def spindle_calibrate_copy(src, dst, stream=None) -> float:
+    """GB/s (read + written) of a plain copy of src into dst (same-size device tensors; measurement aid)."""
+    out = C.c_double(0.0)
+    _check(lib().spindle_calibrate_copy(_ptr(src), _ptr(dst), int(src.numel() * src.element_size()),
+                                        stream or _stream(), C.byref(out)))
     return out.value
 
 

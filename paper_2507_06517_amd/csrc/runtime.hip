@@ -198,8 +198,39 @@ __global__ __launch_bounds__(256) void cal_mfma_f16(int iters) {
   if (sum == -1.2345f) g_cal_sink = sum;               // never: no term is negative
 }
 
+// Plain copy, 16 bytes per thread and trip: the scale reference for the HBM traffic counters
+// and the copy rate the memory system sustains.
+__global__ __launch_bounds__(256) void cal_copy(const u4 *__restrict__ src, u4 *__restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
 }  // namespace spindle
+
+extern "C" spindle_status spindle_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream, double *gbs) {
+  if (!src || !dst || !gbs || bytes < 16 || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15))
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "src, dst (16-byte aligned device buffers), bytes >= 16 and gbs are required");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t n16 = bytes / 16;
+  const int blocks = (int)(n16 / 256 < 16384 ? (n16 + 255) / 256 : 16384);
+  hipEvent_t e0, e1;
+  SPINDLE_HIP(hipEventCreate(&e0));
+  SPINDLE_HIP(hipEventCreate(&e1));
+  hipLaunchKernelGGL(spindle::cal_copy, dim3(blocks), dim3(256), 0, st, static_cast<const spindle::u4 *>(src),
+                     static_cast<spindle::u4 *>(dst), n16);                                  // warm-up
+  SPINDLE_HIP(hipEventRecord(e0, st));
+  hipLaunchKernelGGL(spindle::cal_copy, dim3(blocks), dim3(256), 0, st, static_cast<const spindle::u4 *>(src),
+                     static_cast<spindle::u4 *>(dst), n16);
+  SPINDLE_HIP(hipEventRecord(e1, st));
+  SPINDLE_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  SPINDLE_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  *gbs = 2.0 * (double)(n16 * 16) / ((double)ms * 1e-3) / 1e9;
+  return SPINDLE_OK;
+}
 
 extern "C" spindle_status spindle_calibrate_mfma(int32_t iters, void *stream, double *tflops) {
   if (!tflops || iters < 1) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tflops is required and iters must be >= 1");
