@@ -429,8 +429,11 @@ def main():
     if not args.no_extras:
         bare = [sb.spindle_calibrate_similarity(shallow) for _ in range(5)][1:]
         mfma = max(sb.spindle_calibrate_mfma(4096) for _ in range(3))
+        mfma_data = max(sb.spindle_calibrate_mfma(4096, 1) for _ in range(3))
         out["roofline"]["calibration"] = {
             "mfma_f16_register_loop_tflops": mfma, "mfma_f16_register_loop_frac_of_peak": mfma / PEAK_MFMA_F16_TFLOPS,
+            "mfma_f16_register_loop_workload_like_operands_tflops": mfma_data,
+            "mfma_f16_register_loop_workload_like_operands_frac_of_peak": mfma_data / PEAK_MFMA_F16_TFLOPS,
             "similarity_loop_without_packing_ms": float(np.mean(bare)),
             "similarity_loop_without_packing_frac_of_peak": gram_flop / (float(np.mean(bare)) * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS,
             "note": "the kernel's matrix instructions, staging and barriers alone; what is left between this and "

@@ -393,14 +393,18 @@ int32_t spindle_profile_read(char *names, float *ms, int32_t max);
  *   spindle_calibrate_mfma        four independent chains of `iters` v_mfma_f32_32x32x16_f16 per
  *                                 wave, eight waves per compute unit, operands in registers: the
  *                                 rate of the matrix cores with no memory traffic and no other
- *                                 work, in TFLOP/s.
+ *                                 work, in TFLOP/s.  `pattern` 0: small non-negative operand
+ *                                 values (few bits switch between instructions); 1: pseudo-random
+ *                                 values with the signs and magnitudes of the similarity kernel's
+ *                                 operands, which draw more power per instruction and so show the
+ *                                 clock the part sustains on such data.
  *   spindle_calibrate_similarity  the similarity kernel of spindle_compress_shallow run again on
  *                                 the unit vectors an earlier call with the same desc and n_tensors
  *                                 left in `workspace`, with the same staging, barriers and matrix
  *                                 instructions but without the packing of the results, and
  *                                 nothing written: its duration in milliseconds.
  */
-spindle_status spindle_calibrate_mfma(int32_t iters, void *stream, double *tflops);
+spindle_status spindle_calibrate_mfma(int32_t iters, int32_t pattern, void *stream, double *tflops);
 /*   spindle_calibrate_copy        a plain copy of `bytes` from src to dst (device buffers, 16-byte
  *                                 aligned), run twice and the second timed: bytes read plus bytes
  *                                 written per second, in GB/s; its known size is also what the HBM

@@ -67,7 +67,7 @@ def lib():
             fn.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 14 + [vp, sz, vp]
         L.spindle_shallow_layer_workspace_bytes.argtypes = [C.POINTER(KvDesc), i32, C.POINTER(sz)]
         L.spindle_compress_shallow_layer.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 10 + [vp, sz, vp]
-        L.spindle_calibrate_mfma.argtypes = [i32, vp, C.POINTER(C.c_double)]
+        L.spindle_calibrate_mfma.argtypes = [i32, i32, vp, C.POINTER(C.c_double)]
         L.spindle_calibrate_copy.argtypes = [vp, vp, sz, vp, C.POINTER(C.c_double)]
         L.spindle_calibrate_similarity.argtypes = [C.POINTER(KvDesc), i32, vp, sz, vp, C.POINTER(C.c_double)]
         L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
@@ -501,10 +501,11 @@ def compress_shallow_layer(K, V, dtype, theta_k, theta_v, max_codes):
     return out
 
 
-def spindle_calibrate_mfma(iters: int = 4096, stream=None) -> float:
-    """TFLOP/s of a register-resident fp16 MFMA loop on the whole chip (measurement aid)."""
+def spindle_calibrate_mfma(iters: int = 4096, pattern: int = 0, stream=None) -> float:
+    """TFLOP/s of a register-resident fp16 MFMA loop on the whole chip (measurement aid); pattern 1 =
+    operands with the signs and magnitudes of the similarity kernel's."""
     out = C.c_double(0.0)
-    _check(lib().spindle_calibrate_mfma(int(iters), stream or _stream(), C.byref(out)))
+    _check(lib().spindle_calibrate_mfma(int(iters), int(pattern), stream or _stream(), C.byref(out)))
     return out.value
 
 

@@ -176,15 +176,31 @@ __device__ float g_cal_sink;
 namespace {
 
 // Four independent chains of v_mfma_f32_32x32x16_f16 per wave on operands that never leave the
-// registers: what the matrix cores sustain with no memory traffic and no other work.
-__global__ __launch_bounds__(256) void cal_mfma_f16(int iters) {
-  h8 a[4], b;
+// registers: what the matrix cores sustain with no memory traffic and no other work.  The power
+// a matrix instruction draws, and with it the clock the part sustains, depends on how many operand
+// bits change from one instruction to the next: pattern 0 = small non-negative values (few bits set,
+// little switching), pattern 1 = pseudo-random values with the sign mix and magnitude of the
+// similarity kernel's operands (unit vectors of 128 dimensions scaled by 2^10), different for
+// every chain on both sides.
+__global__ __launch_bounds__(256) void cal_mfma_f16(int iters, int pattern) {
+  h8 a[4], b[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    b[i] = (_Float16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
+  for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
-    for (int ch = 0; ch < 4; ++ch) a[ch][i] = (_Float16)(0.001f * (float)((threadIdx.x + i + 5 * ch) & 15));
-  }
+    for (int i = 0; i < 8; ++i) {
+      if (pattern == 0) {
+        a[ch][i] = (_Float16)(0.001f * (float)((threadIdx.x + i + 5 * ch) & 15));
+        b[ch][i] = (_Float16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
+      } else {
+        uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 64u + (uint32_t)(ch * 16 + i);
+        h = (h ^ 61u) ^ (h >> 16); h *= 9u; h ^= h >> 4; h *= 0x27d4eb2du; h ^= h >> 15;   // integer mix
+        // sum of four uniform bytes, centred: roughly normal, standard deviation 90 = 2^10 / sqrt(128)
+        const float ga = ((float)(h & 255u) + (float)((h >> 8) & 255u) - 255.f) * 0.864f;
+        const float gb = ((float)((h >> 16) & 255u) + (float)(h >> 24) - 255.f) * 0.864f;
+        a[ch][i] = (_Float16)ga;
+        b[ch][i] = (_Float16)gb;
+      }
+    }
   f16v c[4];
 #pragma unroll
   for (int ch = 0; ch < 4; ++ch)
@@ -192,10 +208,10 @@ __global__ __launch_bounds__(256) void cal_mfma_f16(int iters) {
     for (int v = 0; v < 16; ++v) c[ch][v] = (float)ch;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int ch = 0; ch < 4; ++ch) c[ch] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ch], b, c[ch], 0, 0, 0);
+    for (int ch = 0; ch < 4; ++ch) c[ch] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ch], b[ch], c[ch], 0, 0, 0);
   }
   const float sum = c[0][0] + c[1][5] + c[2][9] + c[3][15];
-  if (sum == -1.2345f) g_cal_sink = sum;               // never: no term is negative
+  if (sum == -1.2345e30f) g_cal_sink = sum;            // never reached with these operands
 }
 
 // Plain copy, 16 bytes per thread and trip: the scale reference for the HBM traffic counters
@@ -232,8 +248,9 @@ extern "C" spindle_status spindle_calibrate_copy(const void *src, void *dst, siz
   return SPINDLE_OK;
 }
 
-extern "C" spindle_status spindle_calibrate_mfma(int32_t iters, void *stream, double *tflops) {
-  if (!tflops || iters < 1) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tflops is required and iters must be >= 1");
+extern "C" spindle_status spindle_calibrate_mfma(int32_t iters, int32_t pattern, void *stream, double *tflops) {
+  if (!tflops || iters < 1 || pattern < 0 || pattern > 1)
+    SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "tflops is required, iters must be >= 1 and pattern 0 or 1");
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipDeviceProp_t prop;
   int dev = 0;
@@ -243,9 +260,9 @@ extern "C" spindle_status spindle_calibrate_mfma(int32_t iters, void *stream, do
   hipEvent_t e0, e1;
   SPINDLE_HIP(hipEventCreate(&e0));
   SPINDLE_HIP(hipEventCreate(&e1));
-  hipLaunchKernelGGL(spindle::cal_mfma_f16, dim3(blocks), dim3(256), 0, st, iters);     // warm-up
+  hipLaunchKernelGGL(spindle::cal_mfma_f16, dim3(blocks), dim3(256), 0, st, iters, pattern);     // warm-up
   SPINDLE_HIP(hipEventRecord(e0, st));
-  hipLaunchKernelGGL(spindle::cal_mfma_f16, dim3(blocks), dim3(256), 0, st, iters);
+  hipLaunchKernelGGL(spindle::cal_mfma_f16, dim3(blocks), dim3(256), 0, st, iters, pattern);
   SPINDLE_HIP(hipEventRecord(e1, st));
   SPINDLE_HIP(hipEventSynchronize(e1));
   float ms = 0.f;

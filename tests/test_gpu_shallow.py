@@ -242,7 +242,8 @@ def test_measurement_aids_run_and_leave_results_alone():
     a = {k: v.clone() for k, v in plan.run(K, V).items()}
     ms = sb.spindle_calibrate_similarity(plan)
     tf = sb.spindle_calibrate_mfma(512)
-    assert 0.0 < ms < 50.0 and 50.0 < tf < 2600.0, (ms, tf)
+    tf_data = sb.spindle_calibrate_mfma(512, 1)
+    assert 0.0 < ms < 50.0 and 50.0 < tf < 2600.0 and 50.0 < tf_data < 2600.0, (ms, tf, tf_data)
     b = plan.run(K, V)
     torch.cuda.synchronize()
     for k in a:
