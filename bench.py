@@ -261,6 +261,8 @@ def main():
     ap.add_argument("--cap", type=int, default=4096, help="budget = codebook cap of --workload config5")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run the plain 1 GiB copy (scale reference for the HBM traffic counters) even with --no-extras")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="run the library's matrix-core and similarity-loop calibrations even with --no-extras")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (folded eviction call, config-5 layer, reconstruction, decode)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "shallow_gram_config4_traffic.json"))
@@ -426,8 +428,10 @@ def main():
     if copy_gbs is not None:
         out["hbm_copy_measured"] = {"gb_per_s_read_plus_write": copy_gbs, "frac_of_peak": copy_gbs / PEAK_HBM_GBS,
                                     "bytes": 2 << 30}
-    if not args.no_extras:
+    if args.calibrate or not args.no_extras:
         bare = [sb.spindle_calibrate_similarity(shallow) for _ in range(5)][1:]
+        bare_nostream = float(np.mean([sb.spindle_calibrate_similarity(shallow, 1) for _ in range(4)][1:]))
+        bare_mfma = float(np.mean([sb.spindle_calibrate_similarity(shallow, 2) for _ in range(4)][1:]))
         mfma = max(sb.spindle_calibrate_mfma(4096) for _ in range(3))
         mfma_data = max(sb.spindle_calibrate_mfma(4096, 1) for _ in range(3))
         out["roofline"]["calibration"] = {
@@ -436,8 +440,13 @@ def main():
             "mfma_f16_register_loop_workload_like_operands_frac_of_peak": mfma_data / PEAK_MFMA_F16_TFLOPS,
             "similarity_loop_without_packing_ms": float(np.mean(bare)),
             "similarity_loop_without_packing_frac_of_peak": gram_flop / (float(np.mean(bare)) * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS,
-            "note": "the kernel's matrix instructions, staging and barriers alone; what is left between this and "
-                    "roofline.frac is the vector work on the results"}
+            "similarity_loop_without_packing_and_streaming_loads_ms": bare_nostream,
+            "similarity_loop_matrix_instructions_only_ms": bare_mfma,
+            "similarity_loop_matrix_instructions_only_frac_of_peak": gram_flop / (bare_mfma * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS,
+            "note": "without packing: the kernel's matrix instructions, staging and barriers alone; what is left "
+                    "between this and roofline.frac is the vector work on the results.  The next two leave out the "
+                    "loads that stream tokens into LDS, then also the fragment reads: the part is power-limited, "
+                    "and each of these draws from the same budget as the matrix instructions"}
     # secondary: the eviction call against the HBM roofline, timed on its own without events between
     # its kernels (deep_ms above is the breakdown pass, where every kernel is followed by an event gap)
     esz = K.element_size()

@@ -402,7 +402,13 @@ int32_t spindle_profile_read(char *names, float *ms, int32_t max);
  *                                 the unit vectors an earlier call with the same desc and n_tensors
  *                                 left in `workspace`, with the same staging, barriers and matrix
  *                                 instructions but without the packing of the results, and
- *                                 nothing written: its duration in milliseconds.
+ *                                 nothing written: its duration in milliseconds.  `mode` 0: as
+ *                                 just said; 1: also without the loads that stream a chunk's
+ *                                 tokens into LDS after its first two stages (the matrix
+ *                                 instructions keep reading the same staged tokens); 2: matrix
+ *                                 instructions only, both operands from registers.  The three
+ *                                 show what the vector work, the streaming and the fragment
+ *                                 reads each cost beside the matrix instructions.
  */
 spindle_status spindle_calibrate_mfma(int32_t iters, int32_t pattern, void *stream, double *tflops);
 /*   spindle_calibrate_copy        a plain copy of `bytes` from src to dst (device buffers, 16-byte
@@ -411,7 +417,7 @@ spindle_status spindle_calibrate_mfma(int32_t iters, int32_t pattern, void *stre
  *                                 traffic counters of a profiler run are scaled by. */
 spindle_status spindle_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream, double *gbs);
 spindle_status spindle_calibrate_similarity(const spindle_kv_desc *desc, int32_t n_tensors, void *workspace,
-                                            size_t workspace_bytes, void *stream, double *ms);
+                                            size_t workspace_bytes, int32_t mode, void *stream, double *ms);
 
 /* ------------------------------------------------------------------------- */
 

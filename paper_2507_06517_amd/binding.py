@@ -69,7 +69,7 @@ def lib():
         L.spindle_compress_shallow_layer.argtypes = [C.POINTER(KvDesc), vp, vp, f32, f32, i32] + [vp] * 10 + [vp, sz, vp]
         L.spindle_calibrate_mfma.argtypes = [i32, i32, vp, C.POINTER(C.c_double)]
         L.spindle_calibrate_copy.argtypes = [vp, vp, sz, vp, C.POINTER(C.c_double)]
-        L.spindle_calibrate_similarity.argtypes = [C.POINTER(KvDesc), i32, vp, sz, vp, C.POINTER(C.c_double)]
+        L.spindle_calibrate_similarity.argtypes = [C.POINTER(KvDesc), i32, vp, sz, i32, vp, C.POINTER(C.c_double)]
         L.spindle_reconstruct.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.spindle_profile.argtypes = [i32]
         L.spindle_profile_read.argtypes = [C.c_char_p, C.POINTER(C.c_float), i32]
@@ -517,13 +517,14 @@ def spindle_calibrate_copy(src, dst, stream=None) -> float:
     return out.value
 
 
-def spindle_calibrate_similarity(plan: "ShallowPlan", stream=None) -> float:
+def spindle_calibrate_similarity(plan: "ShallowPlan", mode: int = 0, stream=None) -> float:
     """Milliseconds of the similarity kernel's loop without its packing, on the unit vectors the
-    plan's last run left in its workspace (measurement aid)."""
+    plan's last run left in its workspace (measurement aid); mode 1 also without the streaming
+    loads, mode 2 matrix instructions only."""
     out = C.c_double(0.0)
     n_t = sum(1 for k in plan.out if k.startswith("ref_"))
     _check(lib().spindle_calibrate_similarity(C.byref(plan.desc), n_t, _ptr(plan.ws), int(plan.ws_bytes),
-                                              stream or _stream(), C.byref(out)))
+                                              int(mode), stream or _stream(), C.byref(out)))
     return out.value
 
 

@@ -178,7 +178,7 @@ constexpr int kCandCap = 8;
 // Each enqueues its kernels on `st` in order and returns SPINDLE_OK or the failed HIP call.
 // force: the caller wants the adjacency matrix, so the full bitmap is completed as well.
 spindle_status launch_graph(const ShallowParams &p, hipStream_t st, int force);
-spindle_status launch_bare_similarity(const ShallowParams &p, hipStream_t st);   // measurement aid
+spindle_status launch_bare_similarity(const ShallowParams &p, hipStream_t st, int mode);   // measurement aid
 spindle_status launch_merge(const ShallowParams &p, hipStream_t st);
 spindle_status launch_codebook(const ShallowParams &p, hipStream_t st);
 

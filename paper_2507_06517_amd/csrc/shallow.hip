@@ -282,11 +282,11 @@ extern "C" spindle_status spindle_compress_shallow_layer(
 
 // ---------------------------------------------------------------- measurement aid
 extern "C" spindle_status spindle_calibrate_similarity(const spindle_kv_desc *desc, int32_t n_tensors, void *workspace,
-                                                       size_t workspace_bytes, void *stream, double *ms_out) {
+                                                       size_t workspace_bytes, int32_t mode, void *stream, double *ms_out) {
   size_t need = 0;
   spindle_status s = spindle_shallow_workspace_bytes(desc, n_tensors, &need);
   if (s != SPINDLE_OK) return s;
-  if (!ms_out) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "ms is NULL");
+  if (!ms_out || mode < 0 || mode > 2) SPINDLE_FAIL(SPINDLE_ERR_INVALID_ARG, "ms is NULL or mode is not 0, 1 or 2");
   if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255))
     SPINDLE_FAIL(SPINDLE_ERR_WORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -300,7 +300,7 @@ extern "C" spindle_status spindle_calibrate_similarity(const spindle_kv_desc *de
   SPINDLE_HIP(hipEventCreate(&e0));
   SPINDLE_HIP(hipEventCreate(&e1));
   SPINDLE_HIP(hipEventRecord(e0, st));
-  s = launch_bare_similarity(p, st);
+  s = launch_bare_similarity(p, st, mode);
   if (s == SPINDLE_OK) {
     SPINDLE_HIP(hipEventRecord(e1, st));
     SPINDLE_HIP(hipEventSynchronize(e1));

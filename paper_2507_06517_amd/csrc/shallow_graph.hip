@@ -146,10 +146,14 @@ __device__ __forceinline__ float min3_abs(float m, float a, float b, uint32_t af
 //                   (a record segment, a pair list or a neighbour list ran full): writes every
 //                   word of G with the close pairs decided in place in double precision; no
 //                   records, no queue (degrees and lists then come from the bitmap)
-//   <false, false, true>  measurement aid: the same staging, barriers and matrix instructions with
-//                   the packing of the results left out and nothing written (what the loop
-//                   sustains on this GPU without its vector work)
-template <bool kStore, bool kExact, bool kBare = false>
+//   <false, false, m>  measurement aids, nothing written: m = 1 the same staging, barriers, fragment
+//                   reads and matrix instructions with the packing of the results left out (what
+//                   the loop sustains on this GPU without its vector work); m = 2 also without
+//                   the loads of a chunk's stages after the first two (the matrix instructions
+//                   keep reading the same staged tokens); m = 3 matrix instructions only, both
+//                   operands from registers (no loads to LDS after the first two stages, no
+//                   fragment reads)
+template <bool kStore, bool kExact, int kBare = 0>
 __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p) {
   typedef Mma<SPINDLE_F16> M;
   // two stages of 64 tokens, filled by direct global->LDS loads.  Row r keeps its 16-byte piece
@@ -242,12 +246,18 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   // of stage x >> 1.  Each wave fills 16 rows of a stage with four 1-KiB loads (4 rows x 16
   // pieces, lane = slot).  Rows past the end of the sequence exist (the array is padded) and
   // are never used: their bits are masked and their pairs rejected.
-  auto dma = [&](int b0, int bufsel) {
+  auto dma = [&](int b0, int bufsel, bool later_stage = false) {
+    if (kBare >= 2 && later_stage) return;
     const char *sbase = Xh + (size_t)b0 * 256;
 #pragma unroll
     for (int q = 0; q < 4; ++q) lds_dma16(sbase + voff[q], stage_lds + bufsel * kStageBytes + (wave * 4 + q) * 1024);
   };
   auto frag_at = [&](int bufsel, int ct, int ks) -> M::frag {
+    if (kBare == 3) {                                 // a register operand the compiler cannot see through
+      M::frag f = af[(bufsel + ct) & 1][ks];
+      asm volatile("" : "+v"(f));
+      return f;
+    }
     return *reinterpret_cast<const M::frag *>(stage + bufsel * kStageBytes + ct * 32 * 256 + soff[ks]);
   };
   // One pipeline step: the matrix cores compute the similarities of the NEXT tile x (32
@@ -299,7 +309,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     if (sync_fetch) {
       __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): own loads landed, own reads done
       __builtin_amdgcn_s_barrier();
-      dma(fetch_b0, bufx);
+      dma(fetch_b0, bufx, true);
     }
     __builtin_amdgcn_sched_barrier(0);
     SPINDLE_SLOT(r0 = M::mma(f4, af[0][4], r0), 32);
@@ -892,10 +902,13 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
 
 }  // namespace
 
-spindle_status launch_bare_similarity(const ShallowParams &p, hipStream_t st) {
+spindle_status launch_bare_similarity(const ShallowParams &p, hipStream_t st, int mode) {
   const int nI = (p.n + kPanelRows - 1) / kPanelRows;
   const int nJ = (p.n + kChunkCols * kItemChunks - 1) / (kChunkCols * kItemChunks);
-  hipLaunchKernelGGL((shallow_gram<false, false, true>), dim3(8 * nI * ((p.UT * nJ + 7) / 8)), dim3(kGramThreads), 0, st, p);
+  const dim3 grid(8 * nI * ((p.UT * nJ + 7) / 8));
+  if (mode == 0) hipLaunchKernelGGL((shallow_gram<false, false, 1>), grid, dim3(kGramThreads), 0, st, p);
+  else if (mode == 1) hipLaunchKernelGGL((shallow_gram<false, false, 2>), grid, dim3(kGramThreads), 0, st, p);
+  else hipLaunchKernelGGL((shallow_gram<false, false, 3>), grid, dim3(kGramThreads), 0, st, p);
   SPINDLE_HIP(hipGetLastError());
   return SPINDLE_OK;
 }

@@ -241,6 +241,8 @@ def test_measurement_aids_run_and_leave_results_alone():
     plan = sb.plan_shallow(K, L.dtype, L.theta_k, L.theta_v, L.max_codes)
     a = {k: v.clone() for k, v in plan.run(K, V).items()}
     ms = sb.spindle_calibrate_similarity(plan)
+    for mode in (1, 2):
+        assert 0.0 < sb.spindle_calibrate_similarity(plan, mode) < 50.0
     tf = sb.spindle_calibrate_mfma(512)
     tf_data = sb.spindle_calibrate_mfma(512, 1)
     assert 0.0 < ms < 50.0 and 50.0 < tf < 2600.0 and 50.0 < tf_data < 2600.0, (ms, tf, tf_data)
