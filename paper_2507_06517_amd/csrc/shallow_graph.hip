@@ -280,19 +280,32 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     // into sg0, of a1[v] into sg1, guard band) run in slots 0-11, results of the row block that
     // finished first (a0) first; the word is assembled in slots 12-15.
     uint32_t sg0 = 0, sg1 = 0;
-    float mn = INFINITY;
+    // four chains for the guard band, taken in turn: the compiler puts a wait state between two
+    // inline-assembly instructions that depend on each other unless two others lie between them,
+    // and with one chain that is an s_nop after every one of them
+    float mnA = INFINITY, mnB = INFINITY, mnC = INFINITY, mnD = INFINITY;
 #define SPINDLE_PACK(k)                                                                              \
   do {                                                                                               \
     constexpr int v_ = 15 - (k) % 16;                                                                \
     if (kBare) break;                                                                                \
     if ((k) < 16) sg0 = __builtin_amdgcn_alignbit(sg0, __float_as_uint(a0[v_]), 31);                 \
     else if ((k) < 32) sg1 = __builtin_amdgcn_alignbit(sg1, __float_as_uint(a1[v_]), 31);            \
-    else mn = min3_abs(mn, a0[v_], a1[v_], sg0, sg1);                                                \
+    else if (((k) & 3) == 0) mnA = min3_abs(mnA, a0[v_], a1[v_], sg0, sg1);                          \
+    else if (((k) & 3) == 1) mnB = min3_abs(mnB, a0[v_], a1[v_], sg0, sg1);                          \
+    else if (((k) & 3) == 2) mnC = min3_abs(mnC, a0[v_], a1[v_], sg0, sg1);                          \
+    else mnD = min3_abs(mnD, a0[v_], a1[v_], sg0, sg1);                                              \
   } while (0)
+  // (the empty volatile statement keeps the slot's packing instructions in the slot: they have no
+  // side effects, and without it instruction selection is free to emit them all behind the
+  // matrix instructions of several slots)
 #define SPINDLE_SLOT(mfma, k)                                                                        \
   do {                                                                                               \
     mfma;                                                                                            \
     SPINDLE_PACK(k); SPINDLE_PACK((k) + 1); SPINDLE_PACK((k) + 2); SPINDLE_PACK((k) + 3);            \
+    if (!kBare) {                                                                                    \
+      if ((k) < 16) asm volatile("" : "+v"(sg0));                                                    \
+      else if ((k) < 32) asm volatile("" : "+v"(sg1));                                               \
+    }                                                                                                \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
     M::frag f2 = frag_at(bufx, ctx, 2), f3 = frag_at(bufx, ctx, 3);
@@ -332,7 +345,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     // pairs too close to theta for fp16: clear their bits now, queue them for the exact
     // decision.  Bit 16*cb + v of `rest` = close.
     uint32_t rest = 0;
-    const bool any_close = __any(mn < band);
+    const bool any_close = __any(fminf(fminf(mnA, mnB), fminf(mnC, mnD)) < band);
     __builtin_amdgcn_sched_barrier(0);
     r1 = M::mma(f6, af[1][6], r1);
     if (any_close) {
