@@ -123,6 +123,20 @@ __device__ __forceinline__ void lds_dma16(const void *src, uint32_t lds_addr) {
                : "memory", "m0");
 }
 
+// The same load with the address split into a base that is the same for the whole wave (scalar
+// registers) and a 32-bit byte offset per lane: no vector instruction is spent on the address.
+__device__ __forceinline__ void lds_dma16_at(const void *wave_base, uint32_t lane_offset, uint32_t lds_addr) {
+  const uint64_t b = reinterpret_cast<uint64_t>(wave_base);
+  // (readfirstlane returns a signed int: widen it as unsigned, or a low half with its top bit set
+  // would fill the high half with ones)
+  const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
+                      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_offset), "s"(sb)
+               : "memory", "m0");
+}
+
 // Spread the four nibbles of a 16-bit value to bits [8k, 8k+4) of a 32-bit word.
 __device__ __forceinline__ uint32_t spread_nibbles(uint32_t p) {
   return (p & 0xFu) | ((p & 0xF0u) << 4) | ((p & 0xF00u) << 8) | ((p & 0xF000u) << 12);

@@ -55,6 +55,23 @@ struct Geo {
       lds_dma16(Kunit + (size_t)key * pitch + piece * 16, lds + q * 1024);
     }
   }
+  // The same for a stage that lies inside the sequence, with this lane's byte offsets within a
+  // stage worked out once (`offsets`): a load is then its address registers and nothing else.
+  static __device__ __forceinline__ void offsets(size_t pitch, int wave, int lane, uint32_t (&off)[kLoadsPerWave]) {
+#pragma unroll
+    for (int j = 0; j < kLoadsPerWave; ++j) {
+      const int q = wave * kLoadsPerWave + j;
+      const int r = q * kRowsPerLoad + lane / kPieces;
+      const int piece = (lane % kPieces) ^ (r & (kPieces - 1));
+      off[j] = (uint32_t)((size_t)r * pitch + (size_t)piece * 16);
+    }
+  }
+  static __device__ __forceinline__ void load_inside(const char *Kunit, size_t pitch, int key0, uint32_t lds, int wave,
+                                                     const uint32_t (&off)[kLoadsPerWave]) {
+    const char *base = Kunit + (size_t)key0 * pitch;
+#pragma unroll
+    for (int j = 0; j < kLoadsPerWave; ++j) lds_dma16_at(base, off[j], lds + (wave * kLoadsPerWave + j) * 1024);
+  }
   // MFMA operand fragment ks of staged key `row` for lane group g
   static __device__ __forceinline__ typename M::frag frag(const char *buf, int row, int ks, int g) {
     if constexpr (DT == SPINDLE_F32) {
@@ -118,7 +135,7 @@ __global__ __launch_bounds__(Geo<DT>::kThreads) void deep_stats(DeepParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int u = blockIdx.y, chunk = blockIdx.x;
-  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int g = lane >> 5, c = lane & 31;
   const int wr = wave % WR, wk = wave / WR;
   if (chunk == 0) {                                    // counters of this unit's selection
@@ -133,7 +150,14 @@ __global__ __launch_bounds__(Geo<DT>::kThreads) void deep_stats(DeepParams p) {
   const char *Qunit = p.Q + (size_t)u * p.R * M::kRowBytes;
   const uint32_t lds0 = lds_address(smem);
 
-  S::load(Kunit, kpitch, key_begin, p.l, lds0, wave, lane);
+  uint32_t koff[S::kLoadsPerWave];
+  S::offsets(kpitch, wave, lane, koff);
+  const bool narrow = kpitch * S::kStageKeys <= 0xFFFFFFFFull;   // lane offsets within a stage fit 32 bits
+  auto stage_load = [&](int key0, uint32_t lds) {
+    if (narrow && key0 + S::kStageKeys <= p.l) S::load_inside(Kunit, kpitch, key0, lds, wave, koff);
+    else S::load(Kunit, kpitch, key0, p.l, lds, wave, lane);
+  };
+  stage_load(key_begin, lds0);
 
   // query fragments stay in registers for the whole block
   typename M::frag qf[2][M::kSteps];
@@ -152,7 +176,7 @@ __global__ __launch_bounds__(Geo<DT>::kThreads) void deep_stats(DeepParams p) {
 
   for (int s = 0; s < nst; ++s) {
     const int k0 = key_begin + s * S::kStageKeys;
-    if (s + 1 < nst) S::load(Kunit, kpitch, k0 + S::kStageKeys, p.l, lds0 + ((s + 1) & 1) * S::kStageBytes, wave, lane);
+    if (s + 1 < nst) stage_load(k0 + S::kStageKeys, lds0 + ((s + 1) & 1) * S::kStageBytes);
     const char *buf = smem + (s & 1) * S::kStageBytes;
     const bool tail = k0 + S::kStageKeys > p.lc;       // causal mask / end of the sequence
     // The fragments of a tile are fetched from LDS together, those of the wave's next tile right
@@ -273,7 +297,7 @@ __global__ __launch_bounds__(Geo<DT>::kThreads) void deep_accumulate(DeepParams 
   float *row_const = colpart + 2 * WR * S::kStageKeys;                          // [256]
 
   const int u = blockIdx.y, chunk = blockIdx.x;
-  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int g = lane >> 5, c = lane & 31;
   const int wr = wave % WR, wk = wave / WR;
   const int key_begin = chunk * p.stages * S::kStageKeys;
@@ -284,7 +308,14 @@ __global__ __launch_bounds__(Geo<DT>::kThreads) void deep_accumulate(DeepParams 
   const char *Qunit = p.Q + (size_t)u * p.R * M::kRowBytes;
   const uint32_t lds0 = lds_address(smem);
 
-  S::load(Kunit, kpitch, key_begin, p.l, lds0, wave, lane);
+  uint32_t koff[S::kLoadsPerWave];
+  S::offsets(kpitch, wave, lane, koff);
+  const bool narrow = kpitch * S::kStageKeys <= 0xFFFFFFFFull;   // lane offsets within a stage fit 32 bits
+  auto stage_load = [&](int key0, uint32_t lds) {
+    if (narrow && key0 + S::kStageKeys <= p.l) S::load_inside(Kunit, kpitch, key0, lds, wave, koff);
+    else S::load(Kunit, kpitch, key0, p.l, lds, wave, lane);
+  };
+  stage_load(key_begin, lds0);
 
   // max + log2(sum) of every query row from the per-chunk statistics of the first pass, merged
   // in chunk order by one thread per row (every block of the unit does the same sum in the same
@@ -321,7 +352,7 @@ __global__ __launch_bounds__(Geo<DT>::kThreads) void deep_accumulate(DeepParams 
 
   for (int s = 0; s < nst; ++s) {
     const int k0 = key_begin + s * S::kStageKeys;
-    if (s + 1 < nst) S::load(Kunit, kpitch, k0 + S::kStageKeys, p.l, lds0 + ((s + 1) & 1) * S::kStageBytes, wave, lane);
+    if (s + 1 < nst) stage_load(k0 + S::kStageKeys, lds0 + ((s + 1) & 1) * S::kStageBytes);
     const char *buf = smem + (s & 1) * S::kStageBytes;
     float *cp = colpart + (s & 1) * (WR * S::kStageKeys);
     typename M::frag kf[kPrefetch ? M::kSteps : 1];    // as in deep_stats

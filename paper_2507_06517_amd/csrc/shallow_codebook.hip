@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kAssignThreads, 2) void shallow_assign(ShallowParam
   if (slot0 >= nov) return;
   const int kept = p.n_codes[ut / p.U][ut % p.U];     // = cap whenever tokens were cut
   if (kept <= 0) return;
-  const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5, c = lane & 31;
   const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
   const uint32_t *ovf = p.ovf + (size_t)ut * n;
   const int *rank_vert = p.rank_vert + (size_t)ut * n;
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kAssignThreads, 2) void shallow_assign(ShallowParam
   auto dma = [&](int bufsel) {
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      lds_dma16(Xh + (size_t)tokq[q] * 256 + spiece[q], stage_lds + bufsel * kStageBytes + (wave * 4 + q) * 1024);
+      lds_dma16_at(Xh, (uint32_t)tokq[q] * 256u + spiece[q], stage_lds + bufsel * kStageBytes + (wave * 4 + q) * 1024);
   };
   float runmax[2] = {-INFINITY, -INFINITY};
   int cnt[2] = {0, 0};

@@ -189,7 +189,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   const int Jfirst = (I * kPanelRows) / kChunkCols;
   if ((Jg + 1) * kItemChunks <= Jfirst) continue;
   const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
-  const int lane = lane_id(), wave = threadIdx.x >> 6, g = lane >> 5, c = lane & 31;
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5, c = lane & 31;
   const char *Xh = reinterpret_cast<const char *>(p.Xh) + (size_t)ut * n * 256;
   const int arow0 = I * kPanelRows + 64 * wave;   // first of this wave's 64 rows of G
   uint32_t *buf = pairbuf[wave];
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
     if (kBare >= 2 && later_stage) return;
     const char *sbase = Xh + (size_t)b0 * 256;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) lds_dma16(sbase + voff[q], stage_lds + bufsel * kStageBytes + (wave * 4 + q) * 1024);
+    for (int q = 0; q < 4; ++q) lds_dma16_at(sbase, voff[q], stage_lds + bufsel * kStageBytes + (wave * 4 + q) * 1024);
   };
   auto frag_at = [&](int bufsel, int ct, int ks) -> M::frag {
     if (kBare == 3) {                                 // a register operand the compiler cannot see through
