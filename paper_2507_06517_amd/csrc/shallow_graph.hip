@@ -185,7 +185,8 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   // should see all of them)
   const int ut = pj / nJ, Jg = (pj % nJ + ut) % nJ;
   // G is symmetric: a row panel only computes the chunks from the one holding its own
-  // tokens onwards; shallow_mirror fills the columns to the left from the transposed blocks
+  // tokens onwards (and, when G is not written, of that chunk only the tokens from its own first
+  // row on); shallow_mirror fills the columns to the left from the transposed blocks
   const int Jfirst = (I * kPanelRows) / kChunkCols;
   if ((Jg + 1) * kItemChunks <= Jfirst) continue;
   const float theta_s = p.theta[ut / p.U] * kUnitScale * kUnitScale;
@@ -234,8 +235,13 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   bool carried = false;                            // pipeline state of the chunk to come already in place
   f16v cur0, cur1, nxt0, nxt1;
   for (int J = Jg * kItemChunks > Jfirst ? Jg * kItemChunks : Jfirst; J < (Jg + 1) * kItemChunks && J * kChunkCols < n; ++J) {
-  const int col_begin = J * kChunkCols;
-  const int col_end = col_begin + kChunkCols < n ? col_begin + kChunkCols : n;
+  // In the chunk that holds the panel's own rows, the tokens in front of the panel belong to
+  // earlier panels, which have these pairs in their own rows: when G is not written the panel
+  // starts at its own first row (a multiple of 256 tokens: whole stages and whole pieces).
+  const int chunk_base = J * kChunkCols;
+  const int col_begin = !kStore && chunk_base < I * kPanelRows ? I * kPanelRows : chunk_base;
+  const int piece0 = (col_begin - chunk_base) >> 7;   // first 16-byte piece of a row's line this chunk fills
+  const int col_end = chunk_base + kChunkCols < n ? chunk_base + kChunkCols : n;
   const int ntiles = (col_end - col_begin + 31) / 32;
   // guard band of this lane's two rows against the tokens of the chunk (scaled units)
   const float ech = __uint_as_float(p.echunk[(size_t)ut * ((n + kChunkCols - 1) / kChunkCols) + J]);
@@ -450,7 +456,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
       if (kStore) v = *reinterpret_cast<const u4 *>(&wstage[kStore ? wave : 0][kStore ? key >> 3 : 0][(key & 7u) * 4]);
       else v = wordvals[kStore ? 0 : wave][kStore ? 0 : (e < nw ? e : 0)];
       if (e >= nw) v = u4{0, 0, 0, 0};
-      const uint32_t rec0 = ((uint32_t)(arow0 + (int)(key >> 3)) << 16) | (uint32_t)(col_begin + (int)(key & 7u) * 128);
+      const uint32_t rec0 = ((uint32_t)(arow0 + (int)(key >> 3)) << 16) | (uint32_t)(chunk_base + (int)(key & 7u) * 128);
       for (;;) {
         const bool has = (v[0] | v[1] | v[2] | v[3]) != 0;
         const unsigned long long mk = __ballot(has);
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
         if (nw + add > kWordList) expand();
         if (nz) {
           const int at = nw + __popcll(mk & below);
-          wl[at] = (uint32_t)(lane << 3 | (t0 >> 2));
+          wl[at] = (uint32_t)(lane << 3 | (piece0 + (t0 >> 2)));
           wordvals[kStore ? 0 : wave][kStore ? 0 : at] = words;
         }
         nw += add;
@@ -535,7 +541,7 @@ __global__ __launch_bounds__(kGramThreads, 2) void shallow_gram(ShallowParams p)
   // first 32 of them (the pipeline always runs one tile and two stages ahead): when the next
   // chunk of the item follows, its first tile, the fragments of its second and both stage
   // buffers are already in place.
-  carried = col_end - col_begin == kChunkCols;
+  carried = col_end - chunk_base == kChunkCols;
   }
   if (nbuf) { flush_pairs(p, ut, buf, nbuf); nbuf = 0; }
   }
@@ -686,15 +692,15 @@ __global__ __launch_bounds__(256) void shallow_fixup(ShallowParams p, int store_
     const bool adj = cos64(p, ut, a, b) > theta;
     if (adj && store_bits) atomicOr(p.G + ((size_t)ut * p.n + b) * p.Wp + (a >> 5), 1u << (a & 31));
     // ... and as a record for the neighbour lists, filed under the panel of the row; a pair of
-    // two different 1024-token tiles was only evaluated in this orientation, so it also
-    // extends the list of its column
+    // two different row panels was only evaluated in this orientation, so it also extends the
+    // list of its column
     // (consecutive pairs of the list mostly share their panels, and same-address atomics are
     // served one at a time: one counter update per wave and panel)
     const int nI = (p.n + kPanelRows - 1) / kPanelRows, lane = lane_id();
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
       const int end = k == 0 ? b / kPanelRows : a / kPanelRows;
-      const bool want = adj && (k == 0 || (a >> 10) != (b >> 10));
+      const bool want = adj && (k == 0 || a / kPanelRows != b / kPanelRows);
       unsigned long long todo = __ballot(want);
       while (todo) {                                   // wave-uniform
         const int leader = __builtin_ctzll(todo);
@@ -783,16 +789,16 @@ __global__ __launch_bounds__(256) void shallow_lists(ShallowParams p, int force)
 // shallow_gram and shallow_fixup left, without reading G.  One block per panel of 256 rows;
 // the first 128 entries of every list are collected in LDS and written out in whole pieces.
 // A record (a, b) of the panel's own segments puts b on the list of a.  G is symmetric and
-// only computed from each row's own 1024-token tile on, so a record (a', b) of an earlier
-// panel with b in a later tile also puts a' on the list of b: the block scans the segments
-// of all earlier tiles' panels for its own chunk and keeps the records that end in its rows
-// (inside a tile both orientations were computed and recorded).  Fill counts live in LDS;
+// a panel only computes the tokens from its own first row on, so a record (a', b) of an earlier
+// panel with b in a later panel also puts a' on the list of b: the block scans the segments
+// of all earlier panels for its own chunk and keeps the records that end in its rows
+// (inside a panel both orientations were computed and recorded).  Fill counts live in LDS;
 // the order of a list is whatever the LDS atomics make it, which no consumer depends on.
 // A row with more than kListCap neighbours, or a segment that ran full, raises need_full:
 // shallow_mirror and shallow_lists then redo everything from the bitmap.
 constexpr int kEdgeThreads = 1024;
 constexpr int kEdgeLds = 128;                      // list entries per row collected in LDS; later ones go straight to memory
-constexpr int kSegList = 1280;                     // segments a panel may have to visit at 65535 tokens: 4 x 64 + 16 x 63
+constexpr int kSegList = 1280;                     // segments a panel may have to visit at 65535 tokens: 4 x 64 + 4 x 255
 
 // kCap: the segment capacity when it is the smallest one (long sequences), else 0 = read it from
 // the parameters; with the constant the compiler unrolls the record loop and batches its loads
@@ -820,7 +826,7 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
     else if (pos < kListCap) lists[(size_t)r * kListCap + list_slot(pos)] = (uint16_t)other;
   };
   const int nown = 4 * (nJc - Jm);                   // (chunk, wave) segments of this panel
-  const int nin = 16 * Jm;                           // (panel, wave) segments of earlier tiles for this tile's chunk
+  const int nin = 4 * I;                             // (panel, wave) segments of all earlier panels for this panel's chunk
   auto seg_of = [&](int k) -> size_t {
     const bool own = k < nown;
     const int kk = own ? k : k - nown;
@@ -886,7 +892,7 @@ __global__ __launch_bounds__(kEdgeThreads) void shallow_edge_lists(ShallowParams
       const uint32_t rec = fe[i];
       const int a = (int)(rec >> 16), b = (int)(rec & 0xFFFFu);
       if (a >= row0 && a < row0 + kPanelRows) add(a, b);
-      if ((a >> 10) != (b >> 10) && b >= row0 && b < row0 + kPanelRows) add(b, a);   // other tile: evaluated once
+      if (a / kPanelRows != b / kPanelRows && b >= row0 && b < row0 + kPanelRows) add(b, a);   // other panel: evaluated once
     }
   }
   __syncthreads();
