@@ -33,6 +33,16 @@ def test_without_adjacency_export(oracle, l, n_centroids):
     parity.check_shallow_layer(oracle, L, debug=False)
 
 
+@pytest.mark.parametrize("l", [255, 256, 257, 511, 513, 769, 1023, 1024, 1025, 1281, 2049])
+def test_panel_boundaries_without_adjacency_export(oracle, l):
+    # the similarity kernel starts a 256-row panel's own 1024-token chunk at the panel's first row
+    # and records a pair of two panels once, from the earlier one: lengths around the panel and
+    # chunk boundaries, graphs sparse enough for the lists to come from the records
+    L = wl.small_random(31, "f16", B=1, H=2, l=l, lw=1, cap=l, n_centroids=max(4, l // 24), noise_frac=0.2,
+                        drift_sigma=0.002)
+    parity.check_shallow_layer(oracle, L, debug=False)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_graph_sweep(oracle, seed):
     # graphs of many shapes (sparse to nearly complete, with and without drift and isolated
